@@ -1,0 +1,532 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+None of these tests touches the GPU library.  Each pin compares the oracle with
+something other than itself: published known-answer vectors, closed forms,
+library routines (numpy, scipy, torch autograd, scikit-learn), statistical
+invariants of Bernoulli draws, or brute force on tiny inputs.
+"""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.sparse as sp
+import scipy.stats as st
+import torch
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+# ---------------------------------------------------------------------------
+# Philox and the uniform of Algorithm 1
+
+
+def test_philox_known_answers(ref):
+    rows = [l for l in open(os.path.join(GOLDEN, "philox4x32_10_kat.txt")) if not l.startswith("#")]
+    assert len(rows) == 3
+    for line in rows:
+        lhs, rhs = line.split("|")
+        v = [int(t, 16) for t in lhs.split()]
+        want = [int(t, 16) for t in rhs.split()]
+        got = ref.philox4x32_10(v[:4], v[4:6])
+        assert [int(g) for g in got] == want
+
+
+def test_uniform_counter_layout(ref):
+    # counter = (j, 0, lo(step), hi(step)); key = (lo(seed), hi(seed)); top 24 bits of word 0
+    for seed, step, j in [(42, 7, 5), (0xDEADBEEF12345678, 0x1_0000_0003, 123456), (0, 0, 0)]:
+        out = ref.philox4x32_10([j, 0, step & 0xFFFFFFFF, step >> 32],
+                                [seed & 0xFFFFFFFF, seed >> 32])
+        assert ref.uniform(seed, step, j) == float(int(out[0]) >> 8) * 2.0 ** -24
+    # value computed with an independent implementation when the counter layout was chosen
+    out = ref.philox4x32_10([5, 0, 7, 0], [42, 0])
+    assert int(out[0]) == 0x0D09DEB5
+    assert ref.uniform(42, 7, 5) == pytest.approx(0.05093181133270264, abs=0)
+
+
+def test_uniform_distribution(ref):
+    u = ref.uniforms(1234, 9, 100_000).astype(np.float64)
+    assert u.min() >= 0.0 and u.max() < 1.0
+    assert np.all(u * 2 ** 24 == np.round(u * 2 ** 24))  # on the 2^-24 grid
+    assert abs(u.mean() - 0.5) < 5 / math.sqrt(12 * u.size)
+    assert st.kstest(u, "uniform").pvalue > 1e-3
+    # different steps and seeds give different streams
+    assert not np.array_equal(u[:100], ref.uniforms(1234, 10, 100))
+    assert not np.array_equal(u[:100], ref.uniforms(1235, 9, 100))
+
+
+# ---------------------------------------------------------------------------
+# Assistant score
+
+
+def test_score_selects_coordinate_and_bias(ref):
+    X = rng(0).standard_normal((50, 7)).astype(np.float32)
+    F = ref.Features.dense(X)
+    for k in range(7):
+        phi = np.zeros(7, np.float32)
+        phi[k] = 1.0
+        logit, prob = ref.assistant_score(F, None, 50, phi)
+        assert np.array_equal(logit, X[:, k])
+    logit, prob = ref.assistant_score(F, None, 50, np.zeros(7, np.float32), bias=0.75)
+    assert np.all(logit == 0.75)
+    assert np.allclose(prob, 1 / (1 + math.exp(-0.75)), rtol=1e-7)
+
+
+def test_score_matches_torch_float64(ref):
+    r = rng(1)
+    X = r.standard_normal((300, 129)).astype(np.float32)
+    phi = r.standard_normal(129).astype(np.float32)
+    idx = r.permutation(300)[:200].astype(np.int32)
+    logit, prob = ref.assistant_score(ref.Features.dense(X), idx, 200, phi, bias=-0.3)
+    s = torch.from_numpy(X[idx]).double() @ torch.from_numpy(phi).double() - torch.tensor(
+        np.float32(-0.3)).double().neg()
+    assert np.array_equal(logit, s.float().numpy())
+    assert np.allclose(prob, torch.sigmoid(s.float().double()).numpy(), rtol=1e-7, atol=0)
+
+
+def test_score_padded_rows_and_csr_equal_dense(ref):
+    r = rng(2)
+    X = r.standard_normal((40, 12)).astype(np.float32)
+    X[r.random((40, 12)) < 0.6] = 0.0
+    phi = r.standard_normal(12).astype(np.float32)
+    want = ref.assistant_score(ref.Features.dense(X), None, 40, phi, bias=0.1)
+    Xp = np.concatenate([X, np.full((40, 4), 99.0, np.float32)], axis=1)
+    got = ref.assistant_score(ref.Features.dense(Xp, d=12), None, 40, phi, bias=0.1)
+    assert np.array_equal(want[0], got[0]) and np.array_equal(want[1], got[1])
+    S = sp.csr_matrix(X)
+    Fc = ref.Features.csr(S.indptr, S.indices, S.data, 12)
+    got = ref.assistant_score(Fc, None, 40, phi, bias=0.1)
+    assert np.array_equal(want[0], got[0]) and np.array_equal(want[1], got[1])
+    # val == NULL means all ones
+    Fo = ref.Features.csr(S.indptr, S.indices, None, 12)
+    got1 = ref.assistant_score(Fo, None, 40, phi)
+    ones = (X != 0).astype(np.float64) @ phi.astype(np.float64)
+    assert np.array_equal(got1[0], ones.astype(np.float32))
+
+
+# ---------------------------------------------------------------------------
+# Keep draw and compaction (Algorithm 1)
+
+
+def test_keep_certain_and_impossible(ref):
+    P = 4096
+    keep, pos = ref.shrink(np.ones(P, np.float32), 0.0, 3, 4)
+    assert keep.all() and np.array_equal(pos, np.arange(P))
+    keep, pos = ref.shrink(np.zeros(P, np.float32), 0.0, 3, 4)
+    assert not keep.any() and pos.size == 0
+    keep, pos = ref.shrink(rng(0).random(P).astype(np.float32), 1.0, 3, 4)  # gamma = 1
+    assert keep.all() and np.array_equal(pos, np.arange(P))
+
+
+@pytest.mark.parametrize("gamma", [0.0, 0.1, 0.5])
+def test_keep_probability_is_gamma_plus_one_minus_gamma_g(ref, gamma):
+    P = 50_000
+    g = rng(5).random(P).astype(np.float32)
+    keep, pos = ref.shrink(g, gamma, 77, 3)
+    # definition, from the oracle's own uniforms only (not its compare)
+    u = ref.uniforms(77, 3, P).astype(np.float64)
+    p = gamma + (1 - gamma) * g.astype(np.float64)
+    clear = np.abs(u - p) > 1e-6
+    assert np.array_equal(keep[clear].astype(bool), (u < p)[clear])
+    # kept count tracks sum p
+    sigma = math.sqrt(float(np.sum(p * (1 - p))))
+    assert abs(int(keep.sum()) - p.sum()) < 5 * sigma
+    # compaction is numpy's flatnonzero
+    assert np.array_equal(pos, np.flatnonzero(keep))
+
+
+def test_kept_count_chi_square_over_steps(ref):
+    P, T = 2000, 60
+    g = rng(6).random(P).astype(np.float32)
+    p = 0.1 + 0.9 * g.astype(np.float64)
+    var = float(np.sum(p * (1 - p)))
+    chi = 0.0
+    for t in range(T):
+        keep, _ = ref.shrink(g, 0.1, 99, t)
+        chi += (keep.sum() - p.sum()) ** 2 / var
+    assert st.chi2.sf(chi, T) > 1e-4 and st.chi2.cdf(chi, T) > 1e-4
+
+
+@pytest.mark.parametrize("gamma", [0.0, 0.1, 0.5, 1.0])
+def test_literal_two_branch_sampler_is_a_prefix_of_the_pool_compaction(ref, gamma):
+    P = 3000
+    g = rng(7).random(P).astype(np.float32)
+    keep, pos = ref.shrink(g, gamma, 11, 2)
+    u = ref.uniforms(11, 2, P).astype(np.float64)
+    p = gamma + (1 - gamma) * g.astype(np.float64)
+    assert np.all(np.abs(u - p) > 1e-6), "pick another seed: a draw sits in the rounding band"
+    for batch_size in [0, 1, 64, pos.size, pos.size + 10]:
+        B, consumed = ref.sample_batch(g, gamma, 11, 2, batch_size)
+        want = pos[:batch_size]
+        assert np.array_equal(B, want)
+        if batch_size and batch_size <= pos.size:
+            assert consumed == want[-1] + 1  # stopped right after the last kept candidate
+        elif batch_size > pos.size:
+            assert consumed == P
+
+
+def test_threshold_shrink(ref):
+    crit = rng(8).standard_normal(1000).astype(np.float32)
+    crit[10] = 0.25
+    keep, pos = ref.shrink_threshold(crit, 0.25)
+    assert np.array_equal(keep.astype(bool), crit > np.float32(0.25)) and not keep[10]
+    assert np.array_equal(pos, np.flatnonzero(crit > np.float32(0.25)))
+
+
+# ---------------------------------------------------------------------------
+# Gather
+
+
+@pytest.mark.parametrize("row_bytes", [1, 3, 16, 4095, 4096])
+def test_gather_is_fancy_indexing(ref, row_bytes):
+    r = rng(9)
+    src = r.integers(0, 256, (200, row_bytes), dtype=np.uint8)
+    idx = r.permutation(200)[:150].astype(np.int32)
+    kept_pos = np.sort(r.choice(150, 60, replace=False)).astype(np.int32)
+    dst, ids = ref.gather(src, idx, kept_pos)
+    assert np.array_equal(ids, idx[kept_pos])
+    assert np.array_equal(dst, src[idx[kept_pos]])
+    dst, ids = ref.gather(src, None, kept_pos)
+    assert np.array_equal(ids, kept_pos) and np.array_equal(dst, src[kept_pos])
+    _, ids = ref.gather(None, idx, kept_pos)
+    assert np.array_equal(ids, idx[kept_pos])
+
+
+def test_gather_csr_is_scipy_row_indexing(ref):
+    r = rng(10)
+    S = sp.random(300, 50, density=0.1, format="csr", random_state=3, dtype=np.float32)
+    F = ref.Features.csr(S.indptr, S.indices, S.data, 50)
+    idx = r.permutation(300)[:100].astype(np.int32)
+    kept_pos = np.sort(r.choice(100, 37, replace=False)).astype(np.int32)
+    rowptr, col, val = ref.gather_csr(F, idx, kept_pos, int(S.nnz))
+    want = S[idx[kept_pos]]
+    assert np.array_equal(rowptr, want.indptr)
+    assert np.array_equal(col, want.indices) and np.array_equal(val, want.data)
+    with pytest.raises(ValueError):
+        ref.gather_csr(F, idx, kept_pos, int(want.nnz) - 1)
+
+
+# ---------------------------------------------------------------------------
+# SVM SGD step on kept rows
+
+
+def test_hinge_step_closed_form_single_row(ref):
+    x = np.array([[0.5, -2.0, 1.5]], np.float32)
+    F = ref.Features.dense(x)
+    for y in (1.0, -1.0):
+        w, loss = ref.svm_sgd_step(F, np.array([y], np.float32), None, 1, np.zeros(3), 1e-2, 0.25)
+        assert loss[0] == 1.0                       # w = 0: hinge loss is 1
+        assert np.array_equal(w, (0.25 * y * x[0]).astype(np.float32))
+    # margin >= 1: only the regulariser acts; loss is 0
+    w0 = np.array([2.0, 0.0, 0.0], np.float32)
+    w, loss = ref.svm_sgd_step(F, np.array([1.0], np.float32), None, 1, w0, 0.5, 0.1)
+    assert loss[0] == 0.0 and np.allclose(w, (1 - 0.05) * w0, rtol=1e-7)
+    # exactly on the kink (margin == 1): subgradient taken as 0
+    w0 = np.array([2.0, 0.0, 0.0], np.float32)
+    xk = np.array([[0.5, 1.0, 1.0]], np.float32)
+    w, loss = ref.svm_sgd_step(ref.Features.dense(xk), np.array([1.0], np.float32), None, 1, w0,
+                               0.0, 0.1)
+    assert loss[0] == 0.0 and np.array_equal(w, w0)
+
+
+def _torch_hinge_objective(X, y, w, lam):
+    margins = y * (X @ w)
+    return 0.5 * lam * (w @ w) + torch.relu(1 - margins).mean()
+
+
+def test_hinge_step_matches_autograd_and_finite_differences(ref):
+    r = rng(11)
+    n, d, m = 80, 9, 33
+    X = r.standard_normal((n, d)).astype(np.float32)
+    y = np.where(r.random(n) < 0.5, 1.0, -1.0).astype(np.float32)
+    w0 = (0.3 * r.standard_normal(d)).astype(np.float32)
+    rows = r.choice(n, m, replace=False).astype(np.int32)
+    lam, lr = 0.05, 0.2
+    w1, loss = ref.svm_sgd_step(ref.Features.dense(X), y, rows, m, w0, lam, lr)
+    Xt, yt = torch.from_numpy(X[rows]).double(), torch.from_numpy(y[rows]).double()
+    wt = torch.from_numpy(w0).double().requires_grad_(True)
+    obj = _torch_hinge_objective(Xt, yt, wt, lam)
+    obj.backward()
+    want = wt.detach() - lr * wt.grad
+    assert np.allclose(w1, want.numpy(), rtol=1e-6, atol=1e-7)
+    assert np.allclose(loss, torch.relu(1 - yt * (Xt @ wt.detach())).numpy(), rtol=1e-6, atol=1e-7)
+    # central finite differences of the batch objective (no margin sits on the kink)
+    assert np.min(np.abs(1 - (yt * (Xt @ wt.detach())).numpy())) > 1e-3
+    F = ref.Features.dense(X)
+    g_fd = np.zeros(d)
+    for k in range(d):
+        e = np.zeros(d, np.float32)
+        e[k] = 1e-3
+        g_fd[k] = (ref.primal_objective(F, y, rows, m, w0 + e, lam)
+                   - ref.primal_objective(F, y, rows, m, w0 - e, lam)) / float(
+            (w0 + e)[k].astype(np.float64) - (w0 - e)[k].astype(np.float64))
+    assert np.allclose((w0 - w1) / lr, g_fd, rtol=2e-3, atol=2e-4)
+    assert ref.primal_objective(F, y, rows, m, w0, lam) == pytest.approx(obj.item(), rel=1e-8)
+
+
+def test_hinge_step_empty_batch_and_projection(ref):
+    r = rng(12)
+    X = r.standard_normal((10, 4)).astype(np.float32)
+    y = np.ones(10, np.float32)
+    w0 = r.standard_normal(4).astype(np.float32)
+    w1, loss = ref.svm_sgd_step(ref.Features.dense(X), y, None, 0, w0, 0.1, 0.5)
+    assert np.array_equal(w0, w1) and loss.size == 0
+    w_free, _ = ref.svm_sgd_step(ref.Features.dense(X), y, None, 10, w0, 0.1, 0.5)
+    w_proj, _ = ref.svm_sgd_step(ref.Features.dense(X), y, None, 10, w0, 0.1, 0.5, radius=0.3)
+    nrm = np.linalg.norm(w_free.astype(np.float64))
+    assert nrm > 0.3
+    assert np.allclose(w_proj, w_free * (0.3 / nrm), rtol=1e-6)
+    w_big, _ = ref.svm_sgd_step(ref.Features.dense(X), y, None, 10, w0, 0.1, 0.5, radius=1e3)
+    assert np.array_equal(w_big, w_free)
+
+
+def test_csr_step_equals_dense_step(ref):
+    r = rng(13)
+    X = r.standard_normal((60, 20)).astype(np.float32)
+    X[r.random((60, 20)) < 0.7] = 0
+    S = sp.csr_matrix(X)
+    y = np.where(r.random(60) < 0.5, 1.0, -1.0).astype(np.float32)
+    rows = r.choice(60, 25, replace=False).astype(np.int32)
+    w0 = r.standard_normal(20).astype(np.float32) * 0.2
+    a = ref.svm_sgd_step(ref.Features.dense(X), y, rows, 25, w0, 0.01, 0.3)
+    b = ref.svm_sgd_step(ref.Features.csr(S.indptr, S.indices, S.data, 20), y, rows, 25, w0, 0.01,
+                         0.3)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def test_keep_everything_reduces_to_vanilla_minibatch_sgd(ref):
+    """gamma = 1 keeps every candidate, so the step is the plain Pegasos mini-batch step."""
+    r = rng(14)
+    n, d, P = 500, 16, 128
+    X = r.standard_normal((n, d)).astype(np.float32)
+    y = np.where(r.random(n) < 0.5, 1.0, -1.0).astype(np.float32)
+    F = ref.Features.dense(X)
+    w_a = np.zeros(d, np.float32)
+    w_b = np.zeros(d, np.float32)
+    phi = r.standard_normal(d).astype(np.float32)
+    perm = r.permutation(n).astype(np.int32)
+    for t, s in enumerate(range(0, n, P)):
+        idx = perm[s:s + P]
+        lr = 0.5 / math.sqrt(t + 1)
+        out = ref.step(F, y, idx, idx.size, w_a, phi, 0.0, 1.0, 5, t, 1e-2, lr, 0.0, 0.0)
+        assert out["m"] == idx.size and np.array_equal(out["kept_ids"], idx)
+        w_a = out["w"]
+        w_b = ref.vanilla_minibatch_sgd(F, y, idx, idx.size, w_b, 1e-2, lr)
+        assert np.array_equal(w_a, w_b)  # bit-identical
+
+
+def test_single_row_steps_match_sklearn_hinge_sgd(ref):
+    """Pool of one row, everything kept: one epoch equals scikit-learn's plain SGD with
+    hinge loss, L2 penalty and a constant step (its textbook per-sample update)."""
+    from sklearn.linear_model import SGDClassifier
+    r = rng(15)
+    n, d = 150, 6
+    X = r.standard_normal((n, d)).astype(np.float32)
+    y = np.where(X @ r.standard_normal(d) + 0.3 * r.standard_normal(n) > 0, 1.0, -1.0).astype(
+        np.float32)
+    lam, lr = 0.01, 0.05
+    clf = SGDClassifier(loss="hinge", penalty="l2", alpha=lam, fit_intercept=False,
+                        learning_rate="constant", eta0=lr, shuffle=False, max_iter=1, tol=None,
+                        average=False)
+    clf.fit(X.astype(np.float64), y, coef_init=np.zeros((1, d)))
+    F = ref.Features.dense(X)
+    w = np.zeros(d, np.float32)
+    for i in range(n):
+        w, _ = ref.svm_sgd_step(F, y, np.array([i], np.int32), 1, w, lam, lr)
+    assert np.allclose(w, clf.coef_[0], rtol=1e-4, atol=1e-6)
+
+
+def test_objective_decreases_on_tiny_strongly_convex_instance(ref):
+    r = rng(16)
+    n, d = 16, 4
+    X = r.standard_normal((n, d)).astype(np.float32)
+    X /= np.linalg.norm(X, axis=1, keepdims=True)
+    y = np.where(X @ np.array([1.0, -1.0, 0.5, 0.0]) > 0, 1.0, -1.0).astype(np.float32)
+    F = ref.Features.dense(X)
+    lam = 0.1
+    idx = np.arange(n, dtype=np.int32)
+
+    def run(gamma, steps, seed):
+        w, phi, b = np.zeros(d, np.float32), np.zeros(d, np.float32), 0.0
+        objs = [ref.primal_objective(F, y, None, n, w, lam)]
+        for t in range(steps):
+            out = ref.step(F, y, idx, n, w, phi, b, gamma, seed, t, lam, 0.05, 0.0, 0.1)
+            w, phi, b = out["w"], out["phi"], out["bias"]
+            objs.append(ref.primal_objective(F, y, None, n, w, lam))
+        return np.array(objs)
+
+    vanilla = run(1.0, 400, 1)
+    # Full pool and a small constant step: the objective falls monotonically while the
+    # iterate travels to the optimum (the first 200 steps here); once it chatters across
+    # hinge kinks a subgradient step may rise, but never above the best value by much.
+    assert np.all(np.diff(vanilla[:201]) < 0)
+    assert np.all(vanilla[200:] <= vanilla[200])
+    assert np.all(vanilla[200:] - np.minimum.accumulate(vanilla)[200:] < 5e-4)
+    assert vanilla[-1] < 0.5 * vanilla[0]
+    shrunk = run(0.1, 400, 1)
+    assert shrunk[-1] < shrunk[0]
+    assert abs(shrunk[-1] - vanilla[-1]) < 0.05 * vanilla[-1]   # same objective value region
+
+
+# ---------------------------------------------------------------------------
+# Assistant update
+
+
+def test_assistant_update_matches_autograd(ref):
+    r = rng(17)
+    n, d, m = 70, 11, 29
+    X = r.standard_normal((n, d)).astype(np.float32)
+    phi0 = (0.2 * r.standard_normal(d)).astype(np.float32)
+    rows = r.choice(n, m, replace=False).astype(np.int32)
+    loss = r.gamma(2.0, 0.5, m).astype(np.float32)
+    T, lr_a, l2_a, b0 = 0.8, 0.3, 0.02, 0.15
+    phi1, b1 = ref.assistant_update(ref.Features.dense(X), rows, m, loss, T, phi0, b0, lr_a, l2_a)
+    Xt = torch.from_numpy(X[rows]).double()
+    pt = torch.from_numpy(phi0).double().requires_grad_(True)
+    bt = torch.tensor(float(np.float32(b0)), dtype=torch.float64, requires_grad=True)
+    z = torch.from_numpy((loss > np.float32(T)).astype(np.float64))
+    obj = torch.nn.functional.binary_cross_entropy_with_logits(Xt @ pt + bt, z) + 0.5 * l2_a * (
+        pt @ pt)
+    obj.backward()
+    assert np.allclose(phi1, (pt.detach() - lr_a * pt.grad).numpy(), rtol=2e-6, atol=1e-7)
+    assert b1 == pytest.approx(float(bt.detach() - lr_a * bt.grad), rel=2e-6)
+    # the objective function the oracle exposes is the same cross-entropy
+    zz = (loss > np.float32(T)).astype(np.uint8)
+    ce = ref.assistant_objective(ref.Features.dense(X), rows, m, zz, phi0, b0)
+    assert ce == pytest.approx(float(obj.detach() - 0.5 * l2_a * (pt.detach() @ pt.detach())),
+                               rel=1e-10)
+
+
+def test_assistant_label_direction(ref):
+    """T = +inf labels everything trivial (z=0): every keep probability drops;
+    T = -inf labels everything informative (z=1): every keep probability rises."""
+    r = rng(18)
+    X = np.abs(r.standard_normal((40, 5))).astype(np.float32)   # positive features
+    F = ref.Features.dense(X)
+    phi0 = np.zeros(5, np.float32)
+    loss = np.ones(40, np.float32)
+    _, g0 = ref.assistant_score(F, None, 40, phi0, bias=0.0)
+    phi_d, b_d = ref.assistant_update(F, None, 40, loss, float("inf"), phi0, 0.0, 0.5)
+    phi_u, b_u = ref.assistant_update(F, None, 40, loss, float("-inf"), phi0, 0.0, 0.5)
+    assert np.all(ref.assistant_score(F, None, 40, phi_d, bias=b_d)[1] < g0)
+    assert np.all(ref.assistant_score(F, None, 40, phi_u, bias=b_u)[1] > g0)
+    # strict '>' in the label: loss == T is trivial
+    phi_e, _ = ref.assistant_update(F, None, 40, loss, 1.0, phi0, 0.0, 0.5)
+    assert np.array_equal(phi_e, phi_d)
+
+
+def test_single_row_assistant_steps_match_sklearn_logistic_sgd(ref):
+    from sklearn.linear_model import SGDClassifier
+    r = rng(19)
+    n, d = 120, 5
+    X = r.standard_normal((n, d)).astype(np.float32)
+    loss = r.gamma(2.0, 0.5, n).astype(np.float32)
+    T, lr_a = 0.9, 0.1
+    z = (loss > np.float32(T)).astype(np.int64)
+    clf = SGDClassifier(loss="log_loss", penalty=None, alpha=0.0, fit_intercept=True,
+                        learning_rate="constant", eta0=lr_a, shuffle=False, max_iter=1, tol=None,
+                        average=False)
+    clf.fit(X.astype(np.float64), z, coef_init=np.zeros((1, d)), intercept_init=np.zeros(1))
+    F = ref.Features.dense(X)
+    phi, b = np.zeros(d, np.float32), 0.0
+    for i in range(n):
+        phi, b = ref.assistant_update(F, np.array([i], np.int32), 1, loss[i:i + 1], T, phi, b, lr_a)
+    assert np.allclose(phi, clf.coef_[0], rtol=1e-4, atol=1e-6)
+    assert b == pytest.approx(clf.intercept_[0], rel=1e-4, abs=1e-6)
+
+
+# ---------------------------------------------------------------------------
+# Whole step: order of operations, and brute force over every keep mask
+
+
+def test_step_uses_pre_update_losses_and_composes(ref):
+    r = rng(20)
+    n, d, P = 64, 8, 48
+    X = r.standard_normal((n, d)).astype(np.float32)
+    y = np.where(r.random(n) < 0.5, 1.0, -1.0).astype(np.float32)
+    F = ref.Features.dense(X)
+    w0 = (0.4 * r.standard_normal(d)).astype(np.float32)
+    phi0 = (0.4 * r.standard_normal(d)).astype(np.float32)
+    idx = r.permutation(n)[:P].astype(np.int32)
+    out = ref.step(F, y, idx, P, w0, phi0, 0.05, 0.2, 9, 4, 0.01, 0.3, 0.5, 0.2)
+    logit, prob = ref.assistant_score(F, idx, P, phi0, bias=0.05)
+    keep, pos = ref.shrink(prob, 0.2, 9, 4)
+    assert np.array_equal(out["keep"], keep) and np.array_equal(out["kept_pos"], pos)
+    ids = idx[pos]
+    assert np.array_equal(out["kept_ids"], ids)
+    # losses are the hinge losses at w0 (before the Boss update), by numpy in float64
+    marg = y[ids].astype(np.float64) * (X[ids].astype(np.float64) @ w0.astype(np.float64))
+    assert np.allclose(out["loss"], np.maximum(0, 1 - marg), rtol=1e-6, atol=1e-7)
+    w1, loss = ref.svm_sgd_step(F, y, ids, ids.size, w0, 0.01, 0.3)
+    assert np.array_equal(out["w"], w1) and np.array_equal(out["loss"], loss)
+    phi1, b1 = ref.assistant_update(F, ids, ids.size, loss, 0.5, phi0, 0.05, 0.2)
+    assert np.array_equal(out["phi"], phi1) and out["bias"] == b1
+
+
+@pytest.mark.parametrize("n", [1, 2, 5, 10, 16])
+def test_brute_force_every_keep_mask(ref, n):
+    """prob in {0,1} with gamma = 0 forces any mask.  All 2^n masks (n <= 10) or 4096 of them
+    (n = 16, every mask for compaction) go through keep/compact/gather/SGD and are compared
+    with one-line numpy definitions in float64."""
+    r = rng(100 + n)
+    d = 3
+    X = r.standard_normal((n, d)).astype(np.float32)
+    y = np.where(r.random(n) < 0.5, 1.0, -1.0).astype(np.float32)
+    F = ref.Features.dense(X)
+    w0 = (0.5 * r.standard_normal(d)).astype(np.float32)
+    idx = r.permutation(n).astype(np.int32)
+    Xd, yd, wd = X.astype(np.float64), y.astype(np.float64), w0.astype(np.float64)
+    lam, lr = 0.1, 0.5
+    masks = np.arange(2 ** n, dtype=np.uint32)
+    full_sgd = masks if n <= 10 else masks[:: 16]
+    bits = ((masks[:, None] >> np.arange(n, dtype=np.uint32)[None, :]) & 1).astype(np.uint8)
+    sgd_set = set(int(v) for v in full_sgd)
+    for mask, b in zip(masks, bits):
+        keep, pos = ref.shrink(b.astype(np.float32), 0.0, 1, 2)
+        assert np.array_equal(keep, b) and np.array_equal(pos, np.flatnonzero(b))
+        if int(mask) not in sgd_set:
+            continue
+        rows_g, ids = ref.gather(X, idx, pos)
+        assert np.array_equal(ids, idx[pos]) and np.array_equal(rows_g, X[idx[pos]])
+        w1, loss = ref.svm_sgd_step(F, y, ids, ids.size, w0, lam, lr)
+        if ids.size == 0:
+            assert np.array_equal(w1, w0)
+            continue
+        marg = yd[ids] * (Xd[ids] @ wd)
+        G = ((marg < 1) * yd[ids]) @ Xd[ids]
+        want = (1 - lr * lam) * wd + lr / ids.size * G
+        assert np.allclose(w1, want, rtol=1e-6, atol=1e-7)
+        assert np.allclose(loss, np.maximum(0, 1 - marg), rtol=1e-6, atol=1e-7)
+
+
+# ---------------------------------------------------------------------------
+# Length-bucketed batching (definition is this build's; brute force only)
+
+
+def test_bucket_batches_brute_force(ref):
+    r = rng(21)
+    m = 500
+    ls = np.clip(r.poisson(27, m), 1, 128).astype(np.int32)
+    lt = np.clip(r.poisson(27, m), 1, 128).astype(np.int32)
+    order, start, batch_of, nb = ref.bucket_batches(ls, lt, 8, 16, 4096)
+    bucket = np.minimum(15, (np.maximum(ls, lt) - 1) // 8)
+    assert np.array_equal(np.sort(order), np.arange(m))                   # a permutation
+    assert np.all(np.diff(bucket[order]) >= 0)                            # grouped by bucket
+    for b in range(16):
+        seg = order[start[b]:start[b + 1]]
+        assert np.array_equal(seg, np.flatnonzero(bucket == b))            # stable inside a bucket
+        cap = max(1, 4096 // (16 * (b + 1)))
+        if seg.size:
+            rel = batch_of[start[b]:start[b + 1]] - batch_of[start[b]]
+            assert np.array_equal(rel, np.arange(seg.size) // cap)
+    assert nb == len(np.unique(batch_of)) and batch_of.max() == nb - 1
+    # padded-token budget holds for every batch
+    for q in range(nb):
+        members = order[batch_of == q]
+        width = 8 * (bucket[members[0]] + 1)
+        assert members.size * 2 * width <= 4096 or members.size == 1
