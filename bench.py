@@ -1,0 +1,274 @@
+#!/usr/bin/env python3
+"""Benchmark of the AutoAssist hot path on one MI355X.
+
+A step is one pass of the whole path over one candidate pool: Assistant score ->
+Bernoulli keep -> stable compaction -> gather of the kept ids -> hinge-loss SGD step
+on the kept rows -> Assistant update.  The workload is the dense linear-SVM
+configuration: n = 1,000,000 rows, d = 1024 fp32 (unit-norm Gaussian rows, planted
+labels with 5 % flips), pools of 16,384 cut from a per-epoch permutation, 5 epochs
+= 310 steps.  Inputs are synthetic and resident in HBM before the timed region.
+
+Prints ONE JSON line: candidates/s for the whole job, plus a `roofline` object for the
+dominant kernel (timed live with HIP events around each of its launches) and a
+`cpu_baseline` object (the CPU oracle timed on a bounded sample of the same workload).
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=310)
+    ap.add_argument("--warmup", type=int, default=62)
+    ap.add_argument("--n", type=int, default=1_000_000)
+    ap.add_argument("--d", type=int, default=1024)
+    ap.add_argument("--pool", type=int, default=16384)
+    ap.add_argument("--pipeline", choices=["fused", "two_pass", "staged"], default="fused")
+    ap.add_argument("--launch", choices=["graph", "stream"], default="graph")
+    ap.add_argument("--repeats", type=int, default=5, help="timed regions; the median is reported")
+    ap.add_argument("--lr0", type=float, default=1.0)
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--threads", type=int, default=min(16, os.cpu_count() or 1))
+    return ap.parse_args()
+
+
+class Job:
+    """Device-resident workload and model state; runs ranges of global steps."""
+
+    def __init__(self, a, torch, api, synth):
+        self.a, self.torch, self.api = a, torch, api
+        t0 = time.time()
+        X, y, _ = synth.dense_svm(n=a.n, d=a.d, threads=a.threads)
+        self.gen_s = time.time() - t0
+        self.Xh, self.yh = X, y
+        self.steps_per_epoch = (a.n + a.pool - 1) // a.pool
+        total_steps = a.warmup + a.steps
+        self.n_epochs = (total_steps + self.steps_per_epoch - 1) // self.steps_per_epoch
+        self.perms_h = [synth.epoch_permutation(a.n, seed=7, epoch=e) for e in range(self.n_epochs)]
+        t0 = time.time()
+        self.X = torch.from_numpy(X).cuda()
+        self.y = torch.from_numpy(y).cuda()
+        self.perms = [torch.from_numpy(p).cuda() for p in self.perms_h]
+        torch.cuda.synchronize()
+        self.h2d_s = time.time() - t0
+        self.F = api.Features.dense(self.X)
+        self.ws = api.Workspace(a.pool, a.d)
+        d, P = a.d, a.pool
+        self.w = torch.zeros(d, device="cuda")
+        self.phi = torch.zeros(d, device="cuda")
+        self.b = torch.zeros(1, device="cuda")
+        self.T = torch.zeros(1, device="cuda")
+        self.t_upd = torch.zeros(1, dtype=torch.int32, device="cuda")
+        self.hist = torch.zeros(total_steps, dtype=torch.int32, device="cuda")
+        # per-step outputs of the staged pipelines
+        self.prob = torch.zeros(P, device="cuda")
+        self.keep = torch.zeros(P, dtype=torch.uint8, device="cuda")
+        self.pos = torch.zeros(P, dtype=torch.int32, device="cuda")
+        self.ids = torch.zeros(P, dtype=torch.int32, device="cuda")
+        self.loss = torch.zeros(P, device="cuda")
+        self.cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+        if a.pipeline == "staged":
+            self.Xk = torch.zeros((P, d), device="cuda")
+            self.yk = torch.zeros(P, device="cuda")
+            self.Fk = api.Features.dense(self.Xk)
+        self.gamma, self.lam, self.lr_a, self.seed = 0.1, 1e-4, 0.1, 42
+
+    def reset(self):
+        for t in (self.w, self.phi, self.b, self.t_upd, self.hist):
+            t.zero_()
+
+    def pool_of(self, g):
+        """(epoch, first row, size) of global step g."""
+        e, t = divmod(g, self.steps_per_epoch)
+        lo = t * self.a.pool
+        return e, lo, min(self.a.pool, self.a.n - lo)
+
+    def candidates(self, g0, g1):
+        return sum(self.pool_of(g)[2] for g in range(g0, g1))
+
+    def cfg(self, g, lr):
+        return self.api.step_config(self.gamma, self.lam, lr, self.lr_a, 0.0, self.seed, g, self.T)
+
+    def run(self, g0, g1, hook=None):
+        """Enqueue global steps [g0, g1) on the current stream.  hook(g): called before a step
+        whose row-pass kernel should be bracketed by events."""
+        api, a = self.api, self.a
+        if a.pipeline == "fused" and hook is None:
+            g = g0
+            while g < g1:   # one C call per epoch slice; step size lr0/sqrt(t) lives on the device
+                e, lo, _ = self.pool_of(g)
+                last = min(g1, (e + 1) * self.steps_per_epoch)
+                rows = min(a.n - lo, (last - g) * a.pool)
+                api.train_epoch(self.F, self.y, self.perms[e][lo:], rows, a.pool, self.w, self.phi,
+                                self.b, self.cfg(g, a.lr0), self.t_upd, self.hist[g:], self.ws)
+                g = last
+            return
+        for g in range(g0, g1):
+            e, lo, P = self.pool_of(g)
+            idx = self.perms[e][lo:lo + P]
+            # host-side schedule: every step is assumed to update (m > 0), true for these pools
+            lr = a.lr0 / math.sqrt(g + 1)
+            cfg = self.cfg(g, lr)
+            if hook:
+                hook(g)
+            if a.pipeline == "fused":
+                api.fused_step(self.F, self.y, idx, P, self.w, self.phi, self.b, cfg, None,
+                               self.prob, self.keep, self.pos, self.ids, self.loss, self.cnt,
+                               self.ws)
+            elif a.pipeline == "two_pass":
+                api.score_shrink(self.F, idx, P, self.phi, self.b, self.gamma, self.seed, g, None,
+                                 self.prob, self.keep, self.pos, self.cnt, self.ws)
+                api.gather(None, 0, idx, self.pos, self.cnt, P, None, self.ids)
+                api.boss_assistant_step(self.F, self.y, self.ids, self.cnt, P, self.w, self.phi,
+                                        self.b, cfg, self.loss, self.ws)
+            else:
+                api.assistant_score(self.F, idx, P, self.phi, self.b, None, self.prob)
+                api.shrink(self.prob, P, self.gamma, self.seed, g, self.keep, self.pos, self.cnt,
+                           self.ws)
+                api.gather(self.X, 4 * a.d, idx, self.pos, self.cnt, P, self.Xk, self.ids)
+                api.gather(self.y, 4, idx, self.pos, self.cnt, P, self.yk, None)
+                api.svm_sgd_step(self.Fk, self.yk, None, self.cnt, P, self.w, self.lam, lr, 0.0,
+                                 self.loss, self.ws)
+                api.assistant_update(self.Fk, None, self.cnt, P, self.loss, self.T, self.phi,
+                                     self.b, self.lr_a, 0.0, self.ws)
+
+
+def cpu_baseline(job, budget_s):
+    """The CPU oracle, as it stands, on the first pools of the same workload."""
+    from oracle import aa_ref as ref
+    a = job.a
+    F = ref.Features.dense(job.Xh)
+    w = np.zeros(a.d, np.float32)
+    phi = np.zeros(a.d, np.float32)
+    b = 0.0
+    done, cands, t_upd = 0, 0, 0
+    t0 = time.perf_counter()
+    while done < job.steps_per_epoch and time.perf_counter() - t0 < budget_s:
+        _, lo, P = job.pool_of(done)
+        idx = job.perms_h[0][lo:lo + P]
+        lr = np.float32(a.lr0 / math.sqrt(t_upd + 1))
+        out = ref.step(F, job.yh, idx, P, w, phi, b, job.gamma, job.seed, done, job.lam, lr, 0.0,
+                       job.lr_a)
+        w, phi, b = out["w"], out["phi"], out["bias"]
+        t_upd += 1 if out["m"] > 0 else 0
+        done += 1
+        cands += P
+    el = time.perf_counter() - t0
+    return {"value": cands / el, "unit": "candidates/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {done} pools of epoch 0 ({cands} candidates, {el:.1f} s), "
+                      "single thread, fp64 accumulation"}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print(f"bench.py measures one GPU only (got --gpus {a.gpus}): this build has no "
+              "multi-GPU path; run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_1905_03381_amd import api, synth
+    api.lib()  # fail loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+    job = Job(a, torch, api, synth)
+    W, K = a.warmup, a.steps
+
+    graph = None
+    if a.launch == "graph":
+        # capture the K timed steps once (capture executes nothing); replays re-run them
+        job.reset()
+        job.run(0, min(2, W + K))          # load kernels before capturing
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            job.run(W, W + K)
+
+    regions = []
+    for _ in range(max(1, a.repeats)):
+        job.reset()
+        job.run(0, W)                       # untimed warm-up steps from the initial state
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        if graph is not None:
+            graph.replay()
+        else:
+            job.run(W, W + K)
+        torch.cuda.synchronize()
+        regions.append(time.perf_counter() - t0)
+    elapsed = float(np.median(regions))
+    cands = job.candidates(W, W + K)
+    hist = job.hist.cpu().numpy()
+    kept = int(hist[W:W + K].sum()) if a.pipeline == "fused" else None
+
+    # ---- dominant kernel: the row pass, timed live with HIP events around every launch
+    # (torch events are hipEvent_t underneath: recorded once here so that they exist, then
+    # re-recorded by the library's hook on the stream the kernel is launched on)
+    pairs = {}
+
+    def hook(g):
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        e1.record()
+        pairs[g] = (e0, e1)
+        api.profile_hook(e0.cuda_event, e1.cuda_event)
+
+    job.reset()
+    saved_pipeline = a.pipeline
+    job.run(0, W)
+    job.run(W, W + K, hook=hook)
+    torch.cuda.synchronize()
+    durs = np.array([pairs[g][0].elapsed_time(pairs[g][1]) for g in range(W, W + K)]) * 1e-3
+    sizes = np.array([job.pool_of(g)[2] for g in range(W, W + K)], dtype=np.float64)
+    if saved_pipeline == "fused":
+        # fused pass: row + pool id + label + keep flag per candidate, loss per kept row
+        rho = (kept / cands) if kept is not None else 0.5
+        alg = sizes * (4 * a.d + 4 + 4 + 1) + rho * sizes * 4
+        kname = "k_rows_pass<pool|svm|assist> (score+keep+both gradient sums, rows read once)"
+    else:
+        alg = sizes * (4 * a.d + 4 + 4 + 1)
+        kname = "k_rows_pass<pool> (score, plus keep+compact in two_pass)"
+    achieved = float(alg.sum() / durs.sum() / 1e9)
+    roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": kname,
+                "avg_launch_us": float(durs.mean() * 1e6),
+                "alg_bytes_per_launch": float(alg.mean()), "launches_timed": int(durs.size)}
+
+    out = {
+        "metric": "candidate instances/sec through score+shrink+SGD",
+        "value": cands / elapsed,
+        "unit": "candidates/s",
+        "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": elapsed / K * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"dense linear SVM n={a.n} d={a.d} fp32, pool {a.pool}, "
+                               f"{K} steps after {W} warm-up steps (5 epochs = 310 steps)",
+                   "pipeline": a.pipeline, "launch": a.launch, "gamma": job.gamma,
+                   "lambda": job.lam, "lr0": a.lr0, "lr_a": job.lr_a, "T": 0.0},
+        "regions_ms": [r * 1e3 for r in regions],
+        "keep_rate": (kept / cands) if kept is not None else None,
+        "end_to_end_GBps": float(alg.sum() / elapsed / 1e9),
+        "setup_s": {"generate": job.gen_s, "h2d": job.h2d_s},
+        "roofline": roofline,
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(job, a.cpu_seconds)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,716 @@
+// C ABI of the AutoAssist hot path: argument checks, workspace carving and the
+// choice between the register-resident dense kernels and the general ones.
+// Every step of the path runs in the HIP kernels; there is no host fallback.
+#include "../../include/autoassist.h"
+
+#include "aa_common.hpp"
+#include "aa_dense.hpp"
+#include "aa_general.hpp"
+#include "aa_select.hpp"
+
+using namespace aa;
+
+namespace {
+
+constexpr int kTicketPassTail = 0;
+constexpr int kTicketFinalize = 1;
+constexpr int kTicketKeep = 2;
+
+struct Ws {
+  char *base;
+  int32_t *tickets;
+  int32_t *blk_cnt;
+  float *blk_gb;
+  char *grad;         // gradient partials / accumulators
+  uint8_t *flags;     // [P]
+  float *loss_pool;   // [P]
+  int32_t *blk_off;   // [P/256 + 2]
+  float *prob;        // [P]   per-step outputs of the epoch driver
+  int32_t *kept_pos;  // [P]
+  int32_t *kept_ids;  // [P]
+  float *loss;        // [P]
+  size_t total;
+};
+
+size_t general_acc_bytes(int32_t d) { return (16 + 2 * (size_t)d) * sizeof(float); }
+
+Ws carve(void *ws, size_t grad_bytes, int32_t P, bool epoch_outputs = false) {
+  Ws w;
+  w.base = static_cast<char *>(ws);
+  w.tickets = reinterpret_cast<int32_t *>(w.base + kWsTickets);
+  w.blk_cnt = reinterpret_cast<int32_t *>(w.base + kWsBlkCnt);
+  w.blk_gb = reinterpret_cast<float *>(w.base + kWsBlkGb);
+  size_t off = kWsBody;
+  w.grad = w.base + off;
+  off += align_up(grad_bytes, 256);
+  w.flags = reinterpret_cast<uint8_t *>(w.base + off);
+  off += align_up((size_t)(P > 0 ? P : 0), 256);
+  w.loss_pool = reinterpret_cast<float *>(w.base + off);
+  off += align_up(sizeof(float) * (size_t)(P > 0 ? P : 0), 256);
+  w.blk_off = reinterpret_cast<int32_t *>(w.base + off);
+  off += align_up(sizeof(int32_t) * ((size_t)(P > 0 ? P : 0) / kKeepBlock + 2), 256);
+  const size_t per = align_up(sizeof(float) * (size_t)(P > 0 ? P : 0), 256);
+  w.prob = reinterpret_cast<float *>(w.base + off);
+  w.kept_pos = reinterpret_cast<int32_t *>(w.base + off + per);
+  w.kept_ids = reinterpret_cast<int32_t *>(w.base + off + 2 * per);
+  w.loss = reinterpret_cast<float *>(w.base + off + 3 * per);
+  if (epoch_outputs) off += 4 * per;
+  w.total = off;
+  return w;
+}
+
+int32_t check_ws(const void *ws, size_t ws_bytes, size_t need) {
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255) != 0 || ws_bytes < need)
+    return AA_ERR_WORKSPACE;
+  return AA_OK;
+}
+
+int32_t check_features(const aa_features *F) {
+  if (!F) return AA_ERR_NULL;
+  if (F->d <= 0 || F->n < 0) return AA_ERR_SHAPE;
+  if (F->layout == AA_DENSE) {
+    if (!F->x) return AA_ERR_NULL;
+    if (F->ld < F->d) return AA_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(F->x) & 3) != 0) return AA_ERR_ALIGN;
+    return AA_OK;
+  }
+  if (F->layout == AA_CSR) {
+    if (!F->rowptr || !F->col) return AA_ERR_NULL;
+    return AA_OK;
+  }
+  return AA_ERR_SHAPE;
+}
+
+int32_t hip_status(hipError_t e) { return e == hipSuccess ? AA_OK : AA_ERR_HIP; }
+
+bool vec_ok(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+hipStream_t as_stream(void *s) { return static_cast<hipStream_t>(s); }
+
+// One-shot timing hook: the next row-pass launch is bracketed by two caller events.
+hipEvent_t g_hook_before = nullptr, g_hook_after = nullptr;
+bool g_hook_armed = false;
+
+struct HookScope {
+  hipStream_t st;
+  bool on;
+  explicit HookScope(hipStream_t s) : st(s), on(g_hook_armed) {
+    g_hook_armed = false;
+    if (on) (void)hipEventRecord(g_hook_before, st);
+  }
+  ~HookScope() {
+    if (on) (void)hipEventRecord(g_hook_after, st);
+  }
+};
+
+// Common description of one row pass, lowered to either kernel family.
+struct PassSpec {
+  const aa_features *F;
+  int mode;
+  const float *y;
+  const int32_t *rows;
+  int32_t count_max;
+  const int32_t *m_dev;
+  float *w;
+  float *phi;
+  float *bias;
+  const float *T;
+  float gamma;
+  uint64_t seed, step;
+  int do_keep;
+  float *logit;
+  float *prob;
+  uint8_t *flags;
+  float *loss_out;
+  const float *loss_in;
+  int tail_compact;
+  int32_t *kept_pos;
+  int32_t *kept_count;
+};
+
+bool use_fast(const PassSpec &s) {
+  if (!dense_fast_ok(s.F)) return false;
+  if ((s.mode & kSvm) && !vec_ok(s.w)) return false;
+  if ((s.mode & (kPool | kAssist)) && !vec_ok(s.phi)) return false;
+  return true;
+}
+
+size_t grad_bytes_for(const PassSpec &s) {
+  const int nvec = ((s.mode & kSvm) ? 1 : 0) + ((s.mode & kAssist) ? 1 : 0);
+  if (nvec == 0) return 0;
+  if (use_fast(s))
+    return (size_t)dense_pass_blocks(s.F->d, s.count_max, s.mode) * nvec *
+           dense_d_pad(s.F->d) * sizeof(float);
+  return general_acc_bytes(s.F->d);
+}
+
+// Launch the pass (and, for the general family, the accumulator clear before it).
+hipError_t run_pass(const PassSpec &s, const Ws &ws, int32_t *nblk_out, hipStream_t st) {
+  const float omg = 1.0f - s.gamma;
+  if (use_fast(s)) {
+    PassArgs a{};
+    a.x = s.F->x;
+    a.ld = s.F->ld;
+    a.d4 = s.F->d / 4;
+    a.y = s.y;
+    a.rows = s.rows;
+    a.count_max = s.count_max;
+    a.m_dev = s.m_dev;
+    a.w = s.w;
+    a.phi = s.phi;
+    a.bias = s.bias;
+    a.T = s.T;
+    a.gamma = s.gamma;
+    a.one_minus_gamma = omg;
+    a.key = make_draw_key(s.seed, s.step);
+    a.do_keep = s.do_keep;
+    a.logit = s.logit;
+    a.prob = s.prob;
+    a.flags = s.flags;
+    a.loss_out = s.loss_out;
+    a.loss_in = s.loss_in;
+    a.partial = reinterpret_cast<float *>(ws.grad);
+    a.blk_cnt = ws.blk_cnt;
+    a.blk_gb = ws.blk_gb;
+    a.tail_compact = s.tail_compact;
+    a.kept_pos = s.kept_pos;
+    a.kept_count = s.kept_count;
+    a.ticket = ws.tickets + kTicketPassTail;
+    const int32_t nblk = dense_pass_blocks(s.F->d, s.count_max, s.mode);
+    *nblk_out = nblk;
+    HookScope hook(st);
+    return launch_dense_pass(a, s.mode, s.F->d, nblk, st);
+  }
+  const bool csr = s.F->layout == AA_CSR;
+  float *acc = reinterpret_cast<float *>(ws.grad);
+  if (s.mode & (kSvm | kAssist)) {
+    hipError_t e = launch_zero_f32(acc, 16 + 2 * (size_t)s.F->d, st);
+    if (e != hipSuccess) return e;
+  }
+  GenArgs a{};
+  a.x = s.F->x;
+  a.ld = s.F->ld;
+  a.d = s.F->d;
+  a.rowptr = s.F->rowptr;
+  a.col = s.F->col;
+  a.val = s.F->val;
+  a.y = s.y;
+  a.rows = s.rows;
+  a.count_max = s.count_max;
+  a.m_dev = s.m_dev;
+  a.w = s.w;
+  a.phi = s.phi;
+  a.bias = s.bias;
+  a.T = s.T;
+  a.gamma = s.gamma;
+  a.one_minus_gamma = omg;
+  a.key = make_draw_key(s.seed, s.step);
+  a.do_keep = s.do_keep;
+  a.logit = s.logit;
+  a.prob = s.prob;
+  a.flags = s.flags;
+  a.loss_out = s.loss_out;
+  a.loss_in = s.loss_in;
+  a.acc_cnt = reinterpret_cast<int32_t *>(acc);
+  a.acc_gb = acc + 1;
+  a.acc_w = acc + 16;
+  a.acc_p = acc + 16 + s.F->d;
+  a.tail_compact = s.tail_compact;
+  a.kept_pos = s.kept_pos;
+  a.kept_count = s.kept_count;
+  a.ticket = ws.tickets + kTicketPassTail;
+  const int32_t nblk = general_pass_blocks(s.count_max, csr);
+  *nblk_out = nblk;
+  HookScope hook(st);
+  return launch_general_pass(a, s.mode, csr, nblk, st);
+}
+
+struct UpdateSpec {
+  float lambda, lr, lr_a, l2_a;
+  int32_t *t_upd;
+  int32_t *kept_hist;
+  // compaction of a pool pass (flags == NULL: none)
+  const uint8_t *flags;
+  int32_t P;
+  const int32_t *idx;
+  int32_t *kept_pos;
+  int32_t *kept_ids;
+  const float *loss_pool;
+  float *loss;
+  int32_t *kept_count;
+};
+
+// Fold the gradient sums of the pass into the model.
+hipError_t run_update(const PassSpec &s, const UpdateSpec &u, const Ws &ws, int32_t nblk,
+                      hipStream_t st) {
+  const bool pool = (s.mode & kPool) != 0;
+  if (use_fast(s)) {
+    FinalizeArgs f{};
+    f.partial = reinterpret_cast<const float *>(ws.grad);
+    f.nblk = nblk;
+    f.nvec = ((s.mode & kSvm) ? 1 : 0) + ((s.mode & kAssist) ? 1 : 0);
+    f.d = s.F->d;
+    f.d_pad = dense_d_pad(s.F->d);
+    f.blk_cnt = ws.blk_cnt;
+    f.blk_gb = ws.blk_gb;
+    f.m_dev = pool ? nullptr : s.m_dev;
+    f.m_max = s.count_max;
+    f.w = (s.mode & kSvm) ? s.w : nullptr;
+    f.phi = (s.mode & kAssist) ? s.phi : nullptr;
+    f.bias = (s.mode & kAssist) ? s.bias : nullptr;
+    f.lambda = u.lambda;
+    f.lr = u.lr;
+    f.lr_a = u.lr_a;
+    f.l2_a = u.l2_a;
+    f.t_upd = u.t_upd;
+    f.kept_hist = u.kept_hist;
+    f.ticket = ws.tickets + kTicketFinalize;
+    f.flags = u.flags;
+    f.P = u.P;
+    f.idx = u.idx;
+    f.kept_pos = u.kept_pos;
+    f.kept_ids = u.kept_ids;
+    f.loss_pool = u.loss_pool;
+    f.loss = u.loss;
+    f.kept_count = u.kept_count;
+    return launch_dense_finalize(f, st);
+  }
+  const float *acc = reinterpret_cast<const float *>(ws.grad);
+  ApplyArgs p{};
+  p.d = s.F->d;
+  p.acc_cnt = reinterpret_cast<const int32_t *>(acc);
+  p.acc_gb = acc + 1;
+  p.acc_w = acc + 16;
+  p.acc_p = acc + 16 + s.F->d;
+  p.m_dev = pool ? nullptr : s.m_dev;
+  p.m_max = s.count_max;
+  p.w = (s.mode & kSvm) ? s.w : nullptr;
+  p.phi = (s.mode & kAssist) ? s.phi : nullptr;
+  p.bias = (s.mode & kAssist) ? s.bias : nullptr;
+  p.lambda = u.lambda;
+  p.lr = u.lr;
+  p.lr_a = u.lr_a;
+  p.l2_a = u.l2_a;
+  p.kept_hist = u.kept_hist;
+  p.flags = u.flags;
+  p.P = u.P;
+  p.idx = u.idx;
+  p.kept_pos = u.kept_pos;
+  p.kept_ids = u.kept_ids;
+  p.loss_pool = u.loss_pool;
+  p.loss = u.loss;
+  p.kept_count = u.kept_count;
+  return launch_general_apply(p, st);
+}
+
+__global__ __launch_bounds__(1024) void k_project(float *w, int32_t d, float radius,
+                                                  const int32_t *m_dev) {
+  __shared__ float s_part[16];
+  __shared__ float s_scale;
+  if (m_dev && *m_dev <= 0) return;
+  float ss = 0.f;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) ss = __fmaf_rn(w[k], w[k], ss);
+  ss = group_sum<kWave>(ss);
+  if ((threadIdx.x & 63) == 0) s_part[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float tot = 0.f;
+    for (int i = 0; i < (int)(blockDim.x >> 6); ++i) tot += s_part[i];
+    const float nrm = sqrtf(tot);
+    s_scale = nrm > radius ? radius / nrm : 1.f;
+  }
+  __syncthreads();
+  const float f = s_scale;
+  if (f != 1.f)
+    for (int k = threadIdx.x; k < d; k += blockDim.x) w[k] *= f;
+}
+
+__global__ void k_zero_i32(int32_t *p, int n) {
+  for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = 0;
+}
+
+int32_t fused_step_impl(const aa_features *F, const float *y, const int32_t *idx, int32_t P,
+                        float *w, float *phi, float *bias, const aa_step_config *cfg,
+                        uint64_t step, float *logit, float *prob, uint8_t *keep,
+                        int32_t *kept_pos, int32_t *kept_ids, float *loss, int32_t *kept_count,
+                        int32_t *t_upd, int32_t *kept_hist, bool epoch_outputs, void *ws_ptr,
+                        size_t ws_bytes, hipStream_t st) {
+  PassSpec s{};
+  s.F = F;
+  s.mode = kPool | kSvm | kAssist;
+  s.y = y;
+  s.rows = idx;
+  s.count_max = P;
+  s.w = w;
+  s.phi = phi;
+  s.bias = bias;
+  s.T = cfg->T;
+  s.gamma = cfg->gamma;
+  s.seed = cfg->seed;
+  s.step = step;
+  s.do_keep = 1;
+  s.logit = logit;
+  s.prob = prob;
+  if (t_upd && !use_fast(s)) return AA_ERR_SHAPE;  // device-side step-size schedule: fast dense only
+  const size_t gbytes = grad_bytes_for(s);
+  Ws ws = carve(ws_ptr, gbytes, P, epoch_outputs);
+  if (int32_t rc = check_ws(ws_ptr, ws_bytes, ws.total)) return rc;
+  if (epoch_outputs) {  // the batch of each step is assembled in the workspace
+    s.prob = ws.prob;
+    kept_pos = ws.kept_pos;
+    kept_ids = ws.kept_ids;
+    loss = ws.loss;
+  }
+  s.flags = keep ? keep : ws.flags;
+  s.loss_out = ws.loss_pool;
+  int32_t nblk = 0;
+  hipError_t e = run_pass(s, ws, &nblk, st);
+  if (e != hipSuccess) return AA_ERR_HIP;
+  UpdateSpec u{};
+  u.lambda = cfg->lambda;
+  u.lr = cfg->lr;
+  u.lr_a = cfg->lr_a;
+  u.l2_a = cfg->l2_a;
+  u.t_upd = t_upd;
+  u.kept_hist = kept_hist;
+  if (kept_pos || kept_ids || loss || kept_count) {
+    u.flags = s.flags;
+    u.P = P;
+    u.idx = idx;
+    u.kept_pos = kept_pos;
+    u.kept_ids = kept_ids;
+    u.loss_pool = ws.loss_pool;
+    u.loss = loss;
+    u.kept_count = kept_count;
+  }
+  return hip_status(run_update(s, u, ws, nblk, st));
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t aa_version(void) { return 100; }
+
+const char *aa_status_string(int32_t status) {
+  switch (status) {
+    case AA_OK: return "ok";
+    case AA_ERR_NULL: return "a required pointer is NULL";
+    case AA_ERR_SHAPE: return "bad shape or size";
+    case AA_ERR_ALIGN: return "pointer not aligned as required";
+    case AA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case AA_ERR_HIP: return "HIP launch error";
+    default: return "unknown status";
+  }
+}
+
+size_t aa_workspace_bytes(int32_t P_max, int32_t d_max) {
+  if (P_max < 0) P_max = 0;
+  if (d_max < 1) d_max = 1;
+  // any d up to d_max may be used: the register-resident kernels need block partials for
+  // d <= 2048, the general kernels dense accumulators
+  const int32_t d_fast = d_max < kFastDenseMaxD ? d_max : kFastDenseMaxD;
+  size_t grad = (size_t)kMaxBlocks * 2 * dense_d_pad(d_fast) * sizeof(float);
+  if (general_acc_bytes(d_max) > grad) grad = general_acc_bytes(d_max);
+  return carve(nullptr, grad, P_max, true).total;
+}
+
+int32_t aa_profile_hook(void *event_before, void *event_after) {
+  if (!event_before || !event_after) {
+    g_hook_armed = false;
+    return event_before || event_after ? AA_ERR_NULL : AA_OK;
+  }
+  g_hook_before = static_cast<hipEvent_t>(event_before);
+  g_hook_after = static_cast<hipEvent_t>(event_after);
+  g_hook_armed = true;
+  return AA_OK;
+}
+
+int32_t aa_workspace_init(void *ws, size_t ws_bytes, void *stream) {
+  if (int32_t rc = check_ws(ws, ws_bytes, kWsBody)) return rc;
+  hipLaunchKernelGGL(k_zero_i32, dim3(1), dim3(64), 0, as_stream(stream),
+                     reinterpret_cast<int32_t *>(ws), 64);
+  return hip_status(hipGetLastError());
+}
+
+int32_t aa_assistant_score(const aa_features *F, const int32_t *idx, int32_t P, const float *phi,
+                           const float *bias, float *logit, float *prob, void *stream) {
+  if (P < 0) return AA_ERR_SHAPE;
+  if (P == 0) return AA_OK;
+  if (int32_t rc = check_features(F)) return rc;
+  if (!phi || !prob) return AA_ERR_NULL;
+  PassSpec s{};
+  s.F = F;
+  s.mode = kPool;
+  s.rows = idx;
+  s.count_max = P;
+  s.phi = const_cast<float *>(phi);
+  s.bias = const_cast<float *>(bias);
+  s.logit = logit;
+  s.prob = prob;
+  Ws none{};
+  int32_t nblk = 0;
+  return hip_status(run_pass(s, none, &nblk, as_stream(stream)));
+}
+
+int32_t aa_shrink(const float *prob, int32_t P, float gamma, uint64_t seed, uint64_t step,
+                  uint8_t *keep, int32_t *kept_pos, int32_t *kept_count, void *ws_ptr,
+                  size_t ws_bytes, void *stream) {
+  if (P < 0) return AA_ERR_SHAPE;
+  if (!kept_count) return AA_ERR_NULL;
+  if (P > 0 && (!prob || !kept_pos)) return AA_ERR_NULL;
+  Ws ws = carve(ws_ptr, 0, P);
+  if (int32_t rc = check_ws(ws_ptr, ws_bytes, ws.total)) return rc;
+  KeepArgs k{};
+  k.src = prob;
+  k.P = P;
+  k.gamma = gamma;
+  k.one_minus_gamma = 1.0f - gamma;
+  k.key = make_draw_key(seed, step);
+  k.flags = keep ? keep : ws.flags;
+  k.blk_off = ws.blk_off;
+  k.kept_count = kept_count;
+  k.ticket = ws.tickets + kTicketKeep;
+  hipError_t e = launch_keep_count(k, kFromProb, as_stream(stream));
+  if (e != hipSuccess) return AA_ERR_HIP;
+  ScatterArgs sc{k.flags, P, ws.blk_off, kept_pos};
+  return hip_status(launch_scatter(sc, as_stream(stream)));
+}
+
+int32_t aa_shrink_threshold(const float *crit, int32_t P, const float *T, uint8_t *keep,
+                            int32_t *kept_pos, int32_t *kept_count, void *ws_ptr,
+                            size_t ws_bytes, void *stream) {
+  if (P < 0) return AA_ERR_SHAPE;
+  if (!kept_count || !T) return AA_ERR_NULL;
+  if (P > 0 && (!crit || !kept_pos)) return AA_ERR_NULL;
+  Ws ws = carve(ws_ptr, 0, P);
+  if (int32_t rc = check_ws(ws_ptr, ws_bytes, ws.total)) return rc;
+  KeepArgs k{};
+  k.src = crit;
+  k.T = T;
+  k.P = P;
+  k.flags = keep ? keep : ws.flags;
+  k.blk_off = ws.blk_off;
+  k.kept_count = kept_count;
+  k.ticket = ws.tickets + kTicketKeep;
+  hipError_t e = launch_keep_count(k, kFromCrit, as_stream(stream));
+  if (e != hipSuccess) return AA_ERR_HIP;
+  ScatterArgs sc{k.flags, P, ws.blk_off, kept_pos};
+  return hip_status(launch_scatter(sc, as_stream(stream)));
+}
+
+int32_t aa_score_shrink(const aa_features *F, const int32_t *idx, int32_t P, const float *phi,
+                        const float *bias, float gamma, uint64_t seed, uint64_t step,
+                        float *logit, float *prob, uint8_t *keep, int32_t *kept_pos,
+                        int32_t *kept_count, void *ws_ptr, size_t ws_bytes, void *stream) {
+  if (P < 0) return AA_ERR_SHAPE;
+  if (!kept_count) return AA_ERR_NULL;
+  Ws ws = carve(ws_ptr, 0, P);
+  if (int32_t rc = check_ws(ws_ptr, ws_bytes, ws.total)) return rc;
+  if (P == 0) {
+    KeepArgs k{};
+    k.kept_count = kept_count;
+    return hip_status(launch_keep_count(k, kFromProb, as_stream(stream)));
+  }
+  if (int32_t rc = check_features(F)) return rc;
+  if (!phi || !kept_pos) return AA_ERR_NULL;
+  PassSpec s{};
+  s.F = F;
+  s.mode = kPool;
+  s.rows = idx;
+  s.count_max = P;
+  s.phi = const_cast<float *>(phi);
+  s.bias = const_cast<float *>(bias);
+  s.gamma = gamma;
+  s.seed = seed;
+  s.step = step;
+  s.do_keep = 1;
+  s.logit = logit;
+  s.prob = prob;
+  s.flags = keep ? keep : ws.flags;
+  s.tail_compact = 1;
+  s.kept_pos = kept_pos;
+  s.kept_count = kept_count;
+  int32_t nblk = 0;
+  return hip_status(run_pass(s, ws, &nblk, as_stream(stream)));
+}
+
+int32_t aa_gather(const void *src, int64_t row_bytes, const int32_t *idx, const int32_t *kept_pos,
+                  const int32_t *kept_count, int32_t max_rows, void *dst, int32_t *kept_ids,
+                  void *stream) {
+  if (max_rows < 0 || row_bytes < 0) return AA_ERR_SHAPE;
+  if (!kept_count) return AA_ERR_NULL;
+  if ((src == nullptr) != (dst == nullptr)) return AA_ERR_NULL;
+  GatherArgs g{};
+  g.src = static_cast<const char *>(src);
+  g.dst = static_cast<char *>(dst);
+  g.row_bytes = row_bytes;
+  g.idx = idx;
+  g.kept_pos = kept_pos;
+  g.kept_count = kept_count;
+  g.max_rows = max_rows;
+  g.kept_ids = kept_ids;
+  return hip_status(launch_gather(g, as_stream(stream)));
+}
+
+int32_t aa_gather_csr(const aa_features *F, const int32_t *idx, const int32_t *kept_pos,
+                      const int32_t *kept_count, int32_t max_rows, int64_t *out_rowptr,
+                      int32_t *out_col, float *out_val, int64_t out_nnz_cap, void *ws_ptr,
+                      size_t ws_bytes, void *stream) {
+  (void)ws_ptr;
+  (void)ws_bytes;
+  if (max_rows < 0 || out_nnz_cap < 0) return AA_ERR_SHAPE;
+  if (int32_t rc = check_features(F)) return rc;
+  if (F->layout != AA_CSR) return AA_ERR_SHAPE;
+  if (!kept_count || !out_rowptr) return AA_ERR_NULL;
+  if (out_nnz_cap > 0 && !out_col) return AA_ERR_NULL;
+  if (F->val && out_nnz_cap > 0 && !out_val) return AA_ERR_NULL;
+  GatherCsrArgs g{};
+  g.rowptr = F->rowptr;
+  g.col = F->col;
+  g.val = F->val;
+  g.idx = idx;
+  g.kept_pos = kept_pos;
+  g.kept_count = kept_count;
+  g.max_rows = max_rows;
+  g.out_rowptr = out_rowptr;
+  g.out_col = out_col;
+  g.out_val = out_val;
+  g.out_nnz_cap = out_nnz_cap;
+  return hip_status(launch_gather_csr(g, as_stream(stream)));
+}
+
+int32_t aa_svm_sgd_step(const aa_features *F, const float *y, const int32_t *rows,
+                        const int32_t *m_dev, int32_t m_max, float *w, float lambda, float lr,
+                        float radius, float *loss, void *ws_ptr, size_t ws_bytes, void *stream) {
+  if (m_max < 0) return AA_ERR_SHAPE;
+  if (m_max == 0) return AA_OK;
+  if (int32_t rc = check_features(F)) return rc;
+  if (!y || !w || !m_dev) return AA_ERR_NULL;
+  PassSpec s{};
+  s.F = F;
+  s.mode = kSvm;
+  s.y = y;
+  s.rows = rows;
+  s.count_max = m_max;
+  s.m_dev = m_dev;
+  s.w = w;
+  s.loss_out = loss;
+  Ws ws = carve(ws_ptr, grad_bytes_for(s), 0);
+  if (int32_t rc = check_ws(ws_ptr, ws_bytes, ws.total)) return rc;
+  int32_t nblk = 0;
+  hipStream_t st = as_stream(stream);
+  if (run_pass(s, ws, &nblk, st) != hipSuccess) return AA_ERR_HIP;
+  UpdateSpec u{};
+  u.lambda = lambda;
+  u.lr = lr;
+  if (run_update(s, u, ws, nblk, st) != hipSuccess) return AA_ERR_HIP;
+  if (radius > 0.f) {
+    hipLaunchKernelGGL(k_project, dim3(1), dim3(1024), 0, st, w, F->d, radius, m_dev);
+    return hip_status(hipGetLastError());
+  }
+  return AA_OK;
+}
+
+int32_t aa_assistant_update(const aa_features *F, const int32_t *rows, const int32_t *m_dev,
+                            int32_t m_max, const float *loss, const float *T, float *phi,
+                            float *bias, float lr_a, float l2_a, void *ws_ptr, size_t ws_bytes,
+                            void *stream) {
+  if (m_max < 0) return AA_ERR_SHAPE;
+  if (m_max == 0) return AA_OK;
+  if (int32_t rc = check_features(F)) return rc;
+  if (!loss || !T || !phi || !m_dev) return AA_ERR_NULL;
+  PassSpec s{};
+  s.F = F;
+  s.mode = kAssist;
+  s.rows = rows;
+  s.count_max = m_max;
+  s.m_dev = m_dev;
+  s.phi = phi;
+  s.bias = bias;
+  s.T = T;
+  s.loss_in = loss;
+  Ws ws = carve(ws_ptr, grad_bytes_for(s), 0);
+  if (int32_t rc = check_ws(ws_ptr, ws_bytes, ws.total)) return rc;
+  int32_t nblk = 0;
+  hipStream_t st = as_stream(stream);
+  if (run_pass(s, ws, &nblk, st) != hipSuccess) return AA_ERR_HIP;
+  UpdateSpec u{};
+  u.lr_a = lr_a;
+  u.l2_a = l2_a;
+  return hip_status(run_update(s, u, ws, nblk, st));
+}
+
+int32_t aa_boss_assistant_step(const aa_features *F, const float *y, const int32_t *rows,
+                               const int32_t *m_dev, int32_t m_max, float *w, float *phi,
+                               float *bias, const aa_step_config *cfg, float *loss, void *ws_ptr,
+                               size_t ws_bytes, void *stream) {
+  if (m_max < 0) return AA_ERR_SHAPE;
+  if (m_max == 0) return AA_OK;
+  if (int32_t rc = check_features(F)) return rc;
+  if (!y || !w || !phi || !cfg || !cfg->T || !m_dev) return AA_ERR_NULL;
+  PassSpec s{};
+  s.F = F;
+  s.mode = kSvm | kAssist;
+  s.y = y;
+  s.rows = rows;
+  s.count_max = m_max;
+  s.m_dev = m_dev;
+  s.w = w;
+  s.phi = phi;
+  s.bias = bias;
+  s.T = cfg->T;
+  s.loss_out = loss;
+  Ws ws = carve(ws_ptr, grad_bytes_for(s), 0);
+  if (int32_t rc = check_ws(ws_ptr, ws_bytes, ws.total)) return rc;
+  int32_t nblk = 0;
+  hipStream_t st = as_stream(stream);
+  if (run_pass(s, ws, &nblk, st) != hipSuccess) return AA_ERR_HIP;
+  UpdateSpec u{};
+  u.lambda = cfg->lambda;
+  u.lr = cfg->lr;
+  u.lr_a = cfg->lr_a;
+  u.l2_a = cfg->l2_a;
+  return hip_status(run_update(s, u, ws, nblk, st));
+}
+
+int32_t aa_fused_step(const aa_features *F, const float *y, const int32_t *idx, int32_t P,
+                      float *w, float *phi, float *bias, const aa_step_config *cfg, float *logit,
+                      float *prob, uint8_t *keep, int32_t *kept_pos, int32_t *kept_ids,
+                      float *loss, int32_t *kept_count, void *ws, size_t ws_bytes, void *stream) {
+  if (P < 0) return AA_ERR_SHAPE;
+  if (!kept_count) return AA_ERR_NULL;
+  if (P == 0) {
+    KeepArgs k{};
+    k.kept_count = kept_count;
+    return hip_status(launch_keep_count(k, kFromProb, as_stream(stream)));
+  }
+  if (int32_t rc = check_features(F)) return rc;
+  if (!y || !w || !phi || !cfg || !cfg->T) return AA_ERR_NULL;
+  return fused_step_impl(F, y, idx, P, w, phi, bias, cfg, cfg->step, logit, prob, keep, kept_pos,
+                         kept_ids, loss, kept_count, nullptr, nullptr, false, ws, ws_bytes,
+                         as_stream(stream));
+}
+
+int32_t aa_train_epoch(const aa_features *F, const float *y, const int32_t *perm, int64_t n_perm,
+                       int32_t P, float *w, float *phi, float *bias, const aa_step_config *cfg,
+                       int32_t *t_upd, int32_t *kept_hist, void *ws, size_t ws_bytes,
+                       void *stream) {
+  if (P <= 0 || n_perm < 0) return AA_ERR_SHAPE;
+  if (n_perm == 0) return AA_OK;
+  if (int32_t rc = check_features(F)) return rc;
+  if (!y || !w || !phi || !cfg || !cfg->T || !perm) return AA_ERR_NULL;
+  const int64_t steps = (n_perm + P - 1) / P;
+  for (int64_t t = 0; t < steps; ++t) {
+    const int64_t lo = t * P;
+    const int32_t Pt = (int32_t)((n_perm - lo) < P ? (n_perm - lo) : P);
+    const int32_t rc = fused_step_impl(F, y, perm + lo, Pt, w, phi, bias, cfg, cfg->step + t,
+                                       nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+                                       nullptr, t_upd, kept_hist ? kept_hist + t : nullptr, true,
+                                       ws, ws_bytes, as_stream(stream));
+    if (rc != AA_OK) return rc;
+  }
+  return AA_OK;
+}
+
+}  // extern "C"

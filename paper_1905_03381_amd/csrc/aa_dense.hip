@@ -1,0 +1,471 @@
+// Dense row passes for gfx950 with the model vectors held in registers.
+//
+// One wave64 (or an aligned group of LPR lanes for short rows) owns a feature
+// row: each lane loads VPL 128-bit pieces, so a wave-wide load instruction
+// covers 1 KiB of contiguous row.  phi and w sit in registers for the whole
+// kernel, dot products are folded with wave shuffles, and the gradient sums of
+// the kept rows accumulate per lane before one LDS tree per block.  Waves own
+// contiguous chunks of the pool, so row ids, labels and the Philox draws are
+// produced 64 at a time, one per lane, and broadcast per row.
+#include "aa_compact.hpp"
+#include "aa_dense.hpp"
+
+namespace aa {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+__device__ __forceinline__ float dot4(const f4 a, const f4 b, float acc) {
+  acc = __fmaf_rn(a.x, b.x, acc);
+  acc = __fmaf_rn(a.y, b.y, acc);
+  acc = __fmaf_rn(a.z, b.z, acc);
+  acc = __fmaf_rn(a.w, b.w, acc);
+  return acc;
+}
+
+__device__ __forceinline__ f4 axpy4(const float s, const f4 x, f4 acc) {
+  acc.x = __fmaf_rn(s, x.x, acc.x);
+  acc.y = __fmaf_rn(s, x.y, acc.y);
+  acc.z = __fmaf_rn(s, x.z, acc.z);
+  acc.w = __fmaf_rn(s, x.w, acc.w);
+  return acc;
+}
+
+__device__ __forceinline__ int wave_sum_int(int v) {
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+  return v;
+}
+
+// Fold the row groups of a wave, then the waves of the block (LDS tree, fixed
+// order), and let wave 0 store the block's partial vector.
+template <int LPR, int VPL>
+__device__ __forceinline__ void block_reduce_store(f4 (&acc)[VPL], f4 *red, float *out, int lane,
+                                                   int wave, int nw) {
+  constexpr int ROW4 = LPR * VPL;
+  if (LPR < kWave) {
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) {
+      acc[v].x = fold_groups<LPR>(acc[v].x);
+      acc[v].y = fold_groups<LPR>(acc[v].y);
+      acc[v].z = fold_groups<LPR>(acc[v].z);
+      acc[v].w = fold_groups<LPR>(acc[v].w);
+    }
+  }
+  for (int s = nw >> 1; s >= 1; s >>= 1) {
+    if (wave >= s && wave < 2 * s && lane < LPR) {
+#pragma unroll
+      for (int v = 0; v < VPL; ++v) red[(wave - s) * ROW4 + v * LPR + lane] = acc[v];
+    }
+    __syncthreads();
+    if (wave < s && lane < LPR) {
+#pragma unroll
+      for (int v = 0; v < VPL; ++v) acc[v] += red[wave * ROW4 + v * LPR + lane];
+    }
+    __syncthreads();
+  }
+  if (wave == 0 && lane < LPR) {
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) reinterpret_cast<f4 *>(out)[v * LPR + lane] = acc[v];
+  }
+}
+
+template <int LPR, int VPL, int MODE, int NWMAX>
+__global__ __launch_bounds__(NWMAX * 64) void k_rows_pass(const PassArgs a) {
+  constexpr bool POOL = (MODE & kPool) != 0;
+  constexpr bool SVM = (MODE & kSvm) != 0;
+  constexpr bool ASSIST = (MODE & kAssist) != 0;
+  constexpr bool GRAD = SVM || ASSIST;
+  constexpr bool NEED_PHI = POOL || ASSIST;
+  constexpr int G = kWave / LPR;  // rows per wave iteration
+  constexpr int ROW4 = LPR * VPL;
+  constexpr int NVEC = (SVM ? 1 : 0) + (ASSIST ? 1 : 0);
+
+  __shared__ int s_int[40];
+  __shared__ float s_flt[20];
+  __shared__ f4 s_red[GRAD ? (NWMAX / 2) * ROW4 : 1];
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  const int grp = lane / LPR, sub = lane % LPR;
+
+  int total = a.count_max;
+  if (!POOL && a.m_dev) total = min(max(*a.m_dev, 0), a.count_max);
+
+  // balanced contiguous chunk of rows for this wave
+  const int nwaves = gridDim.x * nw, gwave = blockIdx.x * nw + wave;
+  const int per = total / nwaves, rem = total % nwaves;
+  const int lo = gwave * per + min(gwave, rem);
+  const int hi = lo + per + (gwave < rem ? 1 : 0);
+
+  f4 wv[VPL], pv[VPL], gw[VPL], gp[VPL];
+#pragma unroll
+  for (int v = 0; v < VPL; ++v) {
+    const int c = v * LPR + sub;
+    const bool ok = c < a.d4;
+    const f4 zero = {0.f, 0.f, 0.f, 0.f};
+    wv[v] = (SVM && ok) ? reinterpret_cast<const f4 *>(a.w)[c] : zero;
+    pv[v] = (NEED_PHI && ok) ? reinterpret_cast<const f4 *>(a.phi)[c] : zero;
+    gw[v] = zero;
+    gp[v] = zero;
+  }
+  const float b = (NEED_PHI && a.bias) ? *a.bias : 0.f;
+  const float T = ASSIST ? *a.T : 0.f;
+  float gb = 0.f;
+  int kept = 0;
+
+  for (int base = lo; base < hi; base += kWave) {
+    const int cnt = min(kWave, hi - base);
+    // one row per lane: id, label, draw
+    const int j_l = base + lane;
+    int row_l = 0;
+    float y_l = 0.f, u_l = 2.f, lin_l = 0.f;
+    if (lane < cnt) {
+      row_l = a.rows ? a.rows[j_l] : j_l;
+      if (SVM) y_l = a.y[row_l];
+      if (POOL && a.do_keep) u_l = keep_uniform(a.key, (uint32_t)j_l);
+      if (ASSIST && !SVM) lin_l = a.loss_in[j_l];
+    }
+    const int iters = (cnt + G - 1) / G;
+    f4 xa[VPL], xb[VPL];
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) xb[v] = f4{0.f, 0.f, 0.f, 0.f};
+    auto load = [&](int it, f4(&buf)[VPL]) {
+      const int li = it * G + grp;
+      const int row = __shfl(row_l, li, kWave);
+      const f4 *xr = reinterpret_cast<const f4 *>(a.x + (int64_t)row * a.ld);
+#pragma unroll
+      for (int v = 0; v < VPL; ++v) {
+        const int c = v * LPR + sub;
+        const f4 zero = {0.f, 0.f, 0.f, 0.f};
+        buf[v] = (li < cnt && c < a.d4) ? __builtin_nontemporal_load(xr + c) : zero;
+      }
+    };
+    load(0, xa);
+    for (int it = 0; it < iters; ++it) {
+      if (it + 1 < iters) load(it + 1, xb);
+      const int li = it * G + grp;
+      const bool live = li < cnt;
+      const int j = base + li;
+      float g = 0.f;
+      bool keep = live;
+      if (NEED_PHI) {
+        float dp = 0.f;
+#pragma unroll
+        for (int v = 0; v < VPL; ++v) dp = dot4(xa[v], pv[v], dp);
+        dp = group_sum<LPR>(dp);
+        const float s = dp + b;
+        g = sigmoidf_(s);
+        if (POOL) {
+          const float u = __shfl(u_l, li, kWave);
+          if (a.do_keep) keep = live && keep_decision(u, g, a.gamma, a.one_minus_gamma);
+          if (sub == 0 && live) {
+            if (a.logit) a.logit[j] = s;
+            if (a.prob) a.prob[j] = g;
+            if (a.flags) a.flags[j] = keep ? 1 : 0;
+          }
+        }
+      }
+      if (GRAD) {
+        const float yy = SVM ? __shfl(y_l, li, kWave) : 0.f;
+        const float lin = (ASSIST && !SVM) ? __shfl(lin_l, li, kWave) : 0.f;
+        bool any = true;
+        if (LPR == kWave) any = __builtin_amdgcn_readfirstlane((int)keep) != 0;
+        if (any) {
+          float loss = lin;
+          if (SVM) {
+            float dw = 0.f;
+#pragma unroll
+            for (int v = 0; v < VPL; ++v) dw = dot4(xa[v], wv[v], dw);
+            dw = group_sum<LPR>(dw);
+            const float marg = yy * dw;
+            loss = fmaxf(0.f, 1.f - marg);
+            if (sub == 0 && keep && a.loss_out) a.loss_out[j] = loss;
+            const float cw = (keep && marg < 1.f) ? yy : 0.f;  // -d hinge / d margin, times y
+#pragma unroll
+            for (int v = 0; v < VPL; ++v) gw[v] = axpy4(cw, xa[v], gw[v]);
+          }
+          if (ASSIST) {
+            const float z = loss > T ? 1.f : 0.f;       // label: Boss loss above the threshold
+            const float resid = keep ? g - z : 0.f;     // d cross-entropy / d logit
+#pragma unroll
+            for (int v = 0; v < VPL; ++v) gp[v] = axpy4(resid, xa[v], gp[v]);
+            if (sub == 0) gb += resid;
+          }
+          if (sub == 0 && keep) kept += 1;
+        }
+      }
+#pragma unroll
+      for (int v = 0; v < VPL; ++v) xa[v] = xb[v];
+    }
+  }
+
+  if (GRAD) {
+    float *part = a.partial + (size_t)blockIdx.x * NVEC * (ROW4 * 4);
+    if (SVM) block_reduce_store<LPR, VPL>(gw, s_red, part, lane, wave, nw);
+    if (ASSIST) block_reduce_store<LPR, VPL>(gp, s_red, part + (SVM ? ROW4 * 4 : 0), lane, wave, nw);
+    const int kw = wave_sum_int(kept);
+    const float gbw = group_sum<kWave>(gb);
+    if (lane == 0) {
+      s_int[wave] = kw;
+      s_flt[wave] = gbw;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      int ks = 0;
+      float gs = 0.f;
+      for (int i = 0; i < nw; ++i) {
+        ks += s_int[i];
+        gs += s_flt[i];
+      }
+      a.blk_cnt[blockIdx.x] = ks;
+      a.blk_gb[blockIdx.x] = gs;
+    }
+  }
+  if (POOL && !GRAD) {
+    if (a.tail_compact) {
+      if (last_block_arrives(a.ticket, &s_int[32])) {
+        CompactArgs c;
+        c.flags = a.flags;
+        c.P = a.count_max;
+        c.idx = nullptr;
+        c.kept_pos = a.kept_pos;
+        c.kept_ids = nullptr;
+        c.loss_pool = nullptr;
+        c.loss = nullptr;
+        c.kept_count = a.kept_count;
+        block_compact(c, s_int);
+      }
+    }
+  }
+}
+
+// Sum the block partials in a fixed order and apply the SGD updates; one extra
+// block compacts the keep flags of a pool pass.
+__global__ __launch_bounds__(256) void k_finalize(const FinalizeArgs a) {
+  __shared__ f4 s_acc[2][16][16];
+  __shared__ int s_int[40];
+  __shared__ float s_flt[8];
+  const int tid = threadIdx.x;
+  const int nred = a.d_pad / 64;
+
+  if ((int)blockIdx.x >= nred) {
+    CompactArgs c;
+    c.flags = a.flags;
+    c.P = a.P;
+    c.idx = a.idx;
+    c.kept_pos = a.kept_pos;
+    c.kept_ids = a.kept_ids;
+    c.loss_pool = a.loss_pool;
+    c.loss = a.loss;
+    c.kept_count = a.kept_count;
+    block_compact(c, s_int);
+    return;
+  }
+
+  // kept count m
+  int m;
+  if (a.m_dev) {
+    m = min(max(*a.m_dev, 0), a.m_max);
+  } else {
+    int part = 0;
+    for (int i = tid; i < a.nblk; i += blockDim.x) part += a.blk_cnt[i];
+    part = wave_sum_int(part);
+    if ((tid & 63) == 0) s_int[tid >> 6] = part;
+    __syncthreads();
+    m = s_int[0] + s_int[1] + s_int[2] + s_int[3];
+    __syncthreads();
+  }
+
+  // step size: constant, or lr / sqrt(number of updates made so far)
+  int t_new = 0;
+  float lr = a.lr;
+  if (a.t_upd) {
+    t_new = *a.t_upd + (m > 0 ? 1 : 0);
+    if (m > 0) lr = a.lr / sqrtf((float)t_new);
+  }
+
+  if (m > 0) {
+    const int c4 = tid & 15, pg = tid >> 4;
+    const int col4 = blockIdx.x * 16 + c4;
+    const int row4 = a.d_pad / 4;
+    const f4 zero = {0.f, 0.f, 0.f, 0.f};
+    f4 acc0 = zero, acc1 = zero;
+    const f4 *p = reinterpret_cast<const f4 *>(a.partial);
+    if (a.nvec == 2) {
+#pragma unroll 4
+      for (int blk = pg; blk < a.nblk; blk += 16) {
+        acc0 += p[(size_t)(blk * 2) * row4 + col4];
+        acc1 += p[(size_t)(blk * 2 + 1) * row4 + col4];
+      }
+    } else {
+#pragma unroll 4
+      for (int blk = pg; blk < a.nblk; blk += 16) acc0 += p[(size_t)blk * row4 + col4];
+    }
+    s_acc[0][pg][c4] = acc0;
+    s_acc[1][pg][c4] = acc1;
+    __syncthreads();
+    if (pg == 0) {
+      f4 g0 = zero, g1 = zero;
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        g0 += s_acc[0][q][c4];
+        g1 += s_acc[1][q][c4];
+      }
+      const float inv_m = 1.f / (float)m;
+      const f4 gw = g0;
+      const f4 gp = a.w ? g1 : g0;
+      const int k0 = col4 * 4;
+      if (a.w) {
+        const float shrink = 1.f - lr * a.lambda;
+        const float scale = lr * inv_m;
+        const float gv[4] = {gw.x, gw.y, gw.z, gw.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (k0 + i < a.d) a.w[k0 + i] = __fmaf_rn(scale, gv[i], shrink * a.w[k0 + i]);
+      }
+      if (a.phi) {
+        const float gv[4] = {gp.x, gp.y, gp.z, gp.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (k0 + i < a.d) {
+            const float ph = a.phi[k0 + i];
+            a.phi[k0 + i] = ph - a.lr_a * __fmaf_rn(a.l2_a, ph, gv[i] * inv_m);
+          }
+      }
+    }
+    if (blockIdx.x == 0 && a.phi && a.bias) {
+      // bias gradient: fixed-order tree over the block partials
+      float part = 0.f;
+      for (int i = tid; i < a.nblk; i += blockDim.x) part += a.blk_gb[i];
+      part = group_sum<kWave>(part);
+      if ((tid & 63) == 0) s_flt[tid >> 6] = part;
+      __syncthreads();
+      if (tid == 0) {
+        const float gb = (s_flt[0] + s_flt[1]) + (s_flt[2] + s_flt[3]);
+        *a.bias = *a.bias - a.lr_a * (gb / (float)m);
+      }
+    }
+  }
+  if (blockIdx.x == 0 && tid == 0 && a.kept_hist) *a.kept_hist = m;
+
+  if (a.t_upd) {
+    // every reducing block has read *t_upd before the last arrival rewrites it
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+      const int prev = atomicAdd(a.ticket, 1);
+      if (prev == nred - 1) {
+        *a.ticket = 0;
+        *a.t_upd = t_new;
+      }
+    }
+  }
+}
+
+int g_num_cu = 0;
+
+int num_cu() {
+  if (g_num_cu == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+      g_num_cu = prop.multiProcessorCount;
+    if (g_num_cu <= 0) g_num_cu = 256;
+  }
+  return g_num_cu;
+}
+
+struct Shape {
+  int lpr, vpl;
+};
+
+Shape pick_shape(int32_t d) {
+  const int d4 = (d + 3) / 4;
+  if (d4 <= 16) return {16, 1};
+  if (d4 <= 32) return {32, 1};
+  if (d4 <= 64) return {64, 1};
+  if (d4 <= 128) return {64, 2};
+  if (d4 <= 256) return {64, 4};
+  return {64, 8};
+}
+
+int waves_per_block(const Shape &s, int mode) {
+  const bool grad = (mode & (kSvm | kAssist)) != 0;
+  if (!grad) return 4;
+  return s.vpl == 8 ? 8 : 16;
+}
+
+template <int LPR, int VPL, int NWMAX>
+hipError_t launch_mode(const PassArgs &a, int mode, int nblk, int nw, hipStream_t st) {
+  const dim3 grid(nblk), block(nw * 64);
+  switch (mode) {
+    case kPool:
+      hipLaunchKernelGGL((k_rows_pass<LPR, VPL, kPool, NWMAX>), grid, block, 0, st, a);
+      break;
+    case kSvm:
+      hipLaunchKernelGGL((k_rows_pass<LPR, VPL, kSvm, NWMAX>), grid, block, 0, st, a);
+      break;
+    case kAssist:
+      hipLaunchKernelGGL((k_rows_pass<LPR, VPL, kAssist, NWMAX>), grid, block, 0, st, a);
+      break;
+    case kSvm | kAssist:
+      hipLaunchKernelGGL((k_rows_pass<LPR, VPL, kSvm | kAssist, NWMAX>), grid, block, 0, st, a);
+      break;
+    case kPool | kSvm | kAssist:
+      hipLaunchKernelGGL((k_rows_pass<LPR, VPL, kPool | kSvm | kAssist, NWMAX>), grid, block, 0,
+                         st, a);
+      break;
+    default:
+      return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool dense_fast_ok(const aa_features *F) {
+  return F->layout == AA_DENSE && F->d % 4 == 0 && F->d <= kFastDenseMaxD && F->ld % 4 == 0 &&
+         (reinterpret_cast<uintptr_t>(F->x) & 15) == 0;
+}
+
+int32_t dense_d_pad(int32_t d) {
+  const Shape s = pick_shape(d);
+  return s.lpr * s.vpl * 4;
+}
+
+int32_t dense_pass_blocks(int32_t d, int32_t count, int mode) {
+  const Shape s = pick_shape(d);
+  const int nw = waves_per_block(s, mode);
+  const int rows_per_block = nw * (kWave / s.lpr);
+  const bool grad = (mode & (kSvm | kAssist)) != 0;
+  int64_t want = ((int64_t)count + rows_per_block - 1) / rows_per_block;
+  const int64_t cap = grad ? num_cu() : (int64_t)num_cu() * 8;
+  if (want > cap) want = cap;
+  if (want > kMaxBlocks) want = kMaxBlocks;
+  if (want < 1) want = 1;
+  return (int32_t)want;
+}
+
+hipError_t launch_dense_pass(const PassArgs &a, int mode, int32_t d, int32_t nblk,
+                             hipStream_t st) {
+  const Shape s = pick_shape(d);
+  const int nw = waves_per_block(s, mode);
+  if (s.lpr == 16) return launch_mode<16, 1, 16>(a, mode, nblk, nw, st);
+  if (s.lpr == 32) return launch_mode<32, 1, 16>(a, mode, nblk, nw, st);
+  switch (s.vpl) {
+    case 1: return launch_mode<64, 1, 16>(a, mode, nblk, nw, st);
+    case 2: return launch_mode<64, 2, 16>(a, mode, nblk, nw, st);
+    case 4: return launch_mode<64, 4, 16>(a, mode, nblk, nw, st);
+    default: return launch_mode<64, 8, 8>(a, mode, nblk, nw, st);
+  }
+}
+
+hipError_t launch_dense_finalize(const FinalizeArgs &a, hipStream_t st) {
+  const int nred = a.d_pad / 64;
+  const int extra = a.flags ? 1 : 0;
+  hipLaunchKernelGGL(k_finalize, dim3(nred + extra), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace aa

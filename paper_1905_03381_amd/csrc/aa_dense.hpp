@@ -1,0 +1,81 @@
+// Host-side launch interface of the dense register-resident row passes.
+#pragma once
+
+#include "aa_common.hpp"
+
+namespace aa {
+
+enum : int { kSvm = 1, kAssist = 2, kPool = 4 };
+
+// One pass over feature rows.  In pool mode (kPool) the pass walks the candidate
+// pool: score, keep draw and -- with kSvm|kAssist -- both gradient sums of the
+// kept rows.  Without kPool it walks rows already chosen (kept ids).
+struct PassArgs {
+  const float *x;
+  int64_t ld;
+  int32_t d4;             // d / 4
+  const float *y;         // labels indexed by data-set row (kSvm)
+  const int32_t *rows;    // pool ids idx[P] or kept ids rows[m]; NULL = 0..count-1
+  int32_t count_max;      // P (pool) or m_max (kept)
+  const int32_t *m_dev;   // device row count for kept mode (NULL in pool mode)
+  const float *w;
+  const float *phi;
+  const float *bias;      // device scalar or NULL
+  const float *T;         // device scalar (kAssist)
+  float gamma, one_minus_gamma;
+  DrawKey key;
+  int32_t do_keep;        // pool mode: draw keep flags
+  float *logit;           // pool outputs (may be NULL)
+  float *prob;
+  uint8_t *flags;         // pool: keep flags [P]
+  float *loss_out;        // kSvm: loss per position (pool) or per row (kept); may be NULL
+  const float *loss_in;   // kAssist without kSvm: Boss losses per row
+  float *partial;         // [nblk][nvec][d_pad]
+  int32_t *blk_cnt;       // [nblk] kept count per block (pool mode)
+  float *blk_gb;          // [nblk] bias-gradient partial (kAssist)
+  // tail compaction by the last block (pool mode without gradients)
+  int32_t tail_compact;
+  int32_t *kept_pos;
+  int32_t *kept_count;
+  int32_t *ticket;
+};
+
+struct FinalizeArgs {
+  const float *partial;
+  int32_t nblk, nvec, d, d_pad;
+  const int32_t *blk_cnt;  // pool mode: m = sum
+  const float *blk_gb;
+  const int32_t *m_dev;    // kept mode: m = min(*m_dev, m_max)
+  int32_t m_max;
+  float *w;                // updated if non-NULL (vector 0)
+  float *phi;              // updated if non-NULL (next vector)
+  float *bias;
+  float lambda, lr, lr_a, l2_a;
+  int32_t *t_upd;          // optional device update counter driving lr/sqrt(t)
+  int32_t *kept_hist;      // optional: receives m
+  int32_t *ticket;
+  // optional compaction block (pool mode)
+  const uint8_t *flags;
+  int32_t P;
+  const int32_t *idx;
+  int32_t *kept_pos;
+  int32_t *kept_ids;
+  const float *loss_pool;
+  float *loss;
+  int32_t *kept_count;
+};
+
+// True if the register-resident kernels can take this feature matrix.
+bool dense_fast_ok(const aa_features *F);
+
+// Padded width (floats) of one gradient partial for dimension d.
+int32_t dense_d_pad(int32_t d);
+
+// Number of blocks the pass will use for `count` rows of dimension d.
+int32_t dense_pass_blocks(int32_t d, int32_t count, int mode);
+
+hipError_t launch_dense_pass(const PassArgs &a, int mode, int32_t d, int32_t nblk,
+                             hipStream_t stream);
+hipError_t launch_dense_finalize(const FinalizeArgs &a, hipStream_t stream);
+
+}  // namespace aa

@@ -1,0 +1,250 @@
+// General row passes: CSR rows, and dense rows the register-resident kernels
+// cannot take (d > 2048, d % 4 != 0, unaligned).  A group of GL lanes walks the
+// stored entries of a row; phi and w are read through the caches (they are the
+// only reused data); gradient sums are scattered with fp32 atomics into dense
+// accumulators that a second kernel folds into the model.
+#include "aa_compact.hpp"
+#include "aa_general.hpp"
+
+namespace aa {
+
+namespace {
+
+template <int WIDTH>
+__device__ __forceinline__ float gsum(float v) {
+#pragma unroll
+  for (int off = WIDTH / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+  return v;
+}
+
+template <int GL, int MODE, bool CSR>
+__global__ __launch_bounds__(256) void k_rows_general(const GenArgs a) {
+  constexpr bool POOL = (MODE & kPool) != 0;
+  constexpr bool SVM = (MODE & kSvm) != 0;
+  constexpr bool ASSIST = (MODE & kAssist) != 0;
+  constexpr bool GRAD = SVM || ASSIST;
+  constexpr bool NEED_PHI = POOL || ASSIST;
+  constexpr int G = kWave / GL;
+  __shared__ int s_int[40];
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  const int grp = lane / GL, sub = lane % GL;
+
+  int total = a.count_max;
+  if (!POOL && a.m_dev) total = min(max(*a.m_dev, 0), a.count_max);
+  const int nwaves = gridDim.x * nw, gwave = blockIdx.x * nw + wave;
+  const int per = total / nwaves, rem = total % nwaves;
+  const int lo = gwave * per + min(gwave, rem);
+  const int hi = lo + per + (gwave < rem ? 1 : 0);
+
+  const float b = (NEED_PHI && a.bias) ? *a.bias : 0.f;
+  const float T = ASSIST ? *a.T : 0.f;
+  float gb = 0.f;
+  int kept = 0;
+
+  for (int base = lo; base < hi; base += kWave) {
+    const int cnt = min(kWave, hi - base);
+    const int j_l = base + lane;
+    int row_l = 0;
+    long long e0_l = 0;
+    int len_l = 0;
+    float y_l = 0.f, u_l = 2.f, lin_l = 0.f;
+    if (lane < cnt) {
+      row_l = a.rows ? a.rows[j_l] : j_l;
+      if (CSR) {
+        e0_l = a.rowptr[row_l];
+        len_l = (int)(a.rowptr[row_l + 1] - e0_l);
+      } else {
+        e0_l = (long long)row_l * a.ld;
+        len_l = a.d;
+      }
+      if (SVM) y_l = a.y[row_l];
+      if (POOL && a.do_keep) u_l = keep_uniform(a.key, (uint32_t)j_l);
+      if (ASSIST && !SVM) lin_l = a.loss_in[j_l];
+    }
+    const int iters = (cnt + G - 1) / G;
+    for (int it = 0; it < iters; ++it) {
+      const int li = it * G + grp;
+      const bool live = li < cnt;
+      const int j = base + li;
+      const long long e0 = __shfl(e0_l, li, kWave);
+      const int len = live ? __shfl(len_l, li, kWave) : 0;
+      const float u = __shfl(u_l, li, kWave);
+      const float yy = __shfl(y_l, li, kWave);
+      const float lin = __shfl(lin_l, li, kWave);
+      float dp = 0.f, dw = 0.f;
+      for (int e = sub; e < len; e += GL) {
+        const int c = CSR ? a.col[e0 + e] : e;
+        const float xv = CSR ? (a.val ? a.val[e0 + e] : 1.f) : a.x[e0 + e];
+        if (NEED_PHI) dp = __fmaf_rn(a.phi[c], xv, dp);
+        if (SVM) dw = __fmaf_rn(a.w[c], xv, dw);
+      }
+      float g = 0.f;
+      bool keep = live;
+      if (NEED_PHI) {
+        dp = gsum<GL>(dp);
+        const float s = dp + b;
+        g = sigmoidf_(s);
+        if (POOL) {
+          if (a.do_keep) keep = live && keep_decision(u, g, a.gamma, a.one_minus_gamma);
+          if (sub == 0 && live) {
+            if (a.logit) a.logit[j] = s;
+            if (a.prob) a.prob[j] = g;
+            if (a.flags) a.flags[j] = keep ? 1 : 0;
+          }
+        }
+      }
+      if (GRAD) {
+        float loss = lin;
+        float cw = 0.f, resid = 0.f;
+        if (SVM) {
+          dw = gsum<GL>(dw);
+          const float marg = yy * dw;
+          loss = fmaxf(0.f, 1.f - marg);
+          if (sub == 0 && keep && a.loss_out) a.loss_out[j] = loss;
+          cw = (keep && marg < 1.f) ? yy : 0.f;
+        }
+        if (ASSIST) {
+          const float z = loss > T ? 1.f : 0.f;
+          resid = keep ? g - z : 0.f;
+          if (sub == 0) gb += resid;
+        }
+        if (sub == 0 && keep) kept += 1;
+        if (cw != 0.f || resid != 0.f) {
+          for (int e = sub; e < len; e += GL) {
+            const int c = CSR ? a.col[e0 + e] : e;
+            const float xv = CSR ? (a.val ? a.val[e0 + e] : 1.f) : a.x[e0 + e];
+            if (SVM && cw != 0.f) unsafeAtomicAdd(a.acc_w + c, cw * xv);
+            if (ASSIST && resid != 0.f) unsafeAtomicAdd(a.acc_p + c, resid * xv);
+          }
+        }
+      }
+    }
+  }
+
+  if (GRAD) {
+    // scalars[0] = kept count (int), scalars[1] = bias gradient (float bits via atomics)
+    int kw = kept;
+    float gbw = gb;
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+      kw += __shfl_xor(kw, off, kWave);
+      gbw += __shfl_xor(gbw, off, kWave);
+    }
+    if (lane == 0) {
+      if (kw) atomicAdd(a.acc_cnt, kw);
+      if (ASSIST && gbw != 0.f) unsafeAtomicAdd(a.acc_gb, gbw);
+    }
+  }
+  if (POOL && !GRAD && a.tail_compact) {
+    if (last_block_arrives(a.ticket, &s_int[32])) {
+      CompactArgs c;
+      c.flags = a.flags;
+      c.P = a.count_max;
+      c.idx = nullptr;
+      c.kept_pos = a.kept_pos;
+      c.kept_ids = nullptr;
+      c.loss_pool = nullptr;
+      c.loss = nullptr;
+      c.kept_count = a.kept_count;
+      block_compact(c, s_int);
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void k_zero_f32(float *p, size_t count) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
+       i += (size_t)gridDim.x * blockDim.x)
+    p[i] = 0.f;
+}
+
+__global__ __launch_bounds__(256) void k_apply_general(const ApplyArgs a) {
+  __shared__ int s_int[40];
+  if (blockIdx.x == gridDim.x - 1 && a.flags) {
+    CompactArgs c;
+    c.flags = a.flags;
+    c.P = a.P;
+    c.idx = a.idx;
+    c.kept_pos = a.kept_pos;
+    c.kept_ids = a.kept_ids;
+    c.loss_pool = a.loss_pool;
+    c.loss = a.loss;
+    c.kept_count = a.kept_count;
+    block_compact(c, s_int);
+    return;
+  }
+  const int nb = (int)gridDim.x - (a.flags ? 1 : 0);
+  int m = a.m_dev ? min(max(*a.m_dev, 0), a.m_max) : *a.acc_cnt;
+  if (blockIdx.x == 0 && threadIdx.x == 0 && a.kept_hist) *a.kept_hist = m;
+  if (m <= 0) return;
+  const float inv_m = 1.f / (float)m;
+  const float shrink = 1.f - a.lr * a.lambda, scale = a.lr * inv_m;
+  for (int k = blockIdx.x * blockDim.x + threadIdx.x; k < a.d; k += nb * blockDim.x) {
+    if (a.w) a.w[k] = __fmaf_rn(scale, a.acc_w[k], shrink * a.w[k]);
+    if (a.phi) {
+      const float ph = a.phi[k];
+      a.phi[k] = ph - a.lr_a * __fmaf_rn(a.l2_a, ph, a.acc_p[k] * inv_m);
+    }
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0 && a.phi && a.bias)
+    *a.bias = *a.bias - a.lr_a * (*a.acc_gb * inv_m);
+}
+
+template <int GL, bool CSR>
+hipError_t launch_gl(const GenArgs &a, int mode, int nblk, hipStream_t st) {
+  const dim3 grid(nblk), block(256);
+  switch (mode) {
+    case kPool:
+      hipLaunchKernelGGL((k_rows_general<GL, kPool, CSR>), grid, block, 0, st, a);
+      break;
+    case kSvm:
+      hipLaunchKernelGGL((k_rows_general<GL, kSvm, CSR>), grid, block, 0, st, a);
+      break;
+    case kAssist:
+      hipLaunchKernelGGL((k_rows_general<GL, kAssist, CSR>), grid, block, 0, st, a);
+      break;
+    case kSvm | kAssist:
+      hipLaunchKernelGGL((k_rows_general<GL, kSvm | kAssist, CSR>), grid, block, 0, st, a);
+      break;
+    case kPool | kSvm | kAssist:
+      hipLaunchKernelGGL((k_rows_general<GL, kPool | kSvm | kAssist, CSR>), grid, block, 0, st, a);
+      break;
+    default:
+      return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace
+
+int32_t general_pass_blocks(int32_t count, bool csr) {
+  const int rows_per_block = 4 * (csr ? 4 : 1);
+  int64_t want = ((int64_t)count + rows_per_block - 1) / rows_per_block;
+  if (want > 256 * 8) want = 256 * 8;
+  if (want < 1) want = 1;
+  return (int32_t)want;
+}
+
+hipError_t launch_general_pass(const GenArgs &a, int mode, bool csr, int32_t nblk,
+                               hipStream_t st) {
+  if (csr) return launch_gl<16, true>(a, mode, nblk, st);
+  return launch_gl<64, false>(a, mode, nblk, st);
+}
+
+hipError_t launch_zero_f32(float *p, size_t count, hipStream_t st) {
+  if (count == 0) return hipSuccess;
+  size_t blocks = (count + 1023) / 1024;
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(k_zero_f32, dim3((unsigned)blocks), dim3(256), 0, st, p, count);
+  return hipGetLastError();
+}
+
+hipError_t launch_general_apply(const ApplyArgs &a, hipStream_t st) {
+  int nb = (a.d + 1023) / 1024;
+  if (nb > 1024) nb = 1024;
+  if (nb < 1) nb = 1;
+  hipLaunchKernelGGL(k_apply_general, dim3(nb + (a.flags ? 1 : 0)), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace aa

@@ -1,0 +1,225 @@
+// Keep draw + stable compaction (Algorithm 1) and batch assembly (gather).
+//
+// Compaction is two launches for any pool size: (1) one thread per candidate
+// draws / thresholds the keep flag, a wavefront ballot counts the wave's
+// survivors, an LDS sum gives the block's count, and the last block to arrive
+// turns the block counts into exclusive offsets; (2) one thread per candidate
+// ranks itself inside its wave with mbcnt on the ballot mask, adds the LDS
+// prefix of the waves before it and the block offset, and stores its position.
+#include "aa_select.hpp"
+
+namespace aa {
+
+namespace {
+
+typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+
+template <int SRC>
+__global__ __launch_bounds__(kKeepBlock) void k_keep_count(const KeepArgs a) {
+  __shared__ int s_int[40];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int j = blockIdx.x * kKeepBlock + tid;
+  bool keep = false;
+  if (j < a.P) {
+    if (SRC == kFromProb) {
+      const float u = keep_uniform(a.key, (uint32_t)j);
+      keep = keep_decision(u, a.src[j], a.gamma, a.one_minus_gamma);
+      a.flags[j] = keep ? 1 : 0;
+    } else if (SRC == kFromCrit) {
+      keep = a.src[j] > *a.T;
+      a.flags[j] = keep ? 1 : 0;
+    } else {
+      keep = a.flags[j] != 0;
+    }
+  }
+  const unsigned long long mask = __ballot(keep);
+  if (lane == 0) s_int[wave] = __popcll(mask);
+  __syncthreads();
+  if (tid == 0) a.blk_off[blockIdx.x] = s_int[0] + s_int[1] + s_int[2] + s_int[3];
+  __syncthreads();
+  if (last_block_arrives(a.ticket, &s_int[32])) {
+    const int nblk = gridDim.x;
+    int running = 0;
+    for (int t0 = 0; t0 < nblk; t0 += kKeepBlock) {
+      const int i = t0 + tid;
+      const int v = i < nblk ? a.blk_off[i] : 0;
+      int total;
+      const int excl = block_exclusive_scan(v, s_int, &total);
+      if (i < nblk) a.blk_off[i] = running + excl;
+      running += total;
+    }
+    if (tid == 0) *a.kept_count = running;
+  }
+}
+
+__global__ __launch_bounds__(kKeepBlock) void k_scatter(const ScatterArgs a) {
+  __shared__ int s_int[8];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int j = blockIdx.x * kKeepBlock + tid;
+  const bool keep = j < a.P && a.flags[j] != 0;
+  const unsigned long long mask = __ballot(keep);
+  const int rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                             __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+  if (lane == 0) s_int[wave] = __popcll(mask);
+  __syncthreads();
+  int woff = 0;
+  for (int i = 0; i < wave; ++i) woff += s_int[i];
+  if (keep) a.kept_pos[a.blk_off[blockIdx.x] + woff + rank] = j;
+}
+
+__global__ void k_set_i32(int32_t *p, int32_t v) { *p = v; }
+
+// Copy rows chunk by chunk; a block owns one chunk of one kept row at a time.
+template <int VEC, int UNROLL>
+__global__ __launch_bounds__(256) void k_gather_rows(const GatherArgs a, int cpr,
+                                                     long long chunk_bytes) {
+  const int m = min(max(*a.kept_count, 0), a.max_rows);
+  const long long total = (long long)m * cpr;
+  for (long long wi = blockIdx.x; wi < total; wi += gridDim.x) {
+    const int r = (int)(wi / cpr), ch = (int)(wi % cpr);
+    const int pos = a.kept_pos ? a.kept_pos[r] : r;
+    const long long id = a.idx ? a.idx[pos] : pos;
+    if (ch == 0 && threadIdx.x == 0 && a.kept_ids) a.kept_ids[r] = (int32_t)id;
+    const long long off = (long long)ch * chunk_bytes;
+    const long long nbytes = min(chunk_bytes, a.row_bytes - off);
+    const char *s = a.src + id * a.row_bytes + off;
+    char *d = a.dst + (long long)r * a.row_bytes + off;
+    if (VEC == 16) {
+      const int n = (int)(nbytes >> 4);
+      const u4 *s4 = reinterpret_cast<const u4 *>(s);
+      u4 *d4 = reinterpret_cast<u4 *>(d);
+      u4 v[UNROLL];
+#pragma unroll
+      for (int q = 0; q < UNROLL; ++q) {
+        const int i = q * 256 + threadIdx.x;
+        if (i < n) v[q] = __builtin_nontemporal_load(s4 + i);
+      }
+#pragma unroll
+      for (int q = 0; q < UNROLL; ++q) {
+        const int i = q * 256 + threadIdx.x;
+        if (i < n) __builtin_nontemporal_store(v[q], d4 + i);
+      }
+    } else if (VEC == 4) {
+      const int n = (int)(nbytes >> 2);
+      const uint32_t *s1 = reinterpret_cast<const uint32_t *>(s);
+      uint32_t *d1 = reinterpret_cast<uint32_t *>(d);
+      for (int i = threadIdx.x; i < n; i += 256) d1[i] = s1[i];
+    } else {
+      for (int i = threadIdx.x; i < (int)nbytes; i += 256) d[i] = s[i];
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void k_gather_ids(const GatherArgs a) {
+  const int m = min(max(*a.kept_count, 0), a.max_rows);
+  for (int r = blockIdx.x * 256 + threadIdx.x; r < m; r += gridDim.x * 256) {
+    const int pos = a.kept_pos ? a.kept_pos[r] : r;
+    a.kept_ids[r] = a.idx ? a.idx[pos] : pos;
+  }
+}
+
+// Row lengths of the kept CSR rows -> out_rowptr (one block, running scan).
+__global__ __launch_bounds__(1024) void k_csr_rowptr(const GatherCsrArgs a) {
+  __shared__ int s_int[40];
+  const int m = min(max(*a.kept_count, 0), a.max_rows);
+  const int tid = threadIdx.x;
+  long long running = 0;
+  if (tid == 0) a.out_rowptr[0] = 0;
+  for (int t0 = 0; t0 < m; t0 += 1024) {
+    const int r = t0 + tid;
+    int len = 0;
+    if (r < m) {
+      const int pos = a.kept_pos ? a.kept_pos[r] : r;
+      const long long id = a.idx ? a.idx[pos] : pos;
+      len = (int)(a.rowptr[id + 1] - a.rowptr[id]);
+    }
+    int total;
+    const int excl = block_exclusive_scan(len, s_int, &total);
+    if (r < m) a.out_rowptr[r + 1] = running + excl + len;
+    running += total;
+  }
+}
+
+// 16 lanes copy the entries of one kept row.
+__global__ __launch_bounds__(256) void k_csr_copy(const GatherCsrArgs a) {
+  const int m = min(max(*a.kept_count, 0), a.max_rows);
+  const int sub = threadIdx.x & 15;
+  const int g0 = (blockIdx.x * 256 + threadIdx.x) >> 4, ng = (gridDim.x * 256) >> 4;
+  for (int r = g0; r < m; r += ng) {
+    const int pos = a.kept_pos ? a.kept_pos[r] : r;
+    const long long id = a.idx ? a.idx[pos] : pos;
+    const long long e0 = a.rowptr[id];
+    const int len = (int)(a.rowptr[id + 1] - e0);
+    const long long o0 = a.out_rowptr[r];
+    if (o0 + len > a.out_nnz_cap) continue;
+    for (int e = sub; e < len; e += 16) {
+      a.out_col[o0 + e] = a.col[e0 + e];
+      if (a.val && a.out_val) a.out_val[o0 + e] = a.val[e0 + e];
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_keep_count(const KeepArgs &a, int source, hipStream_t st) {
+  if (a.P <= 0) {
+    hipLaunchKernelGGL(k_set_i32, dim3(1), dim3(1), 0, st, a.kept_count, 0);
+    return hipGetLastError();
+  }
+  const dim3 grid((a.P + kKeepBlock - 1) / kKeepBlock), block(kKeepBlock);
+  if (source == kFromProb)
+    hipLaunchKernelGGL((k_keep_count<kFromProb>), grid, block, 0, st, a);
+  else if (source == kFromCrit)
+    hipLaunchKernelGGL((k_keep_count<kFromCrit>), grid, block, 0, st, a);
+  else
+    hipLaunchKernelGGL((k_keep_count<kFromFlags>), grid, block, 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_scatter(const ScatterArgs &a, hipStream_t st) {
+  if (a.P <= 0) return hipSuccess;
+  const dim3 grid((a.P + kKeepBlock - 1) / kKeepBlock), block(kKeepBlock);
+  hipLaunchKernelGGL(k_scatter, grid, block, 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_gather(const GatherArgs &a, hipStream_t st) {
+  if (a.max_rows <= 0) return hipSuccess;
+  if (a.src == nullptr || a.row_bytes == 0) {
+    if (!a.kept_ids) return hipSuccess;
+    int nb = (a.max_rows + 255) / 256;
+    if (nb > 1024) nb = 1024;
+    hipLaunchKernelGGL(k_gather_ids, dim3(nb), dim3(256), 0, st, a);
+    return hipGetLastError();
+  }
+  const uintptr_t bits = reinterpret_cast<uintptr_t>(a.src) | reinterpret_cast<uintptr_t>(a.dst) |
+                         (uintptr_t)a.row_bytes;
+  const int vec = (bits & 15) == 0 ? 16 : ((bits & 3) == 0 ? 4 : 1);
+  const int unroll = (vec == 16 && a.row_bytes > 8192) ? 4 : 1;
+  const long long chunk = vec == 16 ? 4096ll * unroll : 4096ll;
+  const long long cpr = (a.row_bytes + chunk - 1) / chunk;
+  long long want = (long long)a.max_rows * cpr;
+  if (want > 256 * 16) want = 256 * 16;
+  const dim3 grid((unsigned)want), block(256);
+  if (vec == 16 && unroll == 4)
+    hipLaunchKernelGGL((k_gather_rows<16, 4>), grid, block, 0, st, a, (int)cpr, chunk);
+  else if (vec == 16)
+    hipLaunchKernelGGL((k_gather_rows<16, 1>), grid, block, 0, st, a, (int)cpr, chunk);
+  else if (vec == 4)
+    hipLaunchKernelGGL((k_gather_rows<4, 1>), grid, block, 0, st, a, (int)cpr, chunk);
+  else
+    hipLaunchKernelGGL((k_gather_rows<1, 1>), grid, block, 0, st, a, (int)cpr, chunk);
+  return hipGetLastError();
+}
+
+hipError_t launch_gather_csr(const GatherCsrArgs &a, hipStream_t st) {
+  hipLaunchKernelGGL(k_csr_rowptr, dim3(1), dim3(1024), 0, st, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || a.max_rows <= 0) return e;
+  int nb = (a.max_rows + 15) / 16;
+  if (nb > 256 * 8) nb = 256 * 8;
+  hipLaunchKernelGGL(k_csr_copy, dim3(nb), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace aa

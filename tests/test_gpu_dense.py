@@ -1,0 +1,550 @@
+"""GPU parity: the dense path through the C ABI against the CPU oracle, element by element."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_1905_03381_amd import api, synth
+
+from gpu_util import (RTOL, abs_dot_scale, assert_close_scaled, assert_logit_prob, clear_draws,
+                      dense_features, dev, host, scalar_dev)
+
+pytestmark = pytest.mark.gpu
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+@pytest.fixture(scope="module")
+def ws():
+    return api.Workspace(1 << 17, 4100)
+
+
+def make_dense(n, d, seed, ld=None, unit=False):
+    r = rng(seed)
+    X = r.standard_normal((n, ld or d)).astype(np.float32)
+    if unit:
+        X /= np.linalg.norm(X[:, :d], axis=1, keepdims=True)
+    y = np.where(r.random(n) < 0.5, 1.0, -1.0).astype(np.float32)
+    return X, y
+
+
+# shapes: (n, d, ld, P) -- several register layouts, masked tails, the general kernels
+SCORE_SHAPES = [
+    (300, 128, None, 256),      # tiny config: 32 lanes per row
+    (700, 1024, None, 613),     # dense config row width, ragged pool
+    (500, 512, None, 500),      # image-generator feature width
+    (300, 2048, None, 200),     # widest register layout
+    (400, 36, None, 333),       # masked 16-lane layout
+    (400, 200, 256, 400),       # padded rows (ld > d), masked lanes
+    (300, 130, None, 250),      # d % 4 != 0 -> general kernel
+    (200, 4100, None, 150),     # d > 2048 -> general kernel
+    (64, 1024, None, 1),        # single candidate
+]
+
+
+@pytest.mark.parametrize("n,d,ld,P", SCORE_SHAPES)
+@pytest.mark.parametrize("use_idx", [True, False])
+def test_assistant_score(ref, n, d, ld, P, use_idx):
+    X, _ = make_dense(n, d, 1, ld)
+    r = rng(2)
+    phi = (r.standard_normal(d) / math.sqrt(d)).astype(np.float32)
+    idx = r.permutation(n)[:P].astype(np.int32) if use_idx else None
+    Fh = ref.Features.dense(X, d=d)
+    ref_logit, ref_prob = ref.assistant_score(Fh, idx, P, phi, bias=0.2)
+    F = dense_features(X, d=d)
+    logit = torch.full((P,), 7.0, device="cuda")
+    prob = torch.full((P,), 7.0, device="cuda")
+    api.assistant_score(F, dev(idx), P, dev(phi), scalar_dev(0.2), logit, prob)
+    ids = idx if use_idx else np.arange(P)
+    S = abs_dot_scale(Fh, ids, phi)
+    assert_logit_prob(host(logit), host(prob), ref_logit, ref_prob, S, bias=0.2)
+    # bias NULL and logit NULL
+    api.assistant_score(F, dev(idx), P, dev(phi), None, None, prob)
+    _, ref_prob0 = ref.assistant_score(Fh, idx, P, phi)
+    assert np.allclose(host(prob), ref_prob0, rtol=1e-4, atol=1e-6)
+
+
+@pytest.mark.parametrize("P", [0, 1, 63, 64, 65, 255, 256, 257, 1000, 16384, 100_001])
+@pytest.mark.parametrize("gamma", [0.0, 0.1, 1.0])
+def test_shrink_bit_exact(ref, ws, P, gamma):
+    prob = rng(P + 3).random(P).astype(np.float32)
+    keep_ref, pos_ref = ref.shrink(prob, gamma, 42, 9)
+    keep = torch.full((max(P, 1),), 9, dtype=torch.uint8, device="cuda")
+    pos = torch.full((max(P, 1),), -1, dtype=torch.int32, device="cuda")
+    cnt = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    api.shrink(dev(prob) if P else None, P, gamma, 42, 9, keep, pos, cnt, ws)
+    m = int(host(cnt)[0])
+    assert m == pos_ref.size
+    assert np.array_equal(host(keep)[:P], keep_ref)
+    assert np.array_equal(host(pos)[:m], pos_ref)
+    assert np.all(host(pos)[m:] == -1)          # entries past the count are untouched
+    # keep == NULL: flags live in the workspace
+    pos2 = torch.full((max(P, 1),), -1, dtype=torch.int32, device="cuda")
+    api.shrink(dev(prob) if P else None, P, gamma, 42, 9, None, pos2, cnt, ws)
+    assert int(host(cnt)[0]) == m and np.array_equal(host(pos2)[:m], pos_ref)
+
+
+def test_shrink_large_seed_and_step(ref, ws):
+    P = 5000
+    prob = rng(1).random(P).astype(np.float32)
+    seed, step = 0xDEADBEEF12345678, 0x1_0000_0003
+    keep_ref, pos_ref = ref.shrink(prob, 0.25, seed, step)
+    keep = torch.zeros(P, dtype=torch.uint8, device="cuda")
+    pos = torch.zeros(P, dtype=torch.int32, device="cuda")
+    cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    api.shrink(dev(prob), P, 0.25, seed, step, keep, pos, cnt, ws)
+    assert np.array_equal(host(keep), keep_ref)
+    assert np.array_equal(host(pos)[:pos_ref.size], pos_ref)
+
+
+def test_shrink_threshold(ref, ws):
+    P = 3000
+    crit = rng(5).gamma(2.0, 0.5, P).astype(np.float32)
+    crit[17] = 0.75
+    keep_ref, pos_ref = ref.shrink_threshold(crit, 0.75)
+    keep = torch.zeros(P, dtype=torch.uint8, device="cuda")
+    pos = torch.zeros(P, dtype=torch.int32, device="cuda")
+    cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    api.shrink_threshold(dev(crit), P, scalar_dev(0.75), keep, pos, cnt, ws)
+    assert int(host(cnt)[0]) == pos_ref.size
+    assert np.array_equal(host(keep), keep_ref) and np.array_equal(host(pos)[:pos_ref.size], pos_ref)
+
+
+@pytest.mark.parametrize("n,d,ld,P", SCORE_SHAPES + [(70_000, 128, None, 70_000)])
+def test_score_shrink_fused(ref, ws, n, d, ld, P):
+    X, _ = make_dense(n, d, 11, ld)
+    r = rng(12)
+    phi = (2.0 * r.standard_normal(d) / math.sqrt(d)).astype(np.float32)
+    idx = r.permutation(n)[:P].astype(np.int32)
+    Fh = ref.Features.dense(X, d=d)
+    gamma, seed, step = 0.1, 77, 5
+    ref_logit, ref_prob = ref.assistant_score(Fh, idx, P, phi, bias=-0.1)
+    keep_ref, _ = ref.shrink(ref_prob, gamma, seed, step)
+    F = dense_features(X, d=d)
+    logit = torch.zeros(P, device="cuda")
+    prob = torch.zeros(P, device="cuda")
+    keep = torch.full((P,), 9, dtype=torch.uint8, device="cuda")
+    pos = torch.full((P,), -1, dtype=torch.int32, device="cuda")
+    cnt = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    api.score_shrink(F, dev(idx), P, dev(phi), scalar_dev(-0.1), gamma, seed, step, logit, prob,
+                     keep, pos, cnt, ws)
+    S = abs_dot_scale(Fh, idx, phi)
+    assert_logit_prob(host(logit), host(prob), ref_logit, ref_prob, S, bias=-0.1)
+    k = host(keep)
+    clear = clear_draws(ref, ref_prob, gamma, seed, step)
+    assert np.array_equal(k[clear], keep_ref[clear])        # bit-exact outside the rounding band
+    assert set(np.unique(k)) <= {0, 1}
+    m = int(host(cnt)[0])
+    assert m == int(k.sum())
+    assert np.array_equal(host(pos)[:m], np.flatnonzero(k))  # stable compaction of its own mask
+    # same outputs as the two staged calls on the same inputs
+    prob2 = torch.zeros(P, device="cuda")
+    api.assistant_score(F, dev(idx), P, dev(phi), scalar_dev(-0.1), None, prob2)
+    assert np.array_equal(host(prob2), host(prob))
+    keep2 = torch.zeros(P, dtype=torch.uint8, device="cuda")
+    pos2 = torch.zeros(P, dtype=torch.int32, device="cuda")
+    api.shrink(prob2, P, gamma, seed, step, keep2, pos2, cnt, ws)
+    assert np.array_equal(host(keep2), k) and np.array_equal(host(pos2)[:m], host(pos)[:m])
+
+
+@pytest.mark.parametrize("row_bytes", [1, 3, 4, 16, 4095, 4096, 8200, 150_528])
+def test_gather_rows(ref, row_bytes):
+    r = rng(20)
+    n, P = 300, 257
+    src = r.integers(0, 256, (n, row_bytes), dtype=np.uint8)
+    idx = r.permutation(n)[:P].astype(np.int32)
+    kept_pos = np.sort(r.choice(P, 120, replace=False)).astype(np.int32)
+    want, want_ids = ref.gather(src, idx, kept_pos)
+    dst = torch.full((P, row_bytes), 0xEE, dtype=torch.uint8, device="cuda")
+    ids = torch.full((P,), -1, dtype=torch.int32, device="cuda")
+    pos_d = torch.full((P,), -1, dtype=torch.int32, device="cuda")
+    pos_d[:120] = dev(kept_pos)
+    api.gather(dev(src), row_bytes, dev(idx), pos_d, scalar_dev(120, torch.int32), P, dst, ids)
+    out = host(dst)
+    assert np.array_equal(out[:120], want)
+    assert np.all(out[120:] == 0xEE)                       # rows past the count untouched
+    assert np.array_equal(host(ids)[:120], want_ids) and np.all(host(ids)[120:] == -1)
+    # ids only, and identity positions
+    ids2 = torch.full((P,), -1, dtype=torch.int32, device="cuda")
+    api.gather(None, 0, dev(idx), pos_d, scalar_dev(120, torch.int32), P, None, ids2)
+    assert np.array_equal(host(ids2)[:120], want_ids)
+    dst3 = torch.zeros((P, row_bytes), dtype=torch.uint8, device="cuda")
+    api.gather(dev(src), row_bytes, dev(idx), None, scalar_dev(P, torch.int32), P, dst3, None)
+    assert np.array_equal(host(dst3), src[idx])
+    # count of zero copies nothing
+    dst4 = torch.full((P, row_bytes), 0xEE, dtype=torch.uint8, device="cuda")
+    api.gather(dev(src), row_bytes, dev(idx), pos_d, scalar_dev(0, torch.int32), P, dst4, None)
+    assert np.all(host(dst4) == 0xEE)
+
+
+def _w_scale(Fh, ids, y, w0, lr, lam, m, active):
+    absx = np.abs(Fh.x[np.asarray(ids)[active], :Fh.d].astype(np.float64)).sum(axis=0)
+    return np.abs(1 - lr * lam) * np.abs(w0.astype(np.float64)) + lr / m * absx
+
+
+SGD_SHAPES = [
+    (300, 128, None, 140),
+    (700, 1024, None, 333),
+    (300, 2048, None, 77),
+    (400, 36, None, 333),
+    (400, 200, 256, 250),
+    (300, 130, None, 111),     # general kernel (atomics)
+    (200, 4100, None, 90),     # general kernel
+    (64, 1024, None, 1),
+]
+
+
+@pytest.mark.parametrize("n,d,ld,m", SGD_SHAPES)
+@pytest.mark.parametrize("indexed", [True, False])
+def test_svm_sgd_step(ref, ws, n, d, ld, m, indexed):
+    X, y = make_dense(n, d, 31, ld, unit=True)
+    r = rng(32)
+    w0 = (1.5 * r.standard_normal(d)).astype(np.float32)
+    rows = r.permutation(n)[:m].astype(np.int32) if indexed else None
+    ids = rows if indexed else np.arange(m)
+    Fh = ref.Features.dense(X, d=d)
+    lam, lr = 1e-2, 0.3
+    w_ref, loss_ref = ref.svm_sgd_step(Fh, y, rows, m, w0, lam, lr)
+    S = abs_dot_scale(Fh, ids, w0)
+    marg = 1.0 - loss_ref.astype(np.float64)
+    dots = Fh.x[ids, :d].astype(np.float64) @ w0.astype(np.float64) * y[ids]
+    assert np.all(np.abs(dots - 1) > RTOL * S), "pick another seed: a margin sits on the kink"
+    F = dense_features(X, d=d)
+    w = dev(w0)
+    loss = torch.full((m + 5,), -3.0, device="cuda")
+    api.svm_sgd_step(F, dev(y), dev(rows), scalar_dev(m, torch.int32), m + 5, w, lam, lr, 0.0,
+                     loss, ws)
+    assert_close_scaled(host(loss)[:m], loss_ref, S, "loss")
+    assert np.all(host(loss)[m:] == -3.0)
+    active = dots < 1
+    assert_close_scaled(host(w), w_ref, _w_scale(Fh, ids, y, w0, lr, lam, m, active), "w")
+    del marg
+
+
+def test_svm_sgd_step_empty_and_projection(ref, ws):
+    X, y = make_dense(200, 128, 41, unit=True)
+    w0 = rng(42).standard_normal(128).astype(np.float32)
+    F = dense_features(X)
+    w = dev(w0)
+    api.svm_sgd_step(F, dev(y), None, scalar_dev(0, torch.int32), 100, w, 0.1, 0.5, 0.0, None, ws)
+    assert np.array_equal(host(w), w0)                      # m = 0: untouched, regulariser included
+    api.svm_sgd_step(F, dev(y), None, scalar_dev(0, torch.int32), 100, w, 0.1, 0.5, 0.5, None, ws)
+    assert np.array_equal(host(w), w0)                      # ... and not projected either
+    Fh = ref.Features.dense(X)
+    for radius in (0.5, 1e3):
+        w_ref, _ = ref.svm_sgd_step(Fh, y, None, 150, w0, 0.1, 0.5, radius=radius)
+        w = dev(w0)
+        api.svm_sgd_step(F, dev(y), None, scalar_dev(150, torch.int32), 150, w, 0.1, 0.5, radius,
+                         None, ws)
+        assert np.allclose(host(w), w_ref, rtol=2e-5, atol=1e-6)
+
+
+@pytest.mark.parametrize("n,d,ld,m", SGD_SHAPES)
+def test_assistant_update(ref, ws, n, d, ld, m):
+    X, _ = make_dense(n, d, 51, ld, unit=True)
+    r = rng(52)
+    phi0 = (0.5 * r.standard_normal(d)).astype(np.float32)
+    rows = r.permutation(n)[:m].astype(np.int32)
+    loss = r.gamma(2.0, 0.5, m).astype(np.float32)
+    T, lr_a, l2_a, b0 = 0.9, 0.4, 0.01, -0.2
+    Fh = ref.Features.dense(X, d=d)
+    phi_ref, b_ref = ref.assistant_update(Fh, rows, m, loss, T, phi0, b0, lr_a, l2_a)
+    F = dense_features(X, d=d)
+    phi, b = dev(phi0), scalar_dev(b0)
+    api.assistant_update(F, dev(rows), scalar_dev(m, torch.int32), m, dev(loss), scalar_dev(T),
+                         phi, b, lr_a, l2_a, ws)
+    absx = np.abs(Fh.x[rows, :d].astype(np.float64)).sum(axis=0)
+    scale = np.abs(phi0.astype(np.float64)) + lr_a / m * absx
+    assert_close_scaled(host(phi), phi_ref, scale, "phi")
+    assert abs(float(host(b)[0]) - b_ref) <= RTOL * (abs(b0) + lr_a)
+    # bias NULL
+    phi_ref2, _ = ref.assistant_update(Fh, rows, m, loss, T, phi0, None, lr_a, l2_a)
+    phi2 = dev(phi0)
+    api.assistant_update(F, dev(rows), scalar_dev(m, torch.int32), m, dev(loss), scalar_dev(T),
+                         phi2, None, lr_a, l2_a, ws)
+    assert_close_scaled(host(phi2), phi_ref2, scale, "phi (no bias)")
+
+
+def _check_state(ref_out, w, phi, b, Fh, ids_kept, y, w0, phi0, b0, lr, lam, lr_a, T):
+    m = ref_out["m"]
+    if m == 0:
+        assert np.array_equal(host(w), w0) and np.array_equal(host(phi), phi0)
+        return
+    d = Fh.d
+    Xk = Fh.x[ids_kept, :d].astype(np.float64)
+    dots = (Xk @ w0.astype(np.float64)) * y[ids_kept]
+    active = dots < 1
+    assert_close_scaled(host(w), ref_out["w"], _w_scale(Fh, ids_kept, y, w0, lr, lam, m, active), "w")
+    scale = np.abs(phi0.astype(np.float64)) + lr_a / m * np.abs(Xk).sum(axis=0)
+    assert_close_scaled(host(phi), ref_out["phi"], scale, "phi")
+    assert abs(float(host(b)[0]) - ref_out["bias"]) <= RTOL * (abs(b0) + lr_a)
+
+
+@pytest.mark.parametrize("n,d,ld,P", SCORE_SHAPES)
+def test_fused_step_matches_oracle_step(ref, ws, n, d, ld, P):
+    X, y = make_dense(n, d, 61, ld, unit=True)
+    r = rng(62)
+    w0 = (1.2 * r.standard_normal(d)).astype(np.float32)
+    phi0 = (2.0 * r.standard_normal(d)).astype(np.float32)
+    idx = r.permutation(n)[:P].astype(np.int32)
+    b0, gamma, seed, step, lam, lr, T, lr_a = 0.1, 0.1, 5, 17, 1e-3, 0.5, 0.2, 0.3
+    Fh = ref.Features.dense(X, d=d)
+    for seed in range(5, 25):   # first Philox key with no draw inside the rounding band
+        out = ref.step(Fh, y, idx, P, w0, phi0, b0, gamma, seed, step, lam, lr, T, lr_a)
+        if clear_draws(ref, out["prob"], gamma, seed, step).all():
+            break
+    else:
+        raise AssertionError("no clear seed")
+    F = dense_features(X, d=d)
+    w, phi, b = dev(w0), dev(phi0), scalar_dev(b0)
+    Tt = scalar_dev(T)
+    cfg = api.step_config(gamma, lam, lr, lr_a, 0.0, seed, step, Tt)
+    logit = torch.zeros(P, device="cuda")
+    prob = torch.zeros(P, device="cuda")
+    keep = torch.full((P,), 9, dtype=torch.uint8, device="cuda")
+    pos = torch.full((P,), -1, dtype=torch.int32, device="cuda")
+    ids = torch.full((P,), -1, dtype=torch.int32, device="cuda")
+    loss = torch.full((P,), -3.0, device="cuda")
+    cnt = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    api.fused_step(F, dev(y), dev(idx), P, w, phi, b, cfg, logit, prob, keep, pos, ids, loss, cnt,
+                   ws)
+    m = out["m"]
+    assert int(host(cnt)[0]) == m
+    S = abs_dot_scale(Fh, idx, phi0)
+    assert_logit_prob(host(logit), host(prob), out["logit"], out["prob"], S, bias=b0)
+    assert np.array_equal(host(keep), out["keep"])
+    assert np.array_equal(host(pos)[:m], out["kept_pos"])
+    assert np.array_equal(host(ids)[:m], out["kept_ids"])
+    Sw = abs_dot_scale(Fh, out["kept_ids"], w0)
+    assert_close_scaled(host(loss)[:m], out["loss"], Sw, "loss")
+    assert np.all(host(loss)[m:] == -3.0)
+    _check_state(out, w, phi, b, Fh, out["kept_ids"], y, w0, phi0, b0, lr, lam, lr_a, T)
+
+
+def test_boss_assistant_step_equals_the_two_staged_calls(ref, ws):
+    n, d, m = 500, 1024, 301
+    X, y = make_dense(n, d, 71, unit=True)
+    r = rng(72)
+    w0 = (1.2 * r.standard_normal(d)).astype(np.float32)
+    phi0 = r.standard_normal(d).astype(np.float32)
+    rows = r.permutation(n)[:m].astype(np.int32)
+    b0, lam, lr, T, lr_a = -0.3, 1e-3, 0.4, 0.1, 0.25
+    Fh = ref.Features.dense(X)
+    w_ref, loss_ref = ref.svm_sgd_step(Fh, y, rows, m, w0, lam, lr)
+    phi_ref, b_ref = ref.assistant_update(Fh, rows, m, loss_ref, T, phi0, b0, lr_a)
+    F = dense_features(X)
+    w, phi, b = dev(w0), dev(phi0), scalar_dev(b0)
+    Tt = scalar_dev(T)
+    cfg = api.step_config(0.0, lam, lr, lr_a, 0.0, 0, 0, Tt)
+    loss = torch.zeros(m, device="cuda")
+    api.boss_assistant_step(F, dev(y), dev(rows), scalar_dev(m, torch.int32), m, w, phi, b, cfg,
+                            loss, ws)
+    out = dict(m=m, w=w_ref, phi=phi_ref, bias=b_ref)
+    assert_close_scaled(host(loss), loss_ref, abs_dot_scale(Fh, rows, w0), "loss")
+    _check_state(out, w, phi, b, Fh, rows, y, w0, phi0, b0, lr, lam, lr_a, T)
+    # and the staged GPU calls agree with the fused one to the same tolerance
+    w2, phi2, b2 = dev(w0), dev(phi0), scalar_dev(b0)
+    loss2 = torch.zeros(m, device="cuda")
+    api.svm_sgd_step(F, dev(y), dev(rows), scalar_dev(m, torch.int32), m, w2, lam, lr, 0.0, loss2,
+                     ws)
+    api.assistant_update(F, dev(rows), scalar_dev(m, torch.int32), m, loss2, Tt, phi2, b2, lr_a,
+                         0.0, ws)
+    assert np.array_equal(host(loss2), host(loss))
+    assert np.allclose(host(w2), host(w), rtol=1e-5, atol=1e-7)
+    assert np.allclose(host(phi2), host(phi), rtol=1e-5, atol=1e-7)
+
+
+def test_fused_step_empty_pool_and_nothing_kept(ref, ws):
+    X, y = make_dense(100, 128, 81, unit=True)
+    F = dense_features(X)
+    w0 = rng(82).standard_normal(128).astype(np.float32)
+    w, phi, b = dev(w0), dev(np.zeros(128, np.float32)), scalar_dev(-30.0)   # g ~ 1e-13
+    Tt = scalar_dev(0.0)
+    cfg = api.step_config(0.0, 0.1, 0.5, 0.5, 0.0, 1, 2, Tt)
+    cnt = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    prob = torch.zeros(100, device="cuda")
+    api.fused_step(F, dev(y), None, 100, w, phi, b, cfg, None, prob, None, None, None, None, cnt,
+                   ws)
+    assert int(host(cnt)[0]) == 0
+    assert np.array_equal(host(w), w0) and float(host(b)[0]) == -30.0
+    api.fused_step(F, dev(y), None, 0, w, phi, b, cfg, None, None, None, None, None, None, cnt, ws)
+    assert int(host(cnt)[0]) == 0 and np.array_equal(host(w), w0)
+
+
+def test_fused_step_is_deterministic(ws):
+    n, d, P = 3000, 1024, 2500
+    X, y = make_dense(n, d, 91, unit=True)
+    F = dense_features(X)
+    idx = dev(rng(92).permutation(n)[:P].astype(np.int32))
+    w0 = rng(93).standard_normal(d).astype(np.float32)
+    Tt = scalar_dev(0.0)
+    cfg = api.step_config(0.1, 1e-4, 0.5, 0.1, 0.0, 3, 4, Tt)
+    outs = []
+    for _ in range(3):
+        w, phi, b = dev(w0), dev(np.zeros(d, np.float32)), scalar_dev(0.0)
+        cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+        pos = torch.zeros(P, dtype=torch.int32, device="cuda")
+        api.fused_step(F, dev(y), idx, P, w, phi, b, cfg, None, None, None, pos, None, None, cnt,
+                       ws)
+        outs.append((host(w).copy(), host(phi).copy(), host(b).copy(), host(pos).copy()))
+    for o in outs[1:]:
+        for a, bb in zip(outs[0], o):
+            assert np.array_equal(a, bb)             # bit-identical run to run
+
+
+def _run_tiny_epoch(ref, ws, pipeline):
+    """Tiny-SVM config, one epoch of 40 pools, GPU state chained step to step."""
+    X, y, _ = synth.tiny_svm()
+    n, d = X.shape
+    P, lam, gamma, lr_a, T, seed = 256, 1e-4, 0.1, 0.1, 0.0, 42
+    perm = synth.epoch_permutation(n, seed=7, epoch=0)
+    Fh = ref.Features.dense(X)
+    F = dense_features(X)
+    yd, Tt = dev(y), scalar_dev(T)
+    w_r, phi_r, b_r = np.zeros(d, np.float32), np.zeros(d, np.float32), 0.0
+    w, phi, b = dev(w_r), dev(phi_r), scalar_dev(0.0)
+    t_upd = 0
+    for t, idx in enumerate(synth.pools(perm, P)):
+        Pt = idx.shape[0]
+        lr = np.float32(0.01 / math.sqrt(t_upd + 1))
+        w_prev, phi_prev, b_prev = w_r, phi_r, b_r
+        out = ref.step(Fh, y, idx, Pt, w_r, phi_r, b_r, gamma, seed, t, lam, lr, T, lr_a)
+        assert clear_draws(ref, out["prob"], gamma, seed, t).all()
+        w_r, phi_r, b_r = out["w"], out["phi"], out["bias"]
+        m = out["m"]
+        t_upd += 1 if m > 0 else 0
+        idx_d = dev(idx)
+        keep = torch.zeros(Pt, dtype=torch.uint8, device="cuda")
+        pos = torch.zeros(Pt, dtype=torch.int32, device="cuda")
+        ids = torch.zeros(Pt, dtype=torch.int32, device="cuda")
+        loss = torch.zeros(Pt, device="cuda")
+        cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+        prob = torch.zeros(Pt, device="cuda")
+        cfg = api.step_config(gamma, lam, float(lr), lr_a, 0.0, seed, t, Tt)
+        if pipeline == "fused":
+            api.fused_step(F, yd, idx_d, Pt, w, phi, b, cfg, None, prob, keep, pos, ids, loss, cnt,
+                           ws)
+        elif pipeline == "two_pass":
+            api.score_shrink(F, idx_d, Pt, phi, b, gamma, seed, t, None, prob, keep, pos, cnt, ws)
+            api.gather(None, 0, idx_d, pos, cnt, Pt, None, ids)
+            api.boss_assistant_step(F, yd, ids, cnt, Pt, w, phi, b, cfg, loss, ws)
+        else:  # staged: the five calls, with the kept rows materialised by the gather
+            api.assistant_score(F, idx_d, Pt, phi, b, None, prob)
+            api.shrink(prob, Pt, gamma, seed, t, keep, pos, cnt, ws)
+            Xk = torch.zeros((Pt, d), device="cuda")
+            yk = torch.zeros(Pt, device="cuda")
+            api.gather(F._keep[0], 4 * d, idx_d, pos, cnt, Pt, Xk, ids)
+            api.gather(yd, 4, idx_d, pos, cnt, Pt, yk, None)
+            Fk = api.Features.dense(Xk)
+            api.svm_sgd_step(Fk, yk, None, cnt, Pt, w, lam, float(lr), 0.0, loss, ws)
+            api.assistant_update(Fk, None, cnt, Pt, loss, Tt, phi, b, lr_a, 0.0, ws)
+        assert int(host(cnt)[0]) == m, f"step {t}"
+        assert np.array_equal(host(keep), out["keep"]), f"step {t}"
+        assert np.array_equal(host(pos)[:m], out["kept_pos"])
+        assert np.array_equal(host(ids)[:m], out["kept_ids"])
+        assert_close_scaled(host(loss)[:m], out["loss"],
+                            abs_dot_scale(Fh, out["kept_ids"], w_prev) + 1e-3, f"loss step {t}")
+        _check_state(out, w, phi, b, Fh, out["kept_ids"], y, w_prev, phi_prev, b_prev, float(lr),
+                     lam, lr_a, T)
+    return t_upd
+
+
+@pytest.mark.parametrize("pipeline", ["fused", "two_pass", "staged"])
+def test_tiny_config_epoch_every_step(ref, ws, pipeline):
+    assert _run_tiny_epoch(ref, ws, pipeline) == 40
+
+
+def test_train_epoch_matches_oracle_driver(ref, ws):
+    """aa_train_epoch (device-side lr/sqrt(t) schedule, no host sync) against the oracle loop."""
+    X, y, _ = synth.tiny_svm()
+    n, d = X.shape
+    P, lam, gamma, lr_a, T, seed, lr0 = 256, 1e-4, 0.1, 0.1, 0.0, 42, 0.01
+    perm = synth.epoch_permutation(n, seed=7, epoch=0)
+    Fh = ref.Features.dense(X)
+    w_r, phi_r, b_r = np.zeros(d, np.float32), np.zeros(d, np.float32), 0.0
+    ms, t_upd = [], 0
+    for t, idx in enumerate(synth.pools(perm, P)):
+        lr = np.float32(np.float32(lr0) / np.sqrt(np.float32(t_upd + 1)))
+        out = ref.step(Fh, y, idx, idx.shape[0], w_r, phi_r, b_r, gamma, seed + 0, 100 + t, lam, lr,
+                       T, lr_a)
+        w_r, phi_r, b_r = out["w"], out["phi"], out["bias"]
+        ms.append(out["m"])
+        t_upd += 1 if out["m"] > 0 else 0
+    F = dense_features(X)
+    w, phi, b = dev(np.zeros(d, np.float32)), dev(np.zeros(d, np.float32)), scalar_dev(0.0)
+    Tt = scalar_dev(T)
+    cfg = api.step_config(gamma, lam, lr0, lr_a, 0.0, seed, 100, Tt)
+    tu = torch.zeros(1, dtype=torch.int32, device="cuda")
+    hist = torch.full((len(ms),), -1, dtype=torch.int32, device="cuda")
+    api.train_epoch(F, dev(y), dev(perm), n, P, w, phi, b, cfg, tu, hist, ws)
+    assert np.array_equal(host(hist), np.array(ms))
+    assert int(host(tu)[0]) == t_upd
+    assert np.allclose(host(w), w_r, rtol=1e-4, atol=1e-6)
+    assert np.allclose(host(phi), phi_r, rtol=1e-4, atol=1e-6)
+    assert abs(float(host(b)[0]) - b_r) < 1e-5
+
+
+def test_argument_errors(ws):
+    X, y = make_dense(10, 8, 1)
+    F = dense_features(X)
+    L = api.lib()
+    prob = torch.zeros(10, device="cuda")
+    phi = torch.zeros(8, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    assert L.aa_assistant_score(None, None, 10, phi.data_ptr(), None, None, prob.data_ptr(), st) == -1
+    assert L.aa_assistant_score(F.ref(), None, -1, phi.data_ptr(), None, None, prob.data_ptr(), st) == -2
+    assert L.aa_assistant_score(F.ref(), None, 10, None, None, None, prob.data_ptr(), st) == -1
+    cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    pos = torch.zeros(10, dtype=torch.int32, device="cuda")
+    assert L.aa_shrink(prob.data_ptr(), 10, 0.1, 1, 1, None, pos.data_ptr(), cnt.data_ptr(), None,
+                       0, st) == -4
+    assert L.aa_shrink(prob.data_ptr(), 10, 0.1, 1, 1, None, pos.data_ptr(), cnt.data_ptr(),
+                       ws.ptr, 16, st) == -4
+    assert L.aa_shrink(prob.data_ptr(), 10, 0.1, 1, 1, None, pos.data_ptr(), cnt.data_ptr(),
+                       ws.ptr + 4, ws.bytes - 4, st) == -4
+    bad = api.aa_features(0, 8, 10, X.ctypes.data, 4, None, None, None)   # ld < d
+    import ctypes
+    assert L.aa_assistant_score(ctypes.byref(bad), None, 10, phi.data_ptr(), None, None,
+                                prob.data_ptr(), st) == -2
+    with pytest.raises(api.AAError):
+        api.gather(prob, 4, None, None, cnt, 10, None, None)   # src without dst
+
+
+def test_graph_replays_match_eager(ws):
+    """An epoch captured in a HIP graph gives the eager result on every replay (the library
+    records only kernels, no memset nodes), with eager work and syncs between replays."""
+    n, d, P = 4000, 1024, 1000
+    X, y = make_dense(n, d, 101, unit=True)
+    F = dense_features(X)
+    yd = dev(y)
+    perm = dev(rng(102).permutation(n).astype(np.int32))
+    Tt = scalar_dev(0.0)
+    cfg = api.step_config(0.1, 1e-4, 1.0, 0.1, 0.0, 9, 0, Tt)
+    w, phi, b = torch.zeros(d, device="cuda"), torch.zeros(d, device="cuda"), scalar_dev(0.0)
+    tu = torch.zeros(1, dtype=torch.int32, device="cuda")
+    hist = torch.zeros(4, dtype=torch.int32, device="cuda")
+
+    def reset():
+        for t in (w, phi, b, tu, hist):
+            t.zero_()
+
+    reset()
+    api.train_epoch(F, yd, perm, n, P, w, phi, b, cfg, tu, hist, ws)
+    eager = [host(t).copy() for t in (w, phi, b, tu, hist)]
+    g = torch.cuda.CUDAGraph()
+    reset()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g):
+        api.train_epoch(F, yd, perm, n, P, w, phi, b, cfg, tu, hist, ws)
+    for _ in range(3):
+        reset()
+        scratch = torch.randn(1 << 16, device="cuda").sum()      # unrelated eager work
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        del scratch
+        for got, want in zip((w, phi, b, tu, hist), eager):
+            assert np.array_equal(host(got), want)

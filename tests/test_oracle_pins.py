@@ -123,6 +123,16 @@ def test_keep_certain_and_impossible(ref):
     assert keep.all() and np.array_equal(pos, np.arange(P))
 
 
+def test_keep_is_strict_at_a_tie(ref):
+    """c < p is strict: a candidate whose probability equals its draw is dropped, the next
+    float up is kept (with gamma = 0 the probability is g itself)."""
+    u = ref.uniforms(21, 6, 64)
+    keep, _ = ref.shrink(u, 0.0, 21, 6)
+    assert not keep.any()
+    keep, _ = ref.shrink(np.nextafter(u, np.float32(2.0)), 0.0, 21, 6)
+    assert keep.all()
+
+
 @pytest.mark.parametrize("gamma", [0.0, 0.1, 0.5])
 def test_keep_probability_is_gamma_plus_one_minus_gamma_g(ref, gamma):
     P = 50_000
