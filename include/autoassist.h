@@ -22,7 +22,7 @@
  *  - `ws` is caller-provided device scratch of at least
  *    aa_workspace_bytes(P_max, d_max) bytes, 256-byte aligned, prepared once
  *    with aa_workspace_init().  A workspace must not be used by two calls that
- *    may overlap in time (different streams).
+ *    may overlap in time (different streams).  Keep flags are bytes 0 or 1.
  *  - Row ids are int32, CSR row pointers int64, column ids int32, values fp32.
  *  - P == 0 and *m == 0 are valid and leave the model state untouched.
  */
@@ -115,7 +115,8 @@ int32_t aa_shrink(const float *prob, int32_t P, float gamma, uint64_t seed, uint
                   uint8_t *keep, int32_t *kept_pos, int32_t *kept_count, void *ws,
                   size_t ws_bytes, void *stream);
 
-/* ---- a7: a1 + a2 + a3 in one kernel, so each feature row crosses HBM once.
+/* ---- a7: a1 + a2 fused in the row pass (score and keep draw from registers, so
+ * each feature row crosses HBM once), then the compaction of a3 over the flags.
  * Same outputs as aa_assistant_score followed by aa_shrink. */
 int32_t aa_score_shrink(const aa_features *F, const int32_t *idx, int32_t P, const float *phi,
                         const float *bias, float gamma, uint64_t seed, uint64_t step,

@@ -12,19 +12,17 @@ using namespace aa;
 
 namespace {
 
-constexpr int kTicketPassTail = 0;
-constexpr int kTicketFinalize = 1;
-constexpr int kTicketKeep = 2;
+constexpr int kCtlUpdateSnapshot = 0;  // control word: update counter before the running step
 
 struct Ws {
   char *base;
-  int32_t *tickets;
+  int32_t *ctl;
   int32_t *blk_cnt;
   float *blk_gb;
   char *grad;         // gradient partials / accumulators
   uint8_t *flags;     // [P]
   float *loss_pool;   // [P]
-  int32_t *blk_off;   // [P/256 + 2]
+  int32_t *tile_off;  // [P/2048 + 2]
   float *prob;        // [P]   per-step outputs of the epoch driver
   int32_t *kept_pos;  // [P]
   int32_t *kept_ids;  // [P]
@@ -37,7 +35,7 @@ size_t general_acc_bytes(int32_t d) { return (16 + 2 * (size_t)d) * sizeof(float
 Ws carve(void *ws, size_t grad_bytes, int32_t P, bool epoch_outputs = false) {
   Ws w;
   w.base = static_cast<char *>(ws);
-  w.tickets = reinterpret_cast<int32_t *>(w.base + kWsTickets);
+  w.ctl = reinterpret_cast<int32_t *>(w.base + kWsTickets);
   w.blk_cnt = reinterpret_cast<int32_t *>(w.base + kWsBlkCnt);
   w.blk_gb = reinterpret_cast<float *>(w.base + kWsBlkGb);
   size_t off = kWsBody;
@@ -47,8 +45,8 @@ Ws carve(void *ws, size_t grad_bytes, int32_t P, bool epoch_outputs = false) {
   off += align_up((size_t)(P > 0 ? P : 0), 256);
   w.loss_pool = reinterpret_cast<float *>(w.base + off);
   off += align_up(sizeof(float) * (size_t)(P > 0 ? P : 0), 256);
-  w.blk_off = reinterpret_cast<int32_t *>(w.base + off);
-  off += align_up(sizeof(int32_t) * ((size_t)(P > 0 ? P : 0) / kKeepBlock + 2), 256);
+  w.tile_off = reinterpret_cast<int32_t *>(w.base + off);
+  off += align_up(sizeof(int32_t) * ((size_t)(P > 0 ? P : 0) / kCompactTile + 2), 256);
   const size_t per = align_up(sizeof(float) * (size_t)(P > 0 ? P : 0), 256);
   w.prob = reinterpret_cast<float *>(w.base + off);
   w.kept_pos = reinterpret_cast<int32_t *>(w.base + off + per);
@@ -123,9 +121,7 @@ struct PassSpec {
   uint8_t *flags;
   float *loss_out;
   const float *loss_in;
-  int tail_compact;
-  int32_t *kept_pos;
-  int32_t *kept_count;
+  const int32_t *t_upd;
 };
 
 bool use_fast(const PassSpec &s) {
@@ -172,10 +168,8 @@ hipError_t run_pass(const PassSpec &s, const Ws &ws, int32_t *nblk_out, hipStrea
     a.partial = reinterpret_cast<float *>(ws.grad);
     a.blk_cnt = ws.blk_cnt;
     a.blk_gb = ws.blk_gb;
-    a.tail_compact = s.tail_compact;
-    a.kept_pos = s.kept_pos;
-    a.kept_count = s.kept_count;
-    a.ticket = ws.tickets + kTicketPassTail;
+    a.t_upd = s.t_upd;
+    a.t_snap = ws.ctl + kCtlUpdateSnapshot;
     const int32_t nblk = dense_pass_blocks(s.F->d, s.count_max, s.mode);
     *nblk_out = nblk;
     HookScope hook(st);
@@ -215,10 +209,6 @@ hipError_t run_pass(const PassSpec &s, const Ws &ws, int32_t *nblk_out, hipStrea
   a.acc_gb = acc + 1;
   a.acc_w = acc + 16;
   a.acc_p = acc + 16 + s.F->d;
-  a.tail_compact = s.tail_compact;
-  a.kept_pos = s.kept_pos;
-  a.kept_count = s.kept_count;
-  a.ticket = ws.tickets + kTicketPassTail;
   const int32_t nblk = general_pass_blocks(s.count_max, csr);
   *nblk_out = nblk;
   HookScope hook(st);
@@ -264,7 +254,7 @@ hipError_t run_update(const PassSpec &s, const UpdateSpec &u, const Ws &ws, int3
     f.l2_a = u.l2_a;
     f.t_upd = u.t_upd;
     f.kept_hist = u.kept_hist;
-    f.ticket = ws.tickets + kTicketFinalize;
+    f.t_snap = ws.ctl + kCtlUpdateSnapshot;
     f.flags = u.flags;
     f.P = u.P;
     f.idx = u.idx;
@@ -351,6 +341,7 @@ int32_t fused_step_impl(const aa_features *F, const float *y, const int32_t *idx
   s.do_keep = 1;
   s.logit = logit;
   s.prob = prob;
+  s.t_upd = t_upd;
   if (t_upd && !use_fast(s)) return AA_ERR_SHAPE;  // device-side step-size schedule: fast dense only
   const size_t gbytes = grad_bytes_for(s);
   Ws ws = carve(ws_ptr, gbytes, P, epoch_outputs);
@@ -453,6 +444,17 @@ int32_t aa_assistant_score(const aa_features *F, const int32_t *idx, int32_t P, 
   return hip_status(run_pass(s, none, &nblk, as_stream(stream)));
 }
 
+// Compact `flags` into kept_pos / kept_count (shared tail of the shrink entry points).
+static int32_t compact_flags(const uint8_t *flags, int32_t P, int32_t *kept_pos,
+                             int32_t *kept_count, const Ws &ws, hipStream_t st) {
+  CompactArgs c{};
+  c.flags = flags;
+  c.P = P;
+  c.kept_pos = kept_pos;
+  c.kept_count = kept_count;
+  return hip_status(launch_compact(c, ws.tile_off, st));
+}
+
 int32_t aa_shrink(const float *prob, int32_t P, float gamma, uint64_t seed, uint64_t step,
                   uint8_t *keep, int32_t *kept_pos, int32_t *kept_count, void *ws_ptr,
                   size_t ws_bytes, void *stream) {
@@ -468,13 +470,8 @@ int32_t aa_shrink(const float *prob, int32_t P, float gamma, uint64_t seed, uint
   k.one_minus_gamma = 1.0f - gamma;
   k.key = make_draw_key(seed, step);
   k.flags = keep ? keep : ws.flags;
-  k.blk_off = ws.blk_off;
-  k.kept_count = kept_count;
-  k.ticket = ws.tickets + kTicketKeep;
-  hipError_t e = launch_keep_count(k, kFromProb, as_stream(stream));
-  if (e != hipSuccess) return AA_ERR_HIP;
-  ScatterArgs sc{k.flags, P, ws.blk_off, kept_pos};
-  return hip_status(launch_scatter(sc, as_stream(stream)));
+  if (launch_keep_flags(k, kFromProb, as_stream(stream)) != hipSuccess) return AA_ERR_HIP;
+  return compact_flags(k.flags, P, kept_pos, kept_count, ws, as_stream(stream));
 }
 
 int32_t aa_shrink_threshold(const float *crit, int32_t P, const float *T, uint8_t *keep,
@@ -490,13 +487,8 @@ int32_t aa_shrink_threshold(const float *crit, int32_t P, const float *T, uint8_
   k.T = T;
   k.P = P;
   k.flags = keep ? keep : ws.flags;
-  k.blk_off = ws.blk_off;
-  k.kept_count = kept_count;
-  k.ticket = ws.tickets + kTicketKeep;
-  hipError_t e = launch_keep_count(k, kFromCrit, as_stream(stream));
-  if (e != hipSuccess) return AA_ERR_HIP;
-  ScatterArgs sc{k.flags, P, ws.blk_off, kept_pos};
-  return hip_status(launch_scatter(sc, as_stream(stream)));
+  if (launch_keep_flags(k, kFromCrit, as_stream(stream)) != hipSuccess) return AA_ERR_HIP;
+  return compact_flags(k.flags, P, kept_pos, kept_count, ws, as_stream(stream));
 }
 
 int32_t aa_score_shrink(const aa_features *F, const int32_t *idx, int32_t P, const float *phi,
@@ -507,11 +499,7 @@ int32_t aa_score_shrink(const aa_features *F, const int32_t *idx, int32_t P, con
   if (!kept_count) return AA_ERR_NULL;
   Ws ws = carve(ws_ptr, 0, P);
   if (int32_t rc = check_ws(ws_ptr, ws_bytes, ws.total)) return rc;
-  if (P == 0) {
-    KeepArgs k{};
-    k.kept_count = kept_count;
-    return hip_status(launch_keep_count(k, kFromProb, as_stream(stream)));
-  }
+  if (P == 0) return compact_flags(nullptr, 0, nullptr, kept_count, ws, as_stream(stream));
   if (int32_t rc = check_features(F)) return rc;
   if (!phi || !kept_pos) return AA_ERR_NULL;
   PassSpec s{};
@@ -528,11 +516,9 @@ int32_t aa_score_shrink(const aa_features *F, const int32_t *idx, int32_t P, con
   s.logit = logit;
   s.prob = prob;
   s.flags = keep ? keep : ws.flags;
-  s.tail_compact = 1;
-  s.kept_pos = kept_pos;
-  s.kept_count = kept_count;
   int32_t nblk = 0;
-  return hip_status(run_pass(s, ws, &nblk, as_stream(stream)));
+  if (run_pass(s, ws, &nblk, as_stream(stream)) != hipSuccess) return AA_ERR_HIP;
+  return compact_flags(s.flags, P, kept_pos, kept_count, ws, as_stream(stream));
 }
 
 int32_t aa_gather(const void *src, int64_t row_bytes, const int32_t *idx, const int32_t *kept_pos,
@@ -681,9 +667,9 @@ int32_t aa_fused_step(const aa_features *F, const float *y, const int32_t *idx, 
   if (P < 0) return AA_ERR_SHAPE;
   if (!kept_count) return AA_ERR_NULL;
   if (P == 0) {
-    KeepArgs k{};
-    k.kept_count = kept_count;
-    return hip_status(launch_keep_count(k, kFromProb, as_stream(stream)));
+    CompactArgs c{};
+    c.kept_count = kept_count;
+    return hip_status(launch_compact(c, nullptr, as_stream(stream)));
   }
   if (int32_t rc = check_features(F)) return rc;
   if (!y || !w || !phi || !cfg || !cfg->T) return AA_ERR_NULL;

@@ -12,10 +12,10 @@ namespace aa {
 constexpr int kWave = 64;
 constexpr int kMaxBlocks = 1024;       // upper bound on persistent blocks of a row pass
 constexpr int kFastDenseMaxD = 2048;   // register-resident model vectors up to this d
-constexpr int kTailFlagsPerThread = 64;
+constexpr int kCompactTile = 2048;     // keep flags compacted by one block
 
 // ---- workspace layout (byte offsets from ws) ------------------------------
-// [0, 256)            int32 tickets (self-resetting arrival counters)
+// [0, 256)            int32 control words (word 0: snapshot of the update counter)
 // [256, +4K)          int32 blk_cnt[kMaxBlocks]
 // [.., +4K)           float blk_gb[kMaxBlocks]
 // [.., +8)            scalars
@@ -115,23 +115,6 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int *smem, int *total
   __syncthreads();
   *total = sum;
   return base + incl - v;
-}
-
-// Arrival ticket: returns true in every thread of the last block to arrive.
-// The counter resets itself, so the next launch finds it at zero.
-__device__ __forceinline__ bool last_block_arrives(int32_t *ticket, int *smem_flag) {
-  __threadfence();
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    const int prev = atomicAdd(ticket, 1);
-    const int last = (prev == (int)gridDim.x - 1);
-    if (last) *ticket = 0;
-    *smem_flag = last;
-  }
-  __syncthreads();
-  const bool last = *smem_flag != 0;
-  if (last) __threadfence();
-  return last;
 }
 
 }  // namespace aa

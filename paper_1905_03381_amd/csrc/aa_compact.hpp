@@ -1,5 +1,13 @@
 // Stable stream compaction of keep flags (the append order of Algorithm 1:
 // kept candidates stay in arrival order).
+//
+// A block compacts one tile of kCompactTile flags.  Each of its four waves owns
+// a contiguous 512-flag segment and walks it in eight 64-lane rounds: a wavefront
+// ballot turns the round's flags into a 64-bit mask, mbcnt on the mask ranks a
+// lane among the survivors of its round, popcounts of the masks give the wave's
+// total, and an LDS exchange of the four wave totals gives each wave its base.
+// The tile's own base is the number of flags set before it: either read from a
+// table of tile offsets or counted directly (popcount over the 0/1 bytes).
 #pragma once
 
 #include "aa_common.hpp"
@@ -15,52 +23,76 @@ struct CompactArgs {
   const float *loss_pool;   // per-position loss (may be NULL)
   float *loss;              // out: loss[r] = loss_pool[kept_pos[r]] (may be NULL)
   int32_t *kept_count;      // out, may be NULL
+  const int32_t *tile_off;  // exclusive tile offsets, or NULL: count the flags before the tile
 };
 
-// Whole compaction done by ONE block (any multiple of 64 threads).  Each thread
-// owns kTailFlagsPerThread consecutive flags of a tile; a wave-shuffle scan and an
-// LDS scan over the waves give its output offset.  `smem` >= 32 ints.
-__device__ inline void block_compact(const CompactArgs &c, int *smem) {
-  const int nt = blockDim.x;
-  const int tile = nt * kTailFlagsPerThread;
-  const bool aligned = (((uintptr_t)c.flags) & 15) == 0;
-  int running = 0;
-  for (int t0 = 0; t0 < c.P; t0 += tile) {
-    const int j0 = t0 + (int)threadIdx.x * kTailFlagsPerThread;
-    uint64_t mask = 0;  // bit i = flag of position j0 + i
-    if (j0 < c.P) {
-      if (aligned && j0 + kTailFlagsPerThread <= c.P) {
-        const uint4 *p = reinterpret_cast<const uint4 *>(c.flags + j0);
-#pragma unroll
-        for (int q = 0; q < kTailFlagsPerThread / 16; ++q) {
-          const uint4 v = p[q];
-          const uint32_t wds[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-          for (int k = 0; k < 4; ++k)
-#pragma unroll
-            for (int b = 0; b < 4; ++b)
-              if ((wds[k] >> (8 * b)) & 0xFFu) mask |= 1ull << (q * 16 + k * 4 + b);
-        }
-      } else {
-        for (int i = 0; i < kTailFlagsPerThread && j0 + i < c.P; ++i)
-          if (c.flags[j0 + i]) mask |= 1ull << i;
-      }
+// Number of set flags in [0, j0) (j0 a multiple of 16), whole block cooperates.
+__device__ inline int count_flags_before(const uint8_t *flags, int j0, int *smem) {
+  int cnt = 0;
+  if ((reinterpret_cast<uintptr_t>(flags) & 15) == 0) {
+    const uint4 *p = reinterpret_cast<const uint4 *>(flags);
+    for (int q = threadIdx.x; q < (j0 >> 4); q += blockDim.x) {
+      const uint4 v = p[q];
+      cnt += __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w);  // bytes are 0 or 1
     }
-    const int cnt = __popcll(mask);
-    int total;
-    int off = running + block_exclusive_scan(cnt, smem, &total);
-    while (mask) {
-      const int i = __ffsll((long long)mask) - 1;
-      mask &= mask - 1;
-      const int j = j0 + i;
-      if (c.kept_pos) c.kept_pos[off] = j;
-      if (c.kept_ids) c.kept_ids[off] = c.idx ? c.idx[j] : j;
-      if (c.loss) c.loss[off] = c.loss_pool[j];
-      ++off;
-    }
-    running += total;
+  } else {
+    for (int j = threadIdx.x; j < j0; j += blockDim.x) cnt += flags[j] != 0;
   }
-  if (threadIdx.x == 0 && c.kept_count) *c.kept_count = running;
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off, kWave);
+  const int nw = blockDim.x >> 6;
+  if ((threadIdx.x & 63) == 0) smem[threadIdx.x >> 6] = cnt;
+  __syncthreads();
+  int total = 0;
+  for (int i = 0; i < nw; ++i) total += smem[i];
+  __syncthreads();
+  return total;
 }
+
+// Compact tile `tile` with a 256-thread block.  `smem` holds at least 8 ints.
+__device__ inline void tile_compact(const CompactArgs &c, int tile, int *smem) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int j0 = tile * kCompactTile;
+  const int prefix = c.tile_off ? c.tile_off[tile] : count_flags_before(c.flags, j0, smem);
+  const int seg = j0 + wave * (kCompactTile / 4);
+  unsigned long long masks[8];
+  int ids[8];
+  float ls[8];
+  int wave_total = 0;
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    const int j = seg + r * kWave + lane;
+    const bool in = j < c.P;
+    const bool f = in && c.flags[j] != 0;
+    ids[r] = (in && c.kept_ids) ? (c.idx ? c.idx[j] : j) : 0;
+    ls[r] = (in && c.loss) ? c.loss_pool[j] : 0.f;
+    masks[r] = __ballot(f);
+    wave_total += __popcll(masks[r]);
+  }
+  if (lane == 0) smem[wave] = wave_total;
+  __syncthreads();
+  int running = prefix, total = 0;
+  for (int i = 0; i < 4; ++i) {
+    const int t = smem[i];
+    if (i < wave) running += t;
+    total += t;
+  }
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    const unsigned long long m = masks[r];
+    if ((m >> lane) & 1ull) {
+      const int pos = running + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
+                                                          __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+      const int j = seg + r * kWave + lane;
+      if (c.kept_pos) c.kept_pos[pos] = j;
+      if (c.kept_ids) c.kept_ids[pos] = ids[r];
+      if (c.loss) c.loss[pos] = ls[r];
+    }
+    running += __popcll(m);
+  }
+  if (threadIdx.x == 0 && c.kept_count && j0 + kCompactTile >= c.P) *c.kept_count = prefix + total;
+}
+
+__host__ __device__ inline int compact_tiles(int P) { return (P + kCompactTile - 1) / kCompactTile; }
 
 }  // namespace aa

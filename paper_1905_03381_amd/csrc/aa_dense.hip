@@ -222,26 +222,11 @@ __global__ __launch_bounds__(NWMAX * 64) void k_rows_pass(const PassArgs a) {
       a.blk_gb[blockIdx.x] = gs;
     }
   }
-  if (POOL && !GRAD) {
-    if (a.tail_compact) {
-      if (last_block_arrives(a.ticket, &s_int[32])) {
-        CompactArgs c;
-        c.flags = a.flags;
-        c.P = a.count_max;
-        c.idx = nullptr;
-        c.kept_pos = a.kept_pos;
-        c.kept_ids = nullptr;
-        c.loss_pool = nullptr;
-        c.loss = nullptr;
-        c.kept_count = a.kept_count;
-        block_compact(c, s_int);
-      }
-    }
-  }
+  if (GRAD && a.t_upd && blockIdx.x == 0 && threadIdx.x == 0) *a.t_snap = *a.t_upd;
 }
 
-// Sum the block partials in a fixed order and apply the SGD updates; one extra
-// block compacts the keep flags of a pool pass.
+// Sum the block partials in a fixed order and apply the SGD updates; extra
+// blocks compact the keep flags of a pool pass, one tile each.
 __global__ __launch_bounds__(256) void k_finalize(const FinalizeArgs a) {
   __shared__ f4 s_acc[2][16][16];
   __shared__ int s_int[40];
@@ -259,7 +244,8 @@ __global__ __launch_bounds__(256) void k_finalize(const FinalizeArgs a) {
     c.loss_pool = a.loss_pool;
     c.loss = a.loss;
     c.kept_count = a.kept_count;
-    block_compact(c, s_int);
+    c.tile_off = nullptr;
+    tile_compact(c, (int)blockIdx.x - nred, s_int);
     return;
   }
 
@@ -281,7 +267,7 @@ __global__ __launch_bounds__(256) void k_finalize(const FinalizeArgs a) {
   int t_new = 0;
   float lr = a.lr;
   if (a.t_upd) {
-    t_new = *a.t_upd + (m > 0 ? 1 : 0);
+    t_new = *a.t_snap + (m > 0 ? 1 : 0);
     if (m > 0) lr = a.lr / sqrtf((float)t_new);
   }
 
@@ -349,18 +335,7 @@ __global__ __launch_bounds__(256) void k_finalize(const FinalizeArgs a) {
   }
   if (blockIdx.x == 0 && tid == 0 && a.kept_hist) *a.kept_hist = m;
 
-  if (a.t_upd) {
-    // every reducing block has read *t_upd before the last arrival rewrites it
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-      const int prev = atomicAdd(a.ticket, 1);
-      if (prev == nred - 1) {
-        *a.ticket = 0;
-        *a.t_upd = t_new;
-      }
-    }
-  }
+  if (blockIdx.x == 0 && tid == 0 && a.t_upd) *a.t_upd = t_new;
 }
 
 int g_num_cu = 0;
@@ -463,7 +438,7 @@ hipError_t launch_dense_pass(const PassArgs &a, int mode, int32_t d, int32_t nbl
 
 hipError_t launch_dense_finalize(const FinalizeArgs &a, hipStream_t st) {
   const int nred = a.d_pad / 64;
-  const int extra = a.flags ? 1 : 0;
+  const int extra = a.flags ? compact_tiles(a.P) : 0;
   hipLaunchKernelGGL(k_finalize, dim3(nred + extra), dim3(256), 0, st, a);
   return hipGetLastError();
 }

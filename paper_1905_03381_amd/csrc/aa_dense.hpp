@@ -33,11 +33,8 @@ struct PassArgs {
   float *partial;         // [nblk][nvec][d_pad]
   int32_t *blk_cnt;       // [nblk] kept count per block (pool mode)
   float *blk_gb;          // [nblk] bias-gradient partial (kAssist)
-  // tail compaction by the last block (pool mode without gradients)
-  int32_t tail_compact;
-  int32_t *kept_pos;
-  int32_t *kept_count;
-  int32_t *ticket;
+  const int32_t *t_upd;   // optional update counter; block 0 snapshots it into *t_snap
+  int32_t *t_snap;
 };
 
 struct FinalizeArgs {
@@ -52,9 +49,9 @@ struct FinalizeArgs {
   float *bias;
   float lambda, lr, lr_a, l2_a;
   int32_t *t_upd;          // optional device update counter driving lr/sqrt(t)
+  const int32_t *t_snap;   // its value before this step (written by the pass kernel)
   int32_t *kept_hist;      // optional: receives m
-  int32_t *ticket;
-  // optional compaction block (pool mode)
+  // optional compaction blocks (pool mode), one per tile of flags
   const uint8_t *flags;
   int32_t P;
   const int32_t *idx;

@@ -25,8 +25,6 @@ __global__ __launch_bounds__(256) void k_rows_general(const GenArgs a) {
   constexpr bool GRAD = SVM || ASSIST;
   constexpr bool NEED_PHI = POOL || ASSIST;
   constexpr int G = kWave / GL;
-  __shared__ int s_int[40];
-
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
   const int grp = lane / GL, sub = lane % GL;
 
@@ -136,20 +134,6 @@ __global__ __launch_bounds__(256) void k_rows_general(const GenArgs a) {
       if (ASSIST && gbw != 0.f) unsafeAtomicAdd(a.acc_gb, gbw);
     }
   }
-  if (POOL && !GRAD && a.tail_compact) {
-    if (last_block_arrives(a.ticket, &s_int[32])) {
-      CompactArgs c;
-      c.flags = a.flags;
-      c.P = a.count_max;
-      c.idx = nullptr;
-      c.kept_pos = a.kept_pos;
-      c.kept_ids = nullptr;
-      c.loss_pool = nullptr;
-      c.loss = nullptr;
-      c.kept_count = a.kept_count;
-      block_compact(c, s_int);
-    }
-  }
 }
 
 __global__ __launch_bounds__(256) void k_zero_f32(float *p, size_t count) {
@@ -160,7 +144,8 @@ __global__ __launch_bounds__(256) void k_zero_f32(float *p, size_t count) {
 
 __global__ __launch_bounds__(256) void k_apply_general(const ApplyArgs a) {
   __shared__ int s_int[40];
-  if (blockIdx.x == gridDim.x - 1 && a.flags) {
+  const int nb = (int)gridDim.x - (a.flags ? compact_tiles(a.P) : 0);
+  if ((int)blockIdx.x >= nb) {
     CompactArgs c;
     c.flags = a.flags;
     c.P = a.P;
@@ -170,10 +155,10 @@ __global__ __launch_bounds__(256) void k_apply_general(const ApplyArgs a) {
     c.loss_pool = a.loss_pool;
     c.loss = a.loss;
     c.kept_count = a.kept_count;
-    block_compact(c, s_int);
+    c.tile_off = nullptr;
+    tile_compact(c, (int)blockIdx.x - nb, s_int);
     return;
   }
-  const int nb = (int)gridDim.x - (a.flags ? 1 : 0);
   int m = a.m_dev ? min(max(*a.m_dev, 0), a.m_max) : *a.acc_cnt;
   if (blockIdx.x == 0 && threadIdx.x == 0 && a.kept_hist) *a.kept_hist = m;
   if (m <= 0) return;
@@ -243,7 +228,8 @@ hipError_t launch_general_apply(const ApplyArgs &a, hipStream_t st) {
   int nb = (a.d + 1023) / 1024;
   if (nb > 1024) nb = 1024;
   if (nb < 1) nb = 1;
-  hipLaunchKernelGGL(k_apply_general, dim3(nb + (a.flags ? 1 : 0)), dim3(256), 0, st, a);
+  hipLaunchKernelGGL(k_apply_general, dim3(nb + (a.flags ? compact_tiles(a.P) : 0)), dim3(256), 0, st,
+                     a);
   return hipGetLastError();
 }
 

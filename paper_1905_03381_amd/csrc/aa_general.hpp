@@ -35,10 +35,6 @@ struct GenArgs {
   float *acc_p;      // [d]
   int32_t *acc_cnt;  // kept count
   float *acc_gb;     // bias gradient
-  int32_t tail_compact;
-  int32_t *kept_pos;
-  int32_t *kept_count;
-  int32_t *ticket;
 };
 
 struct ApplyArgs {

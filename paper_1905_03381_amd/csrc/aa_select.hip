@@ -1,11 +1,11 @@
 // Keep draw + stable compaction (Algorithm 1) and batch assembly (gather).
 //
-// Compaction is two launches for any pool size: (1) one thread per candidate
-// draws / thresholds the keep flag, a wavefront ballot counts the wave's
-// survivors, an LDS sum gives the block's count, and the last block to arrive
-// turns the block counts into exclusive offsets; (2) one thread per candidate
-// ranks itself inside its wave with mbcnt on the ballot mask, adds the LDS
-// prefix of the waves before it and the block offset, and stores its position.
+// aa_shrink is two launches: one thread per candidate draws (or thresholds) the
+// keep flag, then one block per 2048-flag tile compacts (ballot + mbcnt + LDS
+// prefix, see aa_compact.hpp).  Up to kDirectCountMax candidates every tile
+// counts the flags before it by itself; larger pools insert a per-tile count
+// and a one-block scan of the tile counts.
+#include "aa_compact.hpp"
 #include "aa_select.hpp"
 
 namespace aa {
@@ -14,57 +14,52 @@ namespace {
 
 typedef unsigned int u4 __attribute__((ext_vector_type(4)));
 
+// One thread per candidate: the keep flag from a Philox draw against the keep
+// probability, or from a threshold on a criterion.
 template <int SRC>
-__global__ __launch_bounds__(kKeepBlock) void k_keep_count(const KeepArgs a) {
-  __shared__ int s_int[40];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int j = blockIdx.x * kKeepBlock + tid;
-  bool keep = false;
-  if (j < a.P) {
-    if (SRC == kFromProb) {
-      const float u = keep_uniform(a.key, (uint32_t)j);
-      keep = keep_decision(u, a.src[j], a.gamma, a.one_minus_gamma);
-      a.flags[j] = keep ? 1 : 0;
-    } else if (SRC == kFromCrit) {
-      keep = a.src[j] > *a.T;
-      a.flags[j] = keep ? 1 : 0;
-    } else {
-      keep = a.flags[j] != 0;
-    }
+__global__ __launch_bounds__(256) void k_keep_flags(const KeepArgs a) {
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  if (j >= a.P) return;
+  bool keep;
+  if (SRC == kFromProb) {
+    const float u = keep_uniform(a.key, (uint32_t)j);
+    keep = keep_decision(u, a.src[j], a.gamma, a.one_minus_gamma);
+  } else {
+    keep = a.src[j] > *a.T;
   }
-  const unsigned long long mask = __ballot(keep);
-  if (lane == 0) s_int[wave] = __popcll(mask);
-  __syncthreads();
-  if (tid == 0) a.blk_off[blockIdx.x] = s_int[0] + s_int[1] + s_int[2] + s_int[3];
-  __syncthreads();
-  if (last_block_arrives(a.ticket, &s_int[32])) {
-    const int nblk = gridDim.x;
-    int running = 0;
-    for (int t0 = 0; t0 < nblk; t0 += kKeepBlock) {
-      const int i = t0 + tid;
-      const int v = i < nblk ? a.blk_off[i] : 0;
-      int total;
-      const int excl = block_exclusive_scan(v, s_int, &total);
-      if (i < nblk) a.blk_off[i] = running + excl;
-      running += total;
-    }
-    if (tid == 0) *a.kept_count = running;
-  }
+  a.flags[j] = keep ? 1 : 0;
 }
 
-__global__ __launch_bounds__(kKeepBlock) void k_scatter(const ScatterArgs a) {
+// Compaction of the flags, one block per tile.
+__global__ __launch_bounds__(256) void k_compact(const CompactArgs c) {
   __shared__ int s_int[8];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int j = blockIdx.x * kKeepBlock + tid;
-  const bool keep = j < a.P && a.flags[j] != 0;
-  const unsigned long long mask = __ballot(keep);
-  const int rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
-                                             __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-  if (lane == 0) s_int[wave] = __popcll(mask);
+  tile_compact(c, blockIdx.x, s_int);
+}
+
+// Large pools: per-tile counts, then one block turns them into exclusive offsets.
+__global__ __launch_bounds__(256) void k_tile_counts(const uint8_t *flags, int P, int32_t *tile_off) {
+  __shared__ int s_int[8];
+  const int j0 = blockIdx.x * kCompactTile;
+  int cnt = 0;
+  for (int j = j0 + threadIdx.x; j < min(P, j0 + kCompactTile); j += 256) cnt += flags[j] != 0;
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off, kWave);
+  if ((threadIdx.x & 63) == 0) s_int[threadIdx.x >> 6] = cnt;
   __syncthreads();
-  int woff = 0;
-  for (int i = 0; i < wave; ++i) woff += s_int[i];
-  if (keep) a.kept_pos[a.blk_off[blockIdx.x] + woff + rank] = j;
+  if (threadIdx.x == 0) tile_off[blockIdx.x] = s_int[0] + s_int[1] + s_int[2] + s_int[3];
+}
+
+__global__ __launch_bounds__(1024) void k_scan_tiles(int32_t *tile_off, int ntiles) {
+  __shared__ int s_int[40];
+  int running = 0;
+  for (int t0 = 0; t0 < ntiles; t0 += 1024) {
+    const int i = t0 + threadIdx.x;
+    const int v = i < ntiles ? tile_off[i] : 0;
+    int total;
+    const int excl = block_exclusive_scan(v, s_int, &total);
+    if (i < ntiles) tile_off[i] = running + excl;
+    running += total;
+  }
 }
 
 __global__ void k_set_i32(int32_t *p, int32_t v) { *p = v; }
@@ -161,25 +156,30 @@ __global__ __launch_bounds__(256) void k_csr_copy(const GatherCsrArgs a) {
 
 }  // namespace
 
-hipError_t launch_keep_count(const KeepArgs &a, int source, hipStream_t st) {
-  if (a.P <= 0) {
-    hipLaunchKernelGGL(k_set_i32, dim3(1), dim3(1), 0, st, a.kept_count, 0);
-    return hipGetLastError();
-  }
-  const dim3 grid((a.P + kKeepBlock - 1) / kKeepBlock), block(kKeepBlock);
+hipError_t launch_keep_flags(const KeepArgs &a, int source, hipStream_t st) {
+  if (a.P <= 0) return hipSuccess;
+  const dim3 grid((a.P + 255) / 256), block(256);
   if (source == kFromProb)
-    hipLaunchKernelGGL((k_keep_count<kFromProb>), grid, block, 0, st, a);
-  else if (source == kFromCrit)
-    hipLaunchKernelGGL((k_keep_count<kFromCrit>), grid, block, 0, st, a);
+    hipLaunchKernelGGL((k_keep_flags<kFromProb>), grid, block, 0, st, a);
   else
-    hipLaunchKernelGGL((k_keep_count<kFromFlags>), grid, block, 0, st, a);
+    hipLaunchKernelGGL((k_keep_flags<kFromCrit>), grid, block, 0, st, a);
   return hipGetLastError();
 }
 
-hipError_t launch_scatter(const ScatterArgs &a, hipStream_t st) {
-  if (a.P <= 0) return hipSuccess;
-  const dim3 grid((a.P + kKeepBlock - 1) / kKeepBlock), block(kKeepBlock);
-  hipLaunchKernelGGL(k_scatter, grid, block, 0, st, a);
+hipError_t launch_compact(CompactArgs c, int32_t *tile_off_scratch, hipStream_t st) {
+  if (c.P <= 0) {
+    if (c.kept_count) hipLaunchKernelGGL(k_set_i32, dim3(1), dim3(1), 0, st, c.kept_count, 0);
+    return hipGetLastError();
+  }
+  const int ntiles = compact_tiles(c.P);
+  c.tile_off = nullptr;
+  if (c.P > kDirectCountMax) {
+    hipLaunchKernelGGL(k_tile_counts, dim3(ntiles), dim3(256), 0, st, c.flags, c.P,
+                       tile_off_scratch);
+    hipLaunchKernelGGL(k_scan_tiles, dim3(1), dim3(1024), 0, st, tile_off_scratch, ntiles);
+    c.tile_off = tile_off_scratch;
+  }
+  hipLaunchKernelGGL(k_compact, dim3(ntiles), dim3(256), 0, st, c);
   return hipGetLastError();
 }
 

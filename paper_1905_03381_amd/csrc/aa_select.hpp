@@ -2,10 +2,11 @@
 #pragma once
 
 #include "aa_common.hpp"
+#include "aa_compact.hpp"
 
 namespace aa {
 
-enum KeepSource : int { kFromProb = 0, kFromCrit = 1, kFromFlags = 2 };
+enum KeepSource : int { kFromProb = 0, kFromCrit = 1 };
 
 struct KeepArgs {
   const float *src;     // prob[P] (kFromProb) or crit[P] (kFromCrit)
@@ -13,17 +14,7 @@ struct KeepArgs {
   int32_t P;
   float gamma, one_minus_gamma;
   DrawKey key;
-  uint8_t *flags;       // [P] written (read for kFromFlags)
-  int32_t *blk_off;     // [nblk] per-block counts, then exclusive offsets
-  int32_t *kept_count;
-  int32_t *ticket;
-};
-
-struct ScatterArgs {
-  const uint8_t *flags;
-  int32_t P;
-  const int32_t *blk_off;
-  int32_t *kept_pos;
+  uint8_t *flags;       // [P] written
 };
 
 struct GatherArgs {
@@ -51,10 +42,12 @@ struct GatherCsrArgs {
   int64_t out_nnz_cap;
 };
 
-constexpr int kKeepBlock = 256;  // candidates per block of the keep/scatter kernels
+// Pools up to this size let every compaction tile count the flags before it directly.
+constexpr int kDirectCountMax = 1 << 18;
 
-hipError_t launch_keep_count(const KeepArgs &a, int source, hipStream_t stream);
-hipError_t launch_scatter(const ScatterArgs &a, hipStream_t stream);
+hipError_t launch_keep_flags(const KeepArgs &a, int source, hipStream_t stream);
+// Compact c.flags (c.tile_off is set here).  tile_off_scratch: P/2048 + 1 ints of workspace.
+hipError_t launch_compact(CompactArgs c, int32_t *tile_off_scratch, hipStream_t stream);
 hipError_t launch_gather(const GatherArgs &a, hipStream_t stream);
 hipError_t launch_gather_csr(const GatherCsrArgs &a, hipStream_t stream);
 

@@ -1,0 +1,205 @@
+"""GPU parity of the CSR path (sparse linear-SVM and token-list shapes) against the oracle."""
+import numpy as np
+import pytest
+import scipy.sparse as sp
+import torch
+
+from paper_1905_03381_amd import api, synth
+
+from gpu_util import (RTOL, abs_dot_scale, assert_close_scaled, assert_logit_prob, clear_draws,
+                      csr_features, dev, host, scalar_dev)
+
+pytestmark = pytest.mark.gpu
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+@pytest.fixture(scope="module")
+def sparse():
+    """Down-scaled sparse config: 30,000 rows, d = 2^16, about 100 entries per row."""
+    rowptr, col, val, y, _ = synth.sparse_svm(n=30_000, d=1 << 16, mean_nnz=100, threads=4)
+    return rowptr, col, val, y, 1 << 16
+
+
+@pytest.fixture(scope="module")
+def ws():
+    return api.Workspace(1 << 16, 1 << 16)
+
+
+def test_csr_score_and_fused_keep(ref, ws, sparse):
+    rowptr, col, val, y, d = sparse
+    n = rowptr.size - 1
+    P = 20_000
+    r = rng(1)
+    phi = (3.0 * r.standard_normal(d)).astype(np.float32)
+    idx = r.permutation(n)[:P].astype(np.int32)
+    Fh = ref.Features.csr(rowptr, col, val, d)
+    F = csr_features(rowptr, col, val, d)
+    ref_logit, ref_prob = ref.assistant_score(Fh, idx, P, phi, bias=0.3)
+    S = abs_dot_scale(Fh, idx, phi)
+    logit, prob = torch.zeros(P, device="cuda"), torch.zeros(P, device="cuda")
+    api.assistant_score(F, dev(idx), P, dev(phi), scalar_dev(0.3), logit, prob)
+    assert_logit_prob(host(logit), host(prob), ref_logit, ref_prob, S, bias=0.3)
+    gamma, seed, step = 0.1, 3, 8
+    keep_ref, _ = ref.shrink(ref_prob, gamma, seed, step)
+    keep = torch.zeros(P, dtype=torch.uint8, device="cuda")
+    pos = torch.full((P,), -1, dtype=torch.int32, device="cuda")
+    cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    api.score_shrink(F, dev(idx), P, dev(phi), scalar_dev(0.3), gamma, seed, step, None, prob, keep,
+                     pos, cnt, ws)
+    k = host(keep)
+    clear = clear_draws(ref, ref_prob, gamma, seed, step)
+    assert np.array_equal(k[clear], keep_ref[clear])
+    m = int(host(cnt)[0])
+    assert m == int(k.sum()) and np.array_equal(host(pos)[:m], np.flatnonzero(k))
+
+
+def test_csr_all_ones_values(ref, ws):
+    """Token lists: val == NULL means every entry is 1; repeated tokens add."""
+    rowptr, col, val, len_s, len_t, d = synth.sentence_pairs(n=5000, vocab=2000)
+    r = rng(2)
+    phi = (0.2 * r.standard_normal(d)).astype(np.float32)
+    Fh = ref.Features.csr(rowptr, col, None, d)
+    F = csr_features(rowptr, col, None, d)
+    P = 5000
+    ref_logit, ref_prob = ref.assistant_score(Fh, None, P, phi)
+    logit, prob = torch.zeros(P, device="cuda"), torch.zeros(P, device="cuda")
+    api.assistant_score(F, None, P, dev(phi), None, logit, prob)
+    assert_logit_prob(host(logit), host(prob), ref_logit, ref_prob, abs_dot_scale(Fh, np.arange(P), phi))
+    # with the length features as values
+    Fh2 = ref.Features.csr(rowptr, col, val, d)
+    F2 = csr_features(rowptr, col, val, d)
+    ref_logit, ref_prob = ref.assistant_score(Fh2, None, P, phi, bias=-0.5)
+    api.assistant_score(F2, None, P, dev(phi), scalar_dev(-0.5), logit, prob)
+    assert_logit_prob(host(logit), host(prob), ref_logit, ref_prob,
+                      abs_dot_scale(Fh2, np.arange(P), phi), bias=-0.5)
+
+
+def _dots(Fh, ids, v):
+    """x_r . v for the listed CSR rows, float64, by scipy."""
+    S = sp.csr_matrix((Fh.val.astype(np.float64), Fh.col, Fh.rowptr), shape=(Fh.n, Fh.d))
+    return S[np.asarray(ids)] @ v.astype(np.float64)
+
+
+def _col_abs_sum(Fh, ids, d):
+    out = np.zeros(d)
+    for i in ids:
+        lo, hi = Fh.rowptr[i], Fh.rowptr[i + 1]
+        v = np.ones(hi - lo) if Fh.val is None else np.abs(Fh.val[lo:hi].astype(np.float64))
+        np.add.at(out, Fh.col[lo:hi], v)
+    return out
+
+
+def test_csr_svm_step_and_assistant_update(ref, ws, sparse):
+    rowptr, col, val, y, d = sparse
+    n = rowptr.size - 1
+    m = 3000
+    r = rng(3)
+    w0 = (2.0 * r.standard_normal(d)).astype(np.float32)
+    phi0 = r.standard_normal(d).astype(np.float32)
+    rows = r.permutation(n)[:m].astype(np.int32)
+    Fh = ref.Features.csr(rowptr, col, val, d)
+    F = csr_features(rowptr, col, val, d)
+    lam, lr, T, lr_a, b0 = 1e-3, 0.5, 0.3, 0.2, 0.1
+    w_ref, loss_ref = ref.svm_sgd_step(Fh, y, rows, m, w0, lam, lr)
+    S = abs_dot_scale(Fh, rows, w0)
+    dots = _dots(Fh, rows, w0) * y[rows]
+    assert np.all(np.abs(dots - 1) > RTOL * S)
+    w = dev(w0)
+    loss = torch.zeros(m, device="cuda")
+    api.svm_sgd_step(F, dev(y), dev(rows), scalar_dev(m, torch.int32), m, w, lam, lr, 0.0, loss, ws)
+    assert_close_scaled(host(loss), loss_ref, S, "loss")
+    absx = _col_abs_sum(Fh, rows[dots < 1], d)
+    assert_close_scaled(host(w), w_ref, np.abs(w0.astype(np.float64)) + lr / m * absx, "w")
+    phi_ref, b_ref = ref.assistant_update(Fh, rows, m, loss_ref, T, phi0, b0, lr_a)
+    phi, b = dev(phi0), scalar_dev(b0)
+    api.assistant_update(F, dev(rows), scalar_dev(m, torch.int32), m, dev(loss_ref), scalar_dev(T),
+                         phi, b, lr_a, 0.0, ws)
+    absx = _col_abs_sum(Fh, rows, d)
+    assert_close_scaled(host(phi), phi_ref, np.abs(phi0.astype(np.float64)) + lr_a / m * absx, "phi")
+    assert abs(float(host(b)[0]) - b_ref) <= RTOL * (abs(b0) + lr_a)
+    # m = 0 leaves everything alone
+    w = dev(w0)
+    api.svm_sgd_step(F, dev(y), dev(rows), scalar_dev(0, torch.int32), m, w, lam, lr, 0.0, None, ws)
+    assert np.array_equal(host(w), w0)
+
+
+def test_csr_fused_step(ref, ws, sparse):
+    rowptr, col, val, y, d = sparse
+    n = rowptr.size - 1
+    P = 8000
+    r = rng(4)
+    w0 = (2.0 * r.standard_normal(d)).astype(np.float32)
+    phi0 = (2.0 * r.standard_normal(d)).astype(np.float32)
+    idx = r.permutation(n)[:P].astype(np.int32)
+    Fh = ref.Features.csr(rowptr, col, val, d)
+    F = csr_features(rowptr, col, val, d)
+    b0, gamma, step, lam, lr, T, lr_a = 0.0, 0.1, 3, 1e-3, 0.5, 0.1, 0.3
+    for seed in range(1, 20):   # first Philox key with no draw inside the rounding band
+        out = ref.step(Fh, y, idx, P, w0, phi0, b0, gamma, seed, step, lam, lr, T, lr_a)
+        if clear_draws(ref, out["prob"], gamma, seed, step).all():
+            break
+    else:
+        raise AssertionError("no clear seed")
+    kept = out["kept_ids"]
+    dots = _dots(Fh, kept, w0) * y[kept]
+    # rows whose margin sits within rounding of the hinge kink may fall on either side
+    on_kink = np.abs(dots - 1) <= RTOL * abs_dot_scale(Fh, kept, w0)
+    assert on_kink.sum() <= 3
+    w, phi, b = dev(w0), dev(phi0), scalar_dev(b0)
+    Tt = scalar_dev(T)
+    cfg = api.step_config(gamma, lam, lr, lr_a, 0.0, seed, step, Tt)
+    prob = torch.zeros(P, device="cuda")
+    keep = torch.zeros(P, dtype=torch.uint8, device="cuda")
+    pos = torch.zeros(P, dtype=torch.int32, device="cuda")
+    ids = torch.zeros(P, dtype=torch.int32, device="cuda")
+    loss = torch.zeros(P, device="cuda")
+    cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    api.fused_step(F, dev(y), dev(idx), P, w, phi, b, cfg, None, prob, keep, pos, ids, loss, cnt, ws)
+    m = out["m"]
+    assert int(host(cnt)[0]) == m
+    assert np.array_equal(host(keep), out["keep"])
+    assert np.array_equal(host(pos)[:m], out["kept_pos"])
+    assert np.array_equal(host(ids)[:m], out["kept_ids"])
+    assert_close_scaled(host(loss)[:m], out["loss"], abs_dot_scale(Fh, kept, w0), "loss")
+    absx_a = _col_abs_sum(Fh, kept[dots < 1], d)
+    assert_close_scaled(host(w), out["w"], np.abs(w0.astype(np.float64)) + lr / m * absx_a, "w",
+                        atol=lr / m * _col_abs_sum(Fh, kept[on_kink], d))
+    absx = _col_abs_sum(Fh, kept, d)
+    assert_close_scaled(host(phi), out["phi"], np.abs(phi0.astype(np.float64)) + lr_a / m * absx,
+                        "phi")
+
+
+def test_gather_csr(ref, ws, sparse):
+    rowptr, col, val, y, d = sparse
+    n = rowptr.size - 1
+    P = 5000
+    r = rng(5)
+    idx = r.permutation(n)[:P].astype(np.int32)
+    kept_pos = np.sort(r.choice(P, 2100, replace=False)).astype(np.int32)
+    Fh = ref.Features.csr(rowptr, col, val, d)
+    F = csr_features(rowptr, col, val, d)
+    cap = int(np.diff(rowptr)[idx[kept_pos]].sum())
+    want_ptr, want_col, want_val = ref.gather_csr(Fh, idx, kept_pos, cap)
+    out_ptr = torch.full((P + 1,), -1, dtype=torch.int64, device="cuda")
+    out_col = torch.full((cap,), -1, dtype=torch.int32, device="cuda")
+    out_val = torch.full((cap,), -1.0, device="cuda")
+    pos_d = torch.zeros(P, dtype=torch.int32, device="cuda")
+    pos_d[:2100] = dev(kept_pos)
+    api.gather_csr(F, dev(idx), pos_d, scalar_dev(2100, torch.int32), P, out_ptr, out_col, out_val,
+                   cap, ws)
+    assert np.array_equal(host(out_ptr)[:2101], want_ptr)
+    assert np.array_equal(host(out_col), want_col) and np.array_equal(host(out_val), want_val)
+    # capacity too small: row pointers complete, rows past the capacity not copied
+    small = cap // 2
+    out_col2 = torch.full((small,), -1, dtype=torch.int32, device="cuda")
+    out_val2 = torch.full((small,), -1.0, device="cuda")
+    api.gather_csr(F, dev(idx), pos_d, scalar_dev(2100, torch.int32), P, out_ptr, out_col2, out_val2,
+                   small, ws)
+    ptr = host(out_ptr)[:2101]
+    assert np.array_equal(ptr, want_ptr) and ptr[-1] > small
+    fits = int(np.searchsorted(want_ptr, small, side="right") - 1)
+    assert np.array_equal(host(out_col2)[:want_ptr[fits]], want_col[:want_ptr[fits]])
+    assert np.all(host(out_col2)[want_ptr[fits]:] == -1)

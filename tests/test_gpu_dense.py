@@ -87,6 +87,22 @@ def test_shrink_bit_exact(ref, ws, P, gamma):
     assert int(host(cnt)[0]) == m and np.array_equal(host(pos2)[:m], pos_ref)
 
 
+def test_shrink_pool_beyond_direct_counting(ref):
+    """Pools above 2^18 candidates insert a per-tile count and a scan of the tile counts."""
+    P = 300_007
+    big = api.Workspace(P, 128)
+    prob = rng(8).random(P).astype(np.float32)
+    keep_ref, pos_ref = ref.shrink(prob, 0.05, 7, 3)
+    keep = torch.zeros(P, dtype=torch.uint8, device="cuda")
+    pos = torch.full((P,), -1, dtype=torch.int32, device="cuda")
+    cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    api.shrink(dev(prob), P, 0.05, 7, 3, keep, pos, cnt, big)
+    m = pos_ref.size
+    assert int(host(cnt)[0]) == m
+    assert np.array_equal(host(keep), keep_ref) and np.array_equal(host(pos)[:m], pos_ref)
+    assert np.all(host(pos)[m:] == -1)
+
+
 def test_shrink_large_seed_and_step(ref, ws):
     P = 5000
     prob = rng(1).random(P).astype(np.float32)
