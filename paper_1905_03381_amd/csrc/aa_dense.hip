@@ -1,14 +1,24 @@
-// Dense row passes for gfx950 with the model vectors held in registers.
+// Dense row passes for gfx950.
 //
 // One wave64 (or an aligned group of LPR lanes for short rows) owns a feature
 // row: each lane loads VPL 128-bit pieces, so a wave-wide load instruction
-// covers 1 KiB of contiguous row.  phi and w sit in registers for the whole
-// kernel, dot products are folded with wave shuffles, and the gradient sums of
-// the kept rows accumulate per lane before one LDS tree per block.  Waves own
-// contiguous chunks of the pool, so row ids, labels and the Philox draws are
-// produced 64 at a time, one per lane, and broadcast per row.
+// covers 1 KiB of contiguous row.  A wave owns a contiguous chunk of the pool,
+// so row ids, labels and the Philox draws are produced 64 at a time, one per
+// lane, and broadcast per row.  All loads of up to RIF rows are issued before
+// the first is consumed (at the dense configuration a wave's whole share of the
+// pool is in flight at once); phi and w are staged in LDS once per block; dot
+// products are folded with DPP row operations and lane reads (no LDS traffic);
+// the gradient sums of the kept rows accumulate per lane in registers and are
+// combined per block in LDS in a fixed order.
 #include "aa_compact.hpp"
 #include "aa_dense.hpp"
+
+#ifndef AA_NW_D1024
+#define AA_NW_D1024 16   // waves per block of the gradient passes at 512 < d <= 1024
+#endif
+#ifndef AA_RIF_D1024
+#define AA_RIF_D1024 2   // rows in flight per wave there
+#endif
 
 namespace aa {
 
@@ -38,9 +48,37 @@ __device__ __forceinline__ int wave_sum_int(int v) {
   return v;
 }
 
-// Fold the row groups of a wave, then the waves of the block (LDS tree, fixed
-// order), and let wave 0 store the block's partial vector.
-template <int LPR, int VPL>
+// v + (v moved by a DPP control): one VALU instruction, no LDS.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v) {
+  const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true);
+  return v + __int_as_float(moved);
+}
+
+__device__ __forceinline__ float lane_read(float v, int lane) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+
+// Sum over aligned groups of LPR lanes (16, 32 or 64); every lane of a group
+// gets the same bits.  Inside a 16-lane row: quad swaps, half mirror, mirror.
+template <int LPR>
+__device__ __forceinline__ float row_group_sum(float v, int lane) {
+  v = dpp_add<0xB1>(v);   // quad_perm [1,0,3,2]
+  v = dpp_add<0x4E>(v);   // quad_perm [2,3,0,1]
+  v = dpp_add<0x141>(v);  // row_half_mirror
+  v = dpp_add<0x140>(v);  // row_mirror
+  if (LPR == 16) return v;
+  const float s0 = lane_read(v, 0), s1 = lane_read(v, 16), s2 = lane_read(v, 32),
+              s3 = lane_read(v, 48);
+  if (LPR == 32) return lane < 32 ? s0 + s1 : s2 + s3;
+  return (s0 + s1) + (s2 + s3);
+}
+
+// Combine the per-lane sums of the block's waves in a fixed order and store the
+// block's partial vector: fold the row groups inside a wave, halve the waves
+// through LDS until at most eight are left, then let one thread per 128-bit
+// column add those in wave order.  `red` holds SLOTS * ROW4 f4.
+template <int LPR, int VPL, int SLOTS>
 __device__ __forceinline__ void block_reduce_store(f4 (&acc)[VPL], f4 *red, float *out, int lane,
                                                    int wave, int nw) {
   constexpr int ROW4 = LPR * VPL;
@@ -53,8 +91,10 @@ __device__ __forceinline__ void block_reduce_store(f4 (&acc)[VPL], f4 *red, floa
       acc[v].w = fold_groups<LPR>(acc[v].w);
     }
   }
-  for (int s = nw >> 1; s >= 1; s >>= 1) {
-    if (wave >= s && wave < 2 * s && lane < LPR) {
+  int live = nw;
+  while (live > SLOTS) {
+    const int s = live >> 1;
+    if (wave >= s && wave < live && lane < LPR) {
 #pragma unroll
       for (int v = 0; v < VPL; ++v) red[(wave - s) * ROW4 + v * LPR + lane] = acc[v];
     }
@@ -64,15 +104,23 @@ __device__ __forceinline__ void block_reduce_store(f4 (&acc)[VPL], f4 *red, floa
       for (int v = 0; v < VPL; ++v) acc[v] += red[wave * ROW4 + v * LPR + lane];
     }
     __syncthreads();
+    live = s;
   }
-  if (wave == 0 && lane < LPR) {
+  if (wave < live && lane < LPR) {
 #pragma unroll
-    for (int v = 0; v < VPL; ++v) reinterpret_cast<f4 *>(out)[v * LPR + lane] = acc[v];
+    for (int v = 0; v < VPL; ++v) red[wave * ROW4 + v * LPR + lane] = acc[v];
   }
+  __syncthreads();
+  for (int c = threadIdx.x; c < ROW4; c += blockDim.x) {
+    f4 t = red[c];
+    for (int q = 1; q < live; ++q) t += red[q * ROW4 + c];
+    reinterpret_cast<f4 *>(out)[c] = t;
+  }
+  __syncthreads();
 }
 
-template <int LPR, int VPL, int MODE, int NWMAX>
-__global__ __launch_bounds__(NWMAX * 64) void k_rows_pass(const PassArgs a) {
+template <int LPR, int VPL, int MODE, int NW, int RIF>
+__global__ __launch_bounds__(NW * 64) void k_rows_pass(const PassArgs a) {
   constexpr bool POOL = (MODE & kPool) != 0;
   constexpr bool SVM = (MODE & kSvm) != 0;
   constexpr bool ASSIST = (MODE & kAssist) != 0;
@@ -81,69 +129,102 @@ __global__ __launch_bounds__(NWMAX * 64) void k_rows_pass(const PassArgs a) {
   constexpr int G = kWave / LPR;  // rows per wave iteration
   constexpr int ROW4 = LPR * VPL;
   constexpr int NVEC = (SVM ? 1 : 0) + (ASSIST ? 1 : 0);
+  constexpr int NT = NW * 64;
+  constexpr int STG = (ROW4 + NT - 1) / NT;  // staged 128-bit pieces per thread and vector
+  constexpr int SLOTS = VPL == 8 ? 4 : (NW < 8 ? NW : 8);  // LDS slots of the block reduction
 
-  __shared__ int s_int[40];
+  __shared__ int s_int[20];
   __shared__ float s_flt[20];
-  __shared__ f4 s_red[GRAD ? (NWMAX / 2) * ROW4 : 1];
+  __shared__ f4 s_w[SVM ? ROW4 : 1];
+  __shared__ f4 s_phi[NEED_PHI ? ROW4 : 1];
+  __shared__ f4 s_red[GRAD ? SLOTS * ROW4 : 1];
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int grp = lane / LPR, sub = lane % LPR;
+  const f4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
   int total = a.count_max;
   if (!POOL && a.m_dev) total = min(max(*a.m_dev, 0), a.count_max);
 
   // balanced contiguous chunk of rows for this wave
-  const int nwaves = gridDim.x * nw, gwave = blockIdx.x * nw + wave;
+  const int nwaves = gridDim.x * NW, gwave = blockIdx.x * NW + wave;
   const int per = total / nwaves, rem = total % nwaves;
   const int lo = gwave * per + min(gwave, rem);
   const int hi = lo + per + (gwave < rem ? 1 : 0);
 
-  f4 wv[VPL], pv[VPL], gw[VPL], gp[VPL];
+  // ---- start-up, ordered so that the row loads leave as early as possible:
+  // row ids of the first 64 rows, model vectors into registers, first rows,
+  // labels and draws, then the model vectors into LDS behind one barrier.
+  int base = lo;
+  int cnt = min(kWave, hi - base);  // rows of the current group of up to 64 (<= 0: none)
+  int row_l = 0;
+  if (lane < cnt) row_l = a.rows ? a.rows[base + lane] : base + lane;
+
+  f4 st_w[STG], st_p[STG];
 #pragma unroll
-  for (int v = 0; v < VPL; ++v) {
-    const int c = v * LPR + sub;
-    const bool ok = c < a.d4;
-    const f4 zero = {0.f, 0.f, 0.f, 0.f};
-    wv[v] = (SVM && ok) ? reinterpret_cast<const f4 *>(a.w)[c] : zero;
-    pv[v] = (NEED_PHI && ok) ? reinterpret_cast<const f4 *>(a.phi)[c] : zero;
-    gw[v] = zero;
-    gp[v] = zero;
+  for (int q = 0; q < STG; ++q) {
+    const int c = q * NT + threadIdx.x;
+    st_w[q] = (SVM && c < a.d4) ? reinterpret_cast<const f4 *>(a.w)[c] : zero4;
+    st_p[q] = (NEED_PHI && c < a.d4) ? reinterpret_cast<const f4 *>(a.phi)[c] : zero4;
   }
   const float b = (NEED_PHI && a.bias) ? *a.bias : 0.f;
   const float T = ASSIST ? *a.T : 0.f;
-  float gb = 0.f;
-  int kept = 0;
 
-  for (int base = lo; base < hi; base += kWave) {
-    const int cnt = min(kWave, hi - base);
-    // one row per lane: id, label, draw
-    const int j_l = base + lane;
-    int row_l = 0;
-    float y_l = 0.f, u_l = 2.f, lin_l = 0.f;
-    if (lane < cnt) {
-      row_l = a.rows ? a.rows[j_l] : j_l;
-      if (SVM) y_l = a.y[row_l];
-      if (POOL && a.do_keep) u_l = keep_uniform(a.key, (uint32_t)j_l);
-      if (ASSIST && !SVM) lin_l = a.loss_in[j_l];
-    }
-    const int iters = (cnt + G - 1) / G;
-    f4 xa[VPL], xb[VPL];
+  f4 x[RIF][VPL];
+  auto issue_rows = [&](int it0) {  // every load of the next RIF rows, before any is used
 #pragma unroll
-    for (int v = 0; v < VPL; ++v) xb[v] = f4{0.f, 0.f, 0.f, 0.f};
-    auto load = [&](int it, f4(&buf)[VPL]) {
-      const int li = it * G + grp;
-      const int row = __shfl(row_l, li, kWave);
+    for (int r = 0; r < RIF; ++r) {
+      const int li = (it0 + r) * G + grp;
+      const int row = __shfl(row_l, li & 63, kWave);
       const f4 *xr = reinterpret_cast<const f4 *>(a.x + (int64_t)row * a.ld);
 #pragma unroll
       for (int v = 0; v < VPL; ++v) {
         const int c = v * LPR + sub;
-        const f4 zero = {0.f, 0.f, 0.f, 0.f};
-        buf[v] = (li < cnt && c < a.d4) ? __builtin_nontemporal_load(xr + c) : zero;
+        x[r][v] = (li < cnt && c < a.d4) ? __builtin_nontemporal_load(xr + c) : zero4;
       }
-    };
-    load(0, xa);
-    for (int it = 0; it < iters; ++it) {
-      if (it + 1 < iters) load(it + 1, xb);
+    }
+  };
+  float y_l = 0.f, u_l = 2.f, lin_l = 0.f;
+  auto lane_inputs = [&]() {  // one row per lane: label, draw, incoming loss
+    y_l = 0.f;
+    u_l = 2.f;
+    lin_l = 0.f;
+    if (lane < cnt) {
+      if (SVM) y_l = a.y[row_l];
+      if (POOL && a.do_keep) u_l = keep_uniform(a.key, (uint32_t)(base + lane));
+      if (ASSIST && !SVM) lin_l = a.loss_in[base + lane];
+    }
+  };
+  if (cnt > 0) {
+    issue_rows(0);
+    lane_inputs();
+  }
+#pragma unroll
+  for (int q = 0; q < STG; ++q) {
+    const int c = q * NT + threadIdx.x;
+    if (c < ROW4) {
+      if (SVM) s_w[c] = st_w[q];
+      if (NEED_PHI) s_phi[c] = st_p[q];
+    }
+  }
+  __syncthreads();
+
+  f4 gw[VPL], gp[VPL];
+#pragma unroll
+  for (int v = 0; v < VPL; ++v) {
+    gw[v] = zero4;
+    gp[v] = zero4;
+  }
+  float gb = 0.f;
+  int kept = 0;
+  int it0 = 0;
+
+  while (cnt > 0) {
+    const int iters = (cnt + G - 1) / G;
+#pragma unroll
+    for (int r = 0; r < RIF; ++r) {
+      const int it = it0 + r;
+      if (it >= iters) break;
       const int li = it * G + grp;
       const bool live = li < cnt;
       const int j = base + li;
@@ -152,12 +233,12 @@ __global__ __launch_bounds__(NWMAX * 64) void k_rows_pass(const PassArgs a) {
       if (NEED_PHI) {
         float dp = 0.f;
 #pragma unroll
-        for (int v = 0; v < VPL; ++v) dp = dot4(xa[v], pv[v], dp);
-        dp = group_sum<LPR>(dp);
+        for (int v = 0; v < VPL; ++v) dp = dot4(x[r][v], s_phi[v * LPR + sub], dp);
+        dp = row_group_sum<LPR>(dp, lane);
         const float s = dp + b;
         g = sigmoidf_(s);
         if (POOL) {
-          const float u = __shfl(u_l, li, kWave);
+          const float u = __shfl(u_l, li & 63, kWave);
           if (a.do_keep) keep = live && keep_decision(u, g, a.gamma, a.one_minus_gamma);
           if (sub == 0 && live) {
             if (a.logit) a.logit[j] = s;
@@ -167,8 +248,8 @@ __global__ __launch_bounds__(NWMAX * 64) void k_rows_pass(const PassArgs a) {
         }
       }
       if (GRAD) {
-        const float yy = SVM ? __shfl(y_l, li, kWave) : 0.f;
-        const float lin = (ASSIST && !SVM) ? __shfl(lin_l, li, kWave) : 0.f;
+        const float yy = SVM ? __shfl(y_l, li & 63, kWave) : 0.f;
+        const float lin = (ASSIST && !SVM) ? __shfl(lin_l, li & 63, kWave) : 0.f;
         bool any = true;
         if (LPR == kWave) any = __builtin_amdgcn_readfirstlane((int)keep) != 0;
         if (any) {
@@ -176,34 +257,47 @@ __global__ __launch_bounds__(NWMAX * 64) void k_rows_pass(const PassArgs a) {
           if (SVM) {
             float dw = 0.f;
 #pragma unroll
-            for (int v = 0; v < VPL; ++v) dw = dot4(xa[v], wv[v], dw);
-            dw = group_sum<LPR>(dw);
+            for (int v = 0; v < VPL; ++v) dw = dot4(x[r][v], s_w[v * LPR + sub], dw);
+            dw = row_group_sum<LPR>(dw, lane);
             const float marg = yy * dw;
             loss = fmaxf(0.f, 1.f - marg);
             if (sub == 0 && keep && a.loss_out) a.loss_out[j] = loss;
             const float cw = (keep && marg < 1.f) ? yy : 0.f;  // -d hinge / d margin, times y
 #pragma unroll
-            for (int v = 0; v < VPL; ++v) gw[v] = axpy4(cw, xa[v], gw[v]);
+            for (int v = 0; v < VPL; ++v) gw[v] = axpy4(cw, x[r][v], gw[v]);
           }
           if (ASSIST) {
             const float z = loss > T ? 1.f : 0.f;       // label: Boss loss above the threshold
             const float resid = keep ? g - z : 0.f;     // d cross-entropy / d logit
 #pragma unroll
-            for (int v = 0; v < VPL; ++v) gp[v] = axpy4(resid, xa[v], gp[v]);
+            for (int v = 0; v < VPL; ++v) gp[v] = axpy4(resid, x[r][v], gp[v]);
             if (sub == 0) gb += resid;
           }
           if (sub == 0 && keep) kept += 1;
         }
       }
-#pragma unroll
-      for (int v = 0; v < VPL; ++v) xa[v] = xb[v];
+    }
+    // next rows: the same group of 64, or the next group
+    it0 += RIF;
+    if (it0 >= iters) {
+      it0 = 0;
+      base += kWave;
+      cnt = min(kWave, hi - base);
+      if (cnt > 0) {
+        row_l = lane < cnt ? (a.rows ? a.rows[base + lane] : base + lane) : 0;
+        issue_rows(0);
+        lane_inputs();
+      }
+    } else {
+      issue_rows(it0);
     }
   }
 
   if (GRAD) {
     float *part = a.partial + (size_t)blockIdx.x * NVEC * (ROW4 * 4);
-    if (SVM) block_reduce_store<LPR, VPL>(gw, s_red, part, lane, wave, nw);
-    if (ASSIST) block_reduce_store<LPR, VPL>(gp, s_red, part + (SVM ? ROW4 * 4 : 0), lane, wave, nw);
+    if (SVM) block_reduce_store<LPR, VPL, SLOTS>(gw, s_red, part, lane, wave, NW);
+    if (ASSIST)
+      block_reduce_store<LPR, VPL, SLOTS>(gp, s_red, part + (SVM ? ROW4 * 4 : 0), lane, wave, NW);
     const int kw = wave_sum_int(kept);
     const float gbw = group_sum<kWave>(gb);
     if (lane == 0) {
@@ -214,7 +308,7 @@ __global__ __launch_bounds__(NWMAX * 64) void k_rows_pass(const PassArgs a) {
     if (threadIdx.x == 0) {
       int ks = 0;
       float gs = 0.f;
-      for (int i = 0; i < nw; ++i) {
+      for (int i = 0; i < NW; ++i) {
         ks += s_int[i];
         gs += s_flt[i];
       }
@@ -225,14 +319,17 @@ __global__ __launch_bounds__(NWMAX * 64) void k_rows_pass(const PassArgs a) {
   if (GRAD && a.t_upd && blockIdx.x == 0 && threadIdx.x == 0) *a.t_snap = *a.t_upd;
 }
 
+constexpr int kFinCols4 = 4;    // 128-bit columns reduced by one finalize block
+constexpr int kFinGroups = 64;  // partial groups per column (256 threads)
+
 // Sum the block partials in a fixed order and apply the SGD updates; extra
 // blocks compact the keep flags of a pool pass, one tile each.
 __global__ __launch_bounds__(256) void k_finalize(const FinalizeArgs a) {
-  __shared__ f4 s_acc[2][16][16];
+  __shared__ f4 s_acc[2][kFinGroups][kFinCols4];
   __shared__ int s_int[40];
   __shared__ float s_flt[8];
   const int tid = threadIdx.x;
-  const int nred = a.d_pad / 64;
+  const int nred = a.d_pad / (4 * kFinCols4);
 
   if ((int)blockIdx.x >= nred) {
     CompactArgs c;
@@ -272,32 +369,36 @@ __global__ __launch_bounds__(256) void k_finalize(const FinalizeArgs a) {
   }
 
   if (m > 0) {
-    const int c4 = tid & 15, pg = tid >> 4;
-    const int col4 = blockIdx.x * 16 + c4;
+    // kFinCols4 128-bit columns per block, kFinGroups groups of partials each summed in
+    // block order, then the groups in a fixed LDS tree
+    const int c4 = tid % kFinCols4, pg = tid / kFinCols4;
+    const int col4 = blockIdx.x * kFinCols4 + c4;
     const int row4 = a.d_pad / 4;
     const f4 zero = {0.f, 0.f, 0.f, 0.f};
     f4 acc0 = zero, acc1 = zero;
     const f4 *p = reinterpret_cast<const f4 *>(a.partial);
     if (a.nvec == 2) {
 #pragma unroll 4
-      for (int blk = pg; blk < a.nblk; blk += 16) {
+      for (int blk = pg; blk < a.nblk; blk += kFinGroups) {
         acc0 += p[(size_t)(blk * 2) * row4 + col4];
         acc1 += p[(size_t)(blk * 2 + 1) * row4 + col4];
       }
     } else {
 #pragma unroll 4
-      for (int blk = pg; blk < a.nblk; blk += 16) acc0 += p[(size_t)blk * row4 + col4];
+      for (int blk = pg; blk < a.nblk; blk += kFinGroups) acc0 += p[(size_t)blk * row4 + col4];
     }
     s_acc[0][pg][c4] = acc0;
     s_acc[1][pg][c4] = acc1;
     __syncthreads();
-    if (pg == 0) {
-      f4 g0 = zero, g1 = zero;
-#pragma unroll
-      for (int q = 0; q < 16; ++q) {
-        g0 += s_acc[0][q][c4];
-        g1 += s_acc[1][q][c4];
+    for (int s = kFinGroups / 2; s >= 1; s >>= 1) {
+      if (pg < s) {
+        s_acc[0][pg][c4] += s_acc[0][pg + s][c4];
+        s_acc[1][pg][c4] += s_acc[1][pg + s][c4];
       }
+      __syncthreads();
+    }
+    if (pg == 0) {
+      const f4 g0 = s_acc[0][0][c4], g1 = s_acc[1][0][c4];
       const float inv_m = 1.f / (float)m;
       const f4 gw = g0;
       const f4 gp = a.w ? g1 : g0;
@@ -365,35 +466,40 @@ Shape pick_shape(int32_t d) {
   return {64, 8};
 }
 
+// Waves per block: passes with gradient sums use one fat block per CU (few block
+// partials); the 1024-wide layout runs 16 waves of 128 registers, the others 8.
 int waves_per_block(const Shape &s, int mode) {
   const bool grad = (mode & (kSvm | kAssist)) != 0;
   if (!grad) return 4;
-  return s.vpl == 8 ? 8 : 16;
+  return s.vpl == 4 ? AA_NW_D1024 : 8;
 }
 
-template <int LPR, int VPL, int NWMAX>
-hipError_t launch_mode(const PassArgs &a, int mode, int nblk, int nw, hipStream_t st) {
-  const dim3 grid(nblk), block(nw * 64);
+template <int LPR, int VPL, int NW, int RIF>
+hipError_t launch_grad(const PassArgs &a, int mode, int nblk, hipStream_t st) {
+  const dim3 grid(nblk), block(NW * 64);
   switch (mode) {
-    case kPool:
-      hipLaunchKernelGGL((k_rows_pass<LPR, VPL, kPool, NWMAX>), grid, block, 0, st, a);
-      break;
     case kSvm:
-      hipLaunchKernelGGL((k_rows_pass<LPR, VPL, kSvm, NWMAX>), grid, block, 0, st, a);
+      hipLaunchKernelGGL((k_rows_pass<LPR, VPL, kSvm, NW, RIF>), grid, block, 0, st, a);
       break;
     case kAssist:
-      hipLaunchKernelGGL((k_rows_pass<LPR, VPL, kAssist, NWMAX>), grid, block, 0, st, a);
+      hipLaunchKernelGGL((k_rows_pass<LPR, VPL, kAssist, NW, RIF>), grid, block, 0, st, a);
       break;
     case kSvm | kAssist:
-      hipLaunchKernelGGL((k_rows_pass<LPR, VPL, kSvm | kAssist, NWMAX>), grid, block, 0, st, a);
+      hipLaunchKernelGGL((k_rows_pass<LPR, VPL, kSvm | kAssist, NW, RIF>), grid, block, 0, st, a);
       break;
     case kPool | kSvm | kAssist:
-      hipLaunchKernelGGL((k_rows_pass<LPR, VPL, kPool | kSvm | kAssist, NWMAX>), grid, block, 0,
+      hipLaunchKernelGGL((k_rows_pass<LPR, VPL, kPool | kSvm | kAssist, NW, RIF>), grid, block, 0,
                          st, a);
       break;
     default:
       return hipErrorInvalidValue;
   }
+  return hipGetLastError();
+}
+
+template <int LPR, int VPL, int RIF>
+hipError_t launch_pool(const PassArgs &a, int nblk, hipStream_t st) {
+  hipLaunchKernelGGL((k_rows_pass<LPR, VPL, kPool, 4, RIF>), dim3(nblk), dim3(256), 0, st, a);
   return hipGetLastError();
 }
 
@@ -425,19 +531,28 @@ int32_t dense_pass_blocks(int32_t d, int32_t count, int mode) {
 hipError_t launch_dense_pass(const PassArgs &a, int mode, int32_t d, int32_t nblk,
                              hipStream_t st) {
   const Shape s = pick_shape(d);
-  const int nw = waves_per_block(s, mode);
-  if (s.lpr == 16) return launch_mode<16, 1, 16>(a, mode, nblk, nw, st);
-  if (s.lpr == 32) return launch_mode<32, 1, 16>(a, mode, nblk, nw, st);
+  if (mode == kPool) {
+    if (s.lpr == 16) return launch_pool<16, 1, 4>(a, nblk, st);
+    if (s.lpr == 32) return launch_pool<32, 1, 4>(a, nblk, st);
+    switch (s.vpl) {
+      case 1: return launch_pool<64, 1, 4>(a, nblk, st);
+      case 2: return launch_pool<64, 2, 4>(a, nblk, st);
+      case 4: return launch_pool<64, 4, 4>(a, nblk, st);
+      default: return launch_pool<64, 8, 2>(a, nblk, st);
+    }
+  }
+  if (s.lpr == 16) return launch_grad<16, 1, 8, 8>(a, mode, nblk, st);
+  if (s.lpr == 32) return launch_grad<32, 1, 8, 8>(a, mode, nblk, st);
   switch (s.vpl) {
-    case 1: return launch_mode<64, 1, 16>(a, mode, nblk, nw, st);
-    case 2: return launch_mode<64, 2, 16>(a, mode, nblk, nw, st);
-    case 4: return launch_mode<64, 4, 16>(a, mode, nblk, nw, st);
-    default: return launch_mode<64, 8, 8>(a, mode, nblk, nw, st);
+    case 1: return launch_grad<64, 1, 8, 8>(a, mode, nblk, st);
+    case 2: return launch_grad<64, 2, 8, 8>(a, mode, nblk, st);
+    case 4: return launch_grad<64, 4, AA_NW_D1024, AA_RIF_D1024>(a, mode, nblk, st);
+    default: return launch_grad<64, 8, 8, 2>(a, mode, nblk, st);
   }
 }
 
 hipError_t launch_dense_finalize(const FinalizeArgs &a, hipStream_t st) {
-  const int nred = a.d_pad / 64;
+  const int nred = a.d_pad / (4 * kFinCols4);
   const int extra = a.flags ? compact_tiles(a.P) : 0;
   hipLaunchKernelGGL(k_finalize, dim3(nred + extra), dim3(256), 0, st, a);
   return hipGetLastError();
