@@ -53,20 +53,25 @@ __device__ inline int count_flags_before(const uint8_t *flags, int j0, int *smem
 __device__ inline void tile_compact(const CompactArgs &c, int tile, int *smem) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int j0 = tile * kCompactTile;
-  const int prefix = c.tile_off ? c.tile_off[tile] : count_flags_before(c.flags, j0, smem);
   const int seg = j0 + wave * (kCompactTile / 4);
-  unsigned long long masks[8];
+  // the tile's own loads go out first, then the count of the flags before the tile
+  uint8_t fl[8];
   int ids[8];
   float ls[8];
-  int wave_total = 0;
 #pragma unroll
   for (int r = 0; r < 8; ++r) {
     const int j = seg + r * kWave + lane;
     const bool in = j < c.P;
-    const bool f = in && c.flags[j] != 0;
+    fl[r] = in ? c.flags[j] : (uint8_t)0;
     ids[r] = (in && c.kept_ids) ? (c.idx ? c.idx[j] : j) : 0;
     ls[r] = (in && c.loss) ? c.loss_pool[j] : 0.f;
-    masks[r] = __ballot(f);
+  }
+  const int prefix = c.tile_off ? c.tile_off[tile] : count_flags_before(c.flags, j0, smem);
+  unsigned long long masks[8];
+  int wave_total = 0;
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    masks[r] = __ballot(fl[r] != 0);
     wave_total += __popcll(masks[r]);
   }
   if (lane == 0) smem[wave] = wave_total;

@@ -20,6 +20,12 @@
 #define AA_RIF_D1024 2   // rows in flight per wave there
 #endif
 
+// Feature rows are read once per step: non-temporal loads keep them from displacing the
+// model vectors and block partials in L2.
+#ifndef AA_ROW_LOAD
+#define AA_ROW_LOAD(p) __builtin_nontemporal_load(p)
+#endif
+
 namespace aa {
 
 typedef float f4 __attribute__((ext_vector_type(4)));
@@ -74,14 +80,10 @@ __device__ __forceinline__ float row_group_sum(float v, int lane) {
   return (s0 + s1) + (s2 + s3);
 }
 
-// Combine the per-lane sums of the block's waves in a fixed order and store the
-// block's partial vector: fold the row groups inside a wave, halve the waves
-// through LDS until at most eight are left, then let one thread per 128-bit
-// column add those in wave order.  `red` holds SLOTS * ROW4 f4.
-template <int LPR, int VPL, int SLOTS>
-__device__ __forceinline__ void block_reduce_store(f4 (&acc)[VPL], f4 *red, float *out, int lane,
-                                                   int wave, int nw) {
-  constexpr int ROW4 = LPR * VPL;
+// Per-lane sums of one wave into its own LDS slot (row groups folded first).
+// Slot layout: red[(wave * NVEC + vec) * ROW4 + column].
+template <int LPR, int VPL>
+__device__ __forceinline__ void wave_slot_store(f4 (&acc)[VPL], f4 *slot, int lane) {
   if (LPR < kWave) {
 #pragma unroll
     for (int v = 0; v < VPL; ++v) {
@@ -91,36 +93,16 @@ __device__ __forceinline__ void block_reduce_store(f4 (&acc)[VPL], f4 *red, floa
       acc[v].w = fold_groups<LPR>(acc[v].w);
     }
   }
-  int live = nw;
-  while (live > SLOTS) {
-    const int s = live >> 1;
-    if (wave >= s && wave < live && lane < LPR) {
+  if (lane < LPR) {
 #pragma unroll
-      for (int v = 0; v < VPL; ++v) red[(wave - s) * ROW4 + v * LPR + lane] = acc[v];
-    }
-    __syncthreads();
-    if (wave < s && lane < LPR) {
-#pragma unroll
-      for (int v = 0; v < VPL; ++v) acc[v] += red[wave * ROW4 + v * LPR + lane];
-    }
-    __syncthreads();
-    live = s;
+    for (int v = 0; v < VPL; ++v) slot[v * LPR + lane] = acc[v];
   }
-  if (wave < live && lane < LPR) {
-#pragma unroll
-    for (int v = 0; v < VPL; ++v) red[wave * ROW4 + v * LPR + lane] = acc[v];
-  }
-  __syncthreads();
-  for (int c = threadIdx.x; c < ROW4; c += blockDim.x) {
-    f4 t = red[c];
-    for (int q = 1; q < live; ++q) t += red[q * ROW4 + c];
-    reinterpret_cast<f4 *>(out)[c] = t;
-  }
-  __syncthreads();
 }
 
 template <int LPR, int VPL, int MODE, int NW, int RIF>
-__global__ __launch_bounds__(NW * 64) void k_rows_pass(const PassArgs a) {
+__global__ __launch_bounds__(NW * 64)
+    __attribute__((amdgpu_waves_per_eu((MODE & 3) ? (VPL == 8 ? 2 : 4) : 1,
+                                       (MODE & 3) ? (VPL == 8 ? 2 : 4) : 8))) void k_rows_pass(const PassArgs a) {
   constexpr bool POOL = (MODE & kPool) != 0;
   constexpr bool SVM = (MODE & kSvm) != 0;
   constexpr bool ASSIST = (MODE & kAssist) != 0;
@@ -131,13 +113,12 @@ __global__ __launch_bounds__(NW * 64) void k_rows_pass(const PassArgs a) {
   constexpr int NVEC = (SVM ? 1 : 0) + (ASSIST ? 1 : 0);
   constexpr int NT = NW * 64;
   constexpr int STG = (ROW4 + NT - 1) / NT;  // staged 128-bit pieces per thread and vector
-  constexpr int SLOTS = VPL == 8 ? 4 : (NW < 8 ? NW : 8);  // LDS slots of the block reduction
 
   __shared__ int s_int[20];
   __shared__ float s_flt[20];
   __shared__ f4 s_w[SVM ? ROW4 : 1];
   __shared__ f4 s_phi[NEED_PHI ? ROW4 : 1];
-  __shared__ f4 s_red[GRAD ? SLOTS * ROW4 : 1];
+  __shared__ f4 s_red[GRAD ? NW * NVEC * ROW4 : 1];  // one slot per wave and vector
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int grp = lane / LPR, sub = lane % LPR;
@@ -171,16 +152,27 @@ __global__ __launch_bounds__(NW * 64) void k_rows_pass(const PassArgs a) {
   const float T = ASSIST ? *a.T : 0.f;
 
   f4 x[RIF][VPL];
-  auto issue_rows = [&](int it0) {  // every load of the next RIF rows, before any is used
+  // Every load of the next RIF rows, before any is used.  When the row fills the lane layout
+  // (d4 == ROW4) the loads are unconditional: a slot past the end of the group re-reads the
+  // group's last row (a cache hit) and is never consumed, so the loads carry no branches.
+  const bool full = a.d4 == ROW4;
+  auto issue_rows = [&](int it0) {
 #pragma unroll
     for (int r = 0; r < RIF; ++r) {
       const int li = (it0 + r) * G + grp;
-      const int row = __shfl(row_l, li & 63, kWave);
-      const f4 *xr = reinterpret_cast<const f4 *>(a.x + (int64_t)row * a.ld);
+      if (full) {
+        const int row = __shfl(row_l, min(li, cnt - 1), kWave);
+        const f4 *xr = reinterpret_cast<const f4 *>(a.x + (int64_t)row * a.ld);
 #pragma unroll
-      for (int v = 0; v < VPL; ++v) {
-        const int c = v * LPR + sub;
-        x[r][v] = (li < cnt && c < a.d4) ? __builtin_nontemporal_load(xr + c) : zero4;
+        for (int v = 0; v < VPL; ++v) x[r][v] = AA_ROW_LOAD(xr + v * LPR + sub);
+      } else {
+        const int row = __shfl(row_l, li & 63, kWave);
+        const f4 *xr = reinterpret_cast<const f4 *>(a.x + (int64_t)row * a.ld);
+#pragma unroll
+        for (int v = 0; v < VPL; ++v) {
+          const int c = v * LPR + sub;
+          x[r][v] = (li < cnt && c < a.d4) ? AA_ROW_LOAD(xr + c) : zero4;
+        }
       }
     }
   };
@@ -294,10 +286,12 @@ __global__ __launch_bounds__(NW * 64) void k_rows_pass(const PassArgs a) {
   }
 
   if (GRAD) {
-    float *part = a.partial + (size_t)blockIdx.x * NVEC * (ROW4 * 4);
-    if (SVM) block_reduce_store<LPR, VPL, SLOTS>(gw, s_red, part, lane, wave, NW);
-    if (ASSIST)
-      block_reduce_store<LPR, VPL, SLOTS>(gp, s_red, part + (SVM ? ROW4 * 4 : 0), lane, wave, NW);
+    // Block reduction behind a single barrier: every wave drops its sums into its own LDS
+    // slot as soon as its rows are done, then one thread per 128-bit column adds the
+    // slots in wave order and stores the block's partial vectors.
+    f4 *slot = s_red + wave * NVEC * ROW4;
+    if (SVM) wave_slot_store<LPR, VPL>(gw, slot, lane);
+    if (ASSIST) wave_slot_store<LPR, VPL>(gp, slot + (SVM ? ROW4 : 0), lane);
     const int kw = wave_sum_int(kept);
     const float gbw = group_sum<kWave>(gb);
     if (lane == 0) {
@@ -305,6 +299,13 @@ __global__ __launch_bounds__(NW * 64) void k_rows_pass(const PassArgs a) {
       s_flt[wave] = gbw;
     }
     __syncthreads();
+    f4 *part = reinterpret_cast<f4 *>(a.partial) + (size_t)blockIdx.x * NVEC * ROW4;
+    for (int c = threadIdx.x; c < NVEC * ROW4; c += NT) {
+      f4 t = s_red[c];
+#pragma unroll
+      for (int q = 1; q < NW; ++q) t += s_red[q * NVEC * ROW4 + c];
+      part[c] = t;
+    }
     if (threadIdx.x == 0) {
       int ks = 0;
       float gs = 0.f;
@@ -346,92 +347,94 @@ __global__ __launch_bounds__(256) void k_finalize(const FinalizeArgs a) {
     return;
   }
 
-  // kept count m
-  int m;
-  if (a.m_dev) {
-    m = min(max(*a.m_dev, 0), a.m_max);
+  // Every load is issued before any result is needed, so the block pays one memory round
+  // trip: per-block kept counts, the block partials, the current model slice.
+  int cnt_part = 0;
+  if (!a.m_dev)
+    for (int i = tid; i < a.nblk; i += blockDim.x) cnt_part += a.blk_cnt[i];
+  const int m_given = a.m_dev ? *a.m_dev : 0;
+  const int t_old = a.t_upd ? *a.t_snap : 0;
+  float gb_part = 0.f;
+  if (blockIdx.x == 0 && a.phi && a.bias)
+    for (int i = tid; i < a.nblk; i += blockDim.x) gb_part += a.blk_gb[i];
+
+  // kFinCols4 128-bit columns per block, kFinGroups groups of partials each summed in
+  // block order, then the groups in a fixed LDS tree
+  const int c4 = tid % kFinCols4, pg = tid / kFinCols4;
+  const int col4 = blockIdx.x * kFinCols4 + c4;
+  const int row4 = a.d_pad / 4;
+  const int k0 = col4 * 4;
+  const f4 zero = {0.f, 0.f, 0.f, 0.f};
+  float w_old[4] = {0.f, 0.f, 0.f, 0.f}, p_old[4] = {0.f, 0.f, 0.f, 0.f};
+  if (pg == 0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (k0 + i < a.d) {
+        if (a.w) w_old[i] = a.w[k0 + i];
+        if (a.phi) p_old[i] = a.phi[k0 + i];
+      }
+  }
+  f4 acc0 = zero, acc1 = zero;
+  const f4 *p = reinterpret_cast<const f4 *>(a.partial);
+  if (a.nvec == 2) {
+#pragma unroll 4
+    for (int blk = pg; blk < a.nblk; blk += kFinGroups) {
+      acc0 += p[(size_t)(blk * 2) * row4 + col4];
+      acc1 += p[(size_t)(blk * 2 + 1) * row4 + col4];
+    }
   } else {
-    int part = 0;
-    for (int i = tid; i < a.nblk; i += blockDim.x) part += a.blk_cnt[i];
-    part = wave_sum_int(part);
-    if ((tid & 63) == 0) s_int[tid >> 6] = part;
-    __syncthreads();
-    m = s_int[0] + s_int[1] + s_int[2] + s_int[3];
+#pragma unroll 4
+    for (int blk = pg; blk < a.nblk; blk += kFinGroups) acc0 += p[(size_t)blk * row4 + col4];
+  }
+  s_acc[0][pg][c4] = acc0;
+  s_acc[1][pg][c4] = acc1;
+  cnt_part = wave_sum_int(cnt_part);
+  gb_part = group_sum<kWave>(gb_part);
+  if ((tid & 63) == 0) {
+    s_int[tid >> 6] = cnt_part;
+    s_flt[tid >> 6] = gb_part;
+  }
+  __syncthreads();
+  for (int s = kFinGroups / 2; s >= 1; s >>= 1) {
+    if (pg < s) {
+      s_acc[0][pg][c4] += s_acc[0][pg + s][c4];
+      s_acc[1][pg][c4] += s_acc[1][pg + s][c4];
+    }
     __syncthreads();
   }
+  const int m = a.m_dev ? min(max(m_given, 0), a.m_max) : (s_int[0] + s_int[1]) + (s_int[2] + s_int[3]);
 
   // step size: constant, or lr / sqrt(number of updates made so far)
-  int t_new = 0;
+  int t_new = t_old + (m > 0 ? 1 : 0);
   float lr = a.lr;
-  if (a.t_upd) {
-    t_new = *a.t_snap + (m > 0 ? 1 : 0);
-    if (m > 0) lr = a.lr / sqrtf((float)t_new);
-  }
+  if (a.t_upd && m > 0) lr = a.lr / sqrtf((float)t_new);
 
   if (m > 0) {
-    // kFinCols4 128-bit columns per block, kFinGroups groups of partials each summed in
-    // block order, then the groups in a fixed LDS tree
-    const int c4 = tid % kFinCols4, pg = tid / kFinCols4;
-    const int col4 = blockIdx.x * kFinCols4 + c4;
-    const int row4 = a.d_pad / 4;
-    const f4 zero = {0.f, 0.f, 0.f, 0.f};
-    f4 acc0 = zero, acc1 = zero;
-    const f4 *p = reinterpret_cast<const f4 *>(a.partial);
-    if (a.nvec == 2) {
-#pragma unroll 4
-      for (int blk = pg; blk < a.nblk; blk += kFinGroups) {
-        acc0 += p[(size_t)(blk * 2) * row4 + col4];
-        acc1 += p[(size_t)(blk * 2 + 1) * row4 + col4];
-      }
-    } else {
-#pragma unroll 4
-      for (int blk = pg; blk < a.nblk; blk += kFinGroups) acc0 += p[(size_t)blk * row4 + col4];
-    }
-    s_acc[0][pg][c4] = acc0;
-    s_acc[1][pg][c4] = acc1;
-    __syncthreads();
-    for (int s = kFinGroups / 2; s >= 1; s >>= 1) {
-      if (pg < s) {
-        s_acc[0][pg][c4] += s_acc[0][pg + s][c4];
-        s_acc[1][pg][c4] += s_acc[1][pg + s][c4];
-      }
-      __syncthreads();
-    }
+    const float inv_m = 1.f / (float)m;
     if (pg == 0) {
       const f4 g0 = s_acc[0][0][c4], g1 = s_acc[1][0][c4];
-      const float inv_m = 1.f / (float)m;
       const f4 gw = g0;
       const f4 gp = a.w ? g1 : g0;
-      const int k0 = col4 * 4;
       if (a.w) {
         const float shrink = 1.f - lr * a.lambda;
         const float scale = lr * inv_m;
         const float gv[4] = {gw.x, gw.y, gw.z, gw.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-          if (k0 + i < a.d) a.w[k0 + i] = __fmaf_rn(scale, gv[i], shrink * a.w[k0 + i]);
+          if (k0 + i < a.d) a.w[k0 + i] = __fmaf_rn(scale, gv[i], shrink * w_old[i]);
       }
       if (a.phi) {
         const float gv[4] = {gp.x, gp.y, gp.z, gp.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-          if (k0 + i < a.d) {
-            const float ph = a.phi[k0 + i];
-            a.phi[k0 + i] = ph - a.lr_a * __fmaf_rn(a.l2_a, ph, gv[i] * inv_m);
-          }
+          if (k0 + i < a.d)
+            a.phi[k0 + i] = p_old[i] - a.lr_a * __fmaf_rn(a.l2_a, p_old[i], gv[i] * inv_m);
       }
     }
-    if (blockIdx.x == 0 && a.phi && a.bias) {
-      // bias gradient: fixed-order tree over the block partials
-      float part = 0.f;
-      for (int i = tid; i < a.nblk; i += blockDim.x) part += a.blk_gb[i];
-      part = group_sum<kWave>(part);
-      if ((tid & 63) == 0) s_flt[tid >> 6] = part;
-      __syncthreads();
-      if (tid == 0) {
-        const float gb = (s_flt[0] + s_flt[1]) + (s_flt[2] + s_flt[3]);
-        *a.bias = *a.bias - a.lr_a * (gb / (float)m);
-      }
+    if (blockIdx.x == 0 && tid == 0 && a.phi && a.bias) {
+      // bias gradient: per-wave sums of the block partials, added in wave order
+      const float gb = (s_flt[0] + s_flt[1]) + (s_flt[2] + s_flt[3]);
+      *a.bias = *a.bias - a.lr_a * (gb * inv_m);
     }
   }
   if (blockIdx.x == 0 && tid == 0 && a.kept_hist) *a.kept_hist = m;
@@ -521,7 +524,8 @@ int32_t dense_pass_blocks(int32_t d, int32_t count, int mode) {
   const int rows_per_block = nw * (kWave / s.lpr);
   const bool grad = (mode & (kSvm | kAssist)) != 0;
   int64_t want = ((int64_t)count + rows_per_block - 1) / rows_per_block;
-  const int64_t cap = grad ? num_cu() : (int64_t)num_cu() * 8;
+  // 16 waves per CU: one block of 16 waves, two of 8 or four of 4
+  const int64_t cap = grad ? (int64_t)num_cu() * (s.vpl == 8 ? 1 : 16 / nw) : (int64_t)num_cu() * 8;
   if (want > cap) want = cap;
   if (want > kMaxBlocks) want = kMaxBlocks;
   if (want < 1) want = 1;
