@@ -43,6 +43,8 @@ def parse():
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--threads", type=int, default=min(16, os.cpu_count() or 1))
+    ap.add_argument("--traffic-calibration", action="store_true",
+                    help="also run one plain 1 GiB row copy (for scaling rocprofv3 --pmc counters)")
     return ap.parse_args()
 
 
@@ -156,10 +158,11 @@ def cpu_baseline(job, budget_s):
     phi = np.zeros(a.d, np.float32)
     b = 0.0
     done, cands, t_upd = 0, 0, 0
+    limit = min(job.n_epochs * job.steps_per_epoch, a.warmup + a.steps)
     t0 = time.perf_counter()
-    while done < job.steps_per_epoch and time.perf_counter() - t0 < budget_s:
-        _, lo, P = job.pool_of(done)
-        idx = job.perms_h[0][lo:lo + P]
+    while done < limit and time.perf_counter() - t0 < budget_s:
+        e, lo, P = job.pool_of(done)
+        idx = job.perms_h[e][lo:lo + P]
         lr = np.float32(a.lr0 / math.sqrt(t_upd + 1))
         out = ref.step(F, job.yh, idx, P, w, phi, b, job.gamma, job.seed, done, job.lam, lr, 0.0,
                        job.lr_a)
@@ -169,8 +172,36 @@ def cpu_baseline(job, budget_s):
         cands += P
     el = time.perf_counter() - t0
     return {"value": cands / el, "unit": "candidates/s", "cores": 1, "kind": "oracle",
-            "sample": f"first {done} pools of epoch 0 ({cands} candidates, {el:.1f} s), "
+            "sample": f"first {done} pools of the same workload ({cands} candidates, {el:.1f} s), "
                       "single thread, fp64 accumulation"}
+
+
+def kernel_source_hash():
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_1905_03381_amd", "csrc")
+    for name in ("aa_dense.hip", "aa_dense.hpp", "aa_common.hpp", "aa_compact.hpp"):
+        h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def stored_traffic(pipeline):
+    """HBM bytes per launch of the fused row pass from the committed rocprofv3 --pmc summary;
+    None if there is none, or if the kernel sources changed since the counters were taken."""
+    path = os.path.join(ROOT, "profiles", "k_rows_pass_fused_dense_1Mx1024_traffic.txt")
+    if pipeline != "fused" or not os.path.exists(path):
+        return None
+    kv = {}
+    for line in open(path):
+        if ":" in line and not line.startswith("#"):
+            k, v = line.split(":", 1)
+            kv[k.strip()] = v.strip()
+    if kv.get("kernel_source_sha256_16") != kernel_source_hash():
+        return None
+    try:
+        return float(kv["hbm_bytes_per_launch"])
+    except (KeyError, ValueError):
+        return None
 
 
 def main():
@@ -242,8 +273,19 @@ def main():
         alg = sizes * (4 * a.d + 4 + 4 + 1)
         kname = "k_rows_pass<pool> (score, plus keep+compact in two_pass)"
     achieved = float(alg.sum() / durs.sum() / 1e9)
+    if a.traffic_calibration:
+        # plain copy of known size through the gather kernel: 262,144 rows of 4 KiB = 1 GiB
+        # read + 1 GiB written; rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE are scaled by what they
+        # read for this dispatch
+        rows = (1 << 30) // (4 * a.d)
+        dst = torch.empty((rows, a.d), device="cuda")
+        api.gather(job.X, 4 * a.d, None, None, torch.tensor([rows], dtype=torch.int32, device="cuda"),
+                   rows, dst, None)
+        torch.cuda.synchronize()
+        del dst
     roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": kname,
+                "frac": achieved / HBM_PEAK_GBS, "traffic": stored_traffic(saved_pipeline),
+                "kernel": kname,
                 "avg_launch_us": float(durs.mean() * 1e6),
                 "alg_bytes_per_launch": float(alg.mean()), "launches_timed": int(durs.size)}
 
