@@ -182,6 +182,31 @@ int32_t aa_boss_assistant_step(const aa_features *F, const float *y, const int32
                                float *bias, const aa_step_config *cfg, float *loss, void *ws,
                                size_t ws_bytes, void *stream);
 
+/* ---- Batch-generator helpers (neither is in the paper; both are this
+ * library's definitions, mirrored by the CPU reference used in the tests).
+ *
+ * Running-median shrinking threshold ("Boss loss above the running median" as
+ * the label of the image batch generator): med = median of loss[0..m-1]
+ * (m = min(*m_dev, m_max) <= 16384; mean of the two middle values for even m);
+ * the first call (*initialised == 0) sets *T = med and *initialised = 1, later
+ * calls *T = momentum * *T + (1 - momentum) * med, every operation rounded to
+ * fp32.  m == 0 changes nothing.  T and initialised are device scalars. */
+int32_t aa_threshold_update(const float *loss, const int32_t *m_dev, int32_t m_max, float momentum,
+                            float *T, int32_t *initialised, void *stream);
+
+/* Length-bucketed batching of m kept sentence pairs (translation batch
+ * generator): bucket(r) = min(n_buckets - 1, (max(len_s[r], len_t[r]) - 1) / width),
+ * n_buckets <= 32.  order[] lists r grouped by bucket, arrival order kept inside
+ * a bucket (stable); bucket_start[n_buckets + 1] are the group boundaries;
+ * batch_of[q] is the batch number of order[q], batches being consecutive runs of
+ * cap_b = max(1, token_budget / (2 * width * (b + 1))) pairs inside bucket b
+ * (padded-token budget), numbered bucket after bucket; *n_batches their count.
+ * len_s / len_t are indexed by r (gather them with aa_gather first). */
+int32_t aa_bucket_batches(const int32_t *len_s, const int32_t *len_t, const int32_t *m_dev,
+                          int32_t m_max, int32_t width, int32_t n_buckets, int32_t token_budget,
+                          int32_t *order, int32_t *bucket_start, int32_t *batch_of,
+                          int32_t *n_batches, void *ws, size_t ws_bytes, void *stream);
+
 /* ---- The whole step a1..a6 with every feature row read once: score, keep,
  * compact, gather ids, SVM step on the kept rows, Assistant update labelled
  * by the pre-update losses.  Outputs as in the staged calls: logit[P],

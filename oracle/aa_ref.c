@@ -360,6 +360,41 @@ done:
   return rc;
 }
 
+static int cmp_float(const void *a, const void *b) {
+  const float x = *(const float *)a, y = *(const float *)b;
+  return (x > y) - (x < y);
+}
+
+int32_t aa_ref_threshold_update(const float *loss, int32_t m, float momentum, float *T,
+                                int32_t *initialised) {
+  if (m < 0) return -2;
+  if (!T || !initialised) return -1;
+  if (m == 0) return 0;
+  if (!loss) return -1;
+  float *sorted = (float *)malloc((size_t)m * sizeof(float));
+  if (!sorted) return -2;
+  memcpy(sorted, loss, (size_t)m * sizeof(float));
+  qsort(sorted, (size_t)m, sizeof(float), cmp_float);
+  float med;
+  if (m % 2) {
+    med = sorted[m / 2];
+  } else {
+    const float sum = sorted[m / 2 - 1] + sorted[m / 2];
+    med = sum * 0.5f;
+  }
+  free(sorted);
+  if (!*initialised) {
+    *T = med;
+    *initialised = 1;
+  } else {
+    const float keep_part = momentum * *T;
+    const float one_minus = 1.0f - momentum;
+    const float new_part = one_minus * med;
+    *T = keep_part + new_part;
+  }
+  return 0;
+}
+
 int32_t aa_ref_bucket_batches(const int32_t *len_s, const int32_t *len_t, int32_t m,
                               int32_t width, int32_t n_buckets, int32_t token_budget,
                               int32_t *order, int32_t *bucket_start, int32_t *batch_of) {

@@ -13,9 +13,10 @@
  *
  * Parity status: every function below is pinned by tests against something
  * other than itself (published Philox known-answer vectors, closed forms,
- * library routines, brute force) except aa_ref_bucket_batches, whose
- * bucketing rule is not given by the paper: parity unpinned beyond brute force
- * of its own definition.
+ * library routines, brute force).  Two helpers are not in the paper and are
+ * this build's definitions: aa_ref_bucket_batches (parity unpinned beyond
+ * brute force of its own definition) and aa_ref_threshold_update (its median is
+ * pinned against numpy's; the momentum rule is parity unpinned).
  */
 #ifndef AA_REF_H
 #define AA_REF_H
@@ -126,6 +127,15 @@ int32_t aa_ref_step(const aa_ref_features *F, const float *y, const int32_t *idx
                     uint64_t step, float lambda, float lr, float T, float lr_a, float l2_a,
                     float *logit, float *prob, uint8_t *keep, int32_t *kept_pos,
                     int32_t *kept_ids, float *loss, int32_t *kept_count);
+
+/* Running-median shrinking threshold for the image batch generator ("loss above
+ * the running median"): med = median of loss[0..m-1] (mean of the two middle
+ * values for even m, in float); the first call sets *T = med, later calls
+ * *T = momentum * *T + (1 - momentum) * med, each product and the sum rounded
+ * to float.  m == 0 changes nothing.  This estimator is this build's reading
+ * (the paper gives no estimator); it is pinned against numpy's median. */
+int32_t aa_ref_threshold_update(const float *loss, int32_t m, float momentum, float *T,
+                                int32_t *initialised);
 
 /* Length-bucketed batching of kept sentence pairs (translation batch
  * generator).  bucket_r = min(n_buckets-1, (max(len_s,len_t)-1)/width);

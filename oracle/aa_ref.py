@@ -252,6 +252,16 @@ def step(F, y, idx, P, w, phi, bias, gamma, seed, step_no, lam, lr, T, lr_a, l2_
                 loss=loss[:k].copy(), m=k)
 
 
+def threshold_update(loss, momentum, T, initialised):
+    """Returns (T_new, initialised_new)."""
+    loss = _f32(loss)
+    t = np.array([T], dtype=np.float32)
+    init = C.c_int32(1 if initialised else 0)
+    _check(lib().aa_ref_threshold_update(_p(loss), C.c_int32(loss.shape[0]), C.c_float(momentum),
+                                         _p(t), C.byref(init)), "threshold_update")
+    return float(t[0]), bool(init.value)
+
+
 def bucket_batches(len_s, len_t, width, n_buckets, token_budget):
     len_s, len_t = _i32(len_s), _i32(len_t)
     m = len_s.shape[0]

@@ -21,7 +21,7 @@ SYMBOLS = [
     "aa_version", "aa_status_string", "aa_workspace_bytes", "aa_workspace_init", "aa_profile_hook",
     "aa_assistant_score", "aa_shrink", "aa_score_shrink", "aa_shrink_threshold", "aa_gather",
     "aa_gather_csr", "aa_svm_sgd_step", "aa_assistant_update", "aa_boss_assistant_step",
-    "aa_fused_step", "aa_train_epoch",
+    "aa_fused_step", "aa_train_epoch", "aa_threshold_update", "aa_bucket_batches",
 ]
 
 
@@ -72,6 +72,8 @@ def lib():
         "aa_boss_assistant_step": (i32, [FP, vp, vp, vp, i32, vp, vp, vp, CP, vp, vp, sz, vp]),
         "aa_fused_step": (i32, [FP, vp, vp, i32, vp, vp, vp, CP, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
         "aa_train_epoch": (i32, [FP, vp, vp, i64, i32, vp, vp, vp, CP, vp, vp, vp, sz, vp]),
+        "aa_threshold_update": (i32, [vp, vp, i32, f32, vp, vp, vp]),
+        "aa_bucket_batches": (i32, [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -220,3 +222,15 @@ def train_epoch(F, y, perm, n_perm, P, w, phi, bias, cfg, t_upd, kept_hist, ws):
     _check(lib().aa_train_epoch(F.ref(), _ptr(y), _ptr(perm), n_perm, P, _ptr(w), _ptr(phi),
                                 _ptr(bias), C.byref(cfg), _ptr(t_upd), _ptr(kept_hist), ws.ptr,
                                 ws.bytes, _stream()), "aa_train_epoch")
+
+
+def threshold_update(loss, m_dev, m_max, momentum, T, initialised):
+    _check(lib().aa_threshold_update(_ptr(loss), _ptr(m_dev), m_max, momentum, _ptr(T),
+                                     _ptr(initialised), _stream()), "aa_threshold_update")
+
+
+def bucket_batches(len_s, len_t, m_dev, m_max, width, n_buckets, token_budget, order, bucket_start,
+                   batch_of, n_batches, ws):
+    _check(lib().aa_bucket_batches(_ptr(len_s), _ptr(len_t), _ptr(m_dev), m_max, width, n_buckets,
+                                   token_budget, _ptr(order), _ptr(bucket_start), _ptr(batch_of),
+                                   _ptr(n_batches), ws.ptr, ws.bytes, _stream()), "aa_bucket_batches")

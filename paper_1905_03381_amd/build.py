@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libautoassist.so")
-SOURCES = ["aa_api.hip", "aa_dense.hip", "aa_general.hip", "aa_select.hip"]
+SOURCES = ["aa_api.hip", "aa_batching.hip", "aa_dense.hip", "aa_general.hip", "aa_select.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function"]

@@ -6,6 +6,7 @@
 #include "aa_common.hpp"
 #include "aa_dense.hpp"
 #include "aa_general.hpp"
+#include "aa_batching.hpp"
 #include "aa_select.hpp"
 
 using namespace aa;
@@ -23,6 +24,7 @@ struct Ws {
   uint8_t *flags;     // [P]
   float *loss_pool;   // [P]
   int32_t *tile_off;  // [P/2048 + 2]
+  int32_t *bucket_tiles;  // [(P/2048 + 2) * kMaxBuckets]
   float *prob;        // [P]   per-step outputs of the epoch driver
   int32_t *kept_pos;  // [P]
   int32_t *kept_ids;  // [P]
@@ -47,6 +49,8 @@ Ws carve(void *ws, size_t grad_bytes, int32_t P, bool epoch_outputs = false) {
   off += align_up(sizeof(float) * (size_t)(P > 0 ? P : 0), 256);
   w.tile_off = reinterpret_cast<int32_t *>(w.base + off);
   off += align_up(sizeof(int32_t) * ((size_t)(P > 0 ? P : 0) / kCompactTile + 2), 256);
+  w.bucket_tiles = reinterpret_cast<int32_t *>(w.base + off);
+  off += align_up(sizeof(int32_t) * ((size_t)(P > 0 ? P : 0) / kCompactTile + 2) * kMaxBuckets, 256);
   const size_t per = align_up(sizeof(float) * (size_t)(P > 0 ? P : 0), 256);
   w.prob = reinterpret_cast<float *>(w.base + off);
   w.kept_pos = reinterpret_cast<int32_t *>(w.base + off + per);
@@ -676,6 +680,42 @@ int32_t aa_fused_step(const aa_features *F, const float *y, const int32_t *idx, 
   return fused_step_impl(F, y, idx, P, w, phi, bias, cfg, cfg->step, logit, prob, keep, kept_pos,
                          kept_ids, loss, kept_count, nullptr, nullptr, false, ws, ws_bytes,
                          as_stream(stream));
+}
+
+int32_t aa_threshold_update(const float *loss, const int32_t *m_dev, int32_t m_max, float momentum,
+                            float *T, int32_t *initialised, void *stream) {
+  if (m_max < 0 || m_max > kMedianMax) return AA_ERR_SHAPE;
+  if (!(momentum >= 0.f && momentum <= 1.f)) return AA_ERR_SHAPE;
+  if (m_max == 0) return AA_OK;
+  if (!loss || !m_dev || !T || !initialised) return AA_ERR_NULL;
+  ThresholdArgs a{loss, m_dev, m_max, momentum, T, initialised};
+  return hip_status(launch_threshold_update(a, as_stream(stream)));
+}
+
+int32_t aa_bucket_batches(const int32_t *len_s, const int32_t *len_t, const int32_t *m_dev,
+                          int32_t m_max, int32_t width, int32_t n_buckets, int32_t token_budget,
+                          int32_t *order, int32_t *bucket_start, int32_t *batch_of,
+                          int32_t *n_batches, void *ws_ptr, size_t ws_bytes, void *stream) {
+  if (m_max < 0 || width <= 0 || n_buckets <= 0 || n_buckets > kMaxBuckets || token_budget <= 0)
+    return AA_ERR_SHAPE;
+  if (!m_dev || !bucket_start || !n_batches) return AA_ERR_NULL;
+  if (m_max > 0 && (!len_s || !len_t || !order || !batch_of)) return AA_ERR_NULL;
+  Ws ws = carve(ws_ptr, 0, m_max);
+  if (int32_t rc = check_ws(ws_ptr, ws_bytes, ws.total)) return rc;
+  BucketArgs a{};
+  a.len_s = len_s;
+  a.len_t = len_t;
+  a.m_dev = m_dev;
+  a.m_max = m_max;
+  a.width = width;
+  a.n_buckets = n_buckets;
+  a.token_budget = token_budget;
+  a.order = order;
+  a.bucket_start = bucket_start;
+  a.batch_of = batch_of;
+  a.n_batches = n_batches;
+  a.tile_base = ws.bucket_tiles;
+  return hip_status(launch_bucket_batches(a, as_stream(stream)));
 }
 
 int32_t aa_train_epoch(const aa_features *F, const float *y, const int32_t *perm, int64_t n_perm,

@@ -1,0 +1,190 @@
+// Batch-generator helpers around the shrink path.
+//
+// Running-median threshold: one block sorts the batch's losses in LDS (bitonic
+// network, padded with +inf) and folds the median into the threshold.
+//
+// Length-bucketed batching: a stable multi-way partition of the kept pairs by
+// length bucket, three launches: per-tile bucket histograms (LDS integer
+// atomics), one block that turns them into per-tile, per-bucket offsets, bucket
+// starts and batch numbers, and a scatter in which a wave ranks each pair among
+// the earlier pairs of its bucket with one ballot per bucket and mbcnt.
+#include "aa_batching.hpp"
+
+namespace aa {
+
+namespace {
+
+__global__ __launch_bounds__(1024) void k_threshold_update(const ThresholdArgs a) {
+  __shared__ float s[kMedianMax];
+  const int m = min(max(*a.m_dev, 0), a.m_max);
+  if (m == 0) return;
+  int n = 1;
+  while (n < m) n <<= 1;
+  for (int i = threadIdx.x; i < n; i += blockDim.x) s[i] = i < m ? a.loss[i] : __builtin_inff();
+  __syncthreads();
+  for (int k = 2; k <= n; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int i = threadIdx.x; i < n; i += blockDim.x) {
+        const int p = i ^ j;
+        if (p > i) {
+          const float x = s[i], y = s[p];
+          const bool up = (i & k) == 0;
+          if (up ? (x > y) : (x < y)) {
+            s[i] = y;
+            s[p] = x;
+          }
+        }
+      }
+      __syncthreads();
+    }
+  }
+  if (threadIdx.x == 0) {
+    // every product and sum below is rounded to fp32 on its own: no fused multiply-add
+#pragma clang fp contract(off)
+    float med;
+    if (m & 1) {
+      med = s[m / 2];
+    } else {
+      const float sum = s[m / 2 - 1] + s[m / 2];
+      med = sum * 0.5f;
+    }
+    if (*a.initialised == 0) {
+      *a.T = med;
+      *a.initialised = 1;
+    } else {
+      const float keep_part = a.momentum * *a.T;
+      const float one_minus = 1.0f - a.momentum;
+      const float new_part = one_minus * med;
+      *a.T = keep_part + new_part;
+    }
+  }
+}
+
+__device__ __forceinline__ int bucket_of(int ls, int lt, int width, int nb) {
+  const int L = max(ls, lt);
+  int b = (L - 1) / width;
+  b = max(b, 0);
+  return min(b, nb - 1);
+}
+
+constexpr int kBucketTile = 2048;
+
+__global__ __launch_bounds__(256) void k_bucket_counts(const BucketArgs a) {
+  __shared__ int hist[kMaxBuckets];
+  const int m = min(max(*a.m_dev, 0), a.m_max);
+  if (threadIdx.x < kMaxBuckets) hist[threadIdx.x] = 0;
+  __syncthreads();
+  const int r0 = blockIdx.x * kBucketTile;
+  for (int r = r0 + threadIdx.x; r < min(m, r0 + kBucketTile); r += 256)
+    atomicAdd(&hist[bucket_of(a.len_s[r], a.len_t[r], a.width, a.n_buckets)], 1);
+  __syncthreads();
+  if (threadIdx.x < a.n_buckets) a.tile_base[blockIdx.x * a.n_buckets + threadIdx.x] = hist[threadIdx.x];
+}
+
+__global__ __launch_bounds__(64) void k_bucket_scan(const BucketArgs a, int ntiles_max) {
+  __shared__ int total[kMaxBuckets], start[kMaxBuckets + 1], batch_base[kMaxBuckets + 1];
+  const int m = min(max(*a.m_dev, 0), a.m_max);
+  const int ntiles = (m + kBucketTile - 1) / kBucketTile;
+  const int b = threadIdx.x;
+  const int nb = a.n_buckets;
+  if (b < nb) {
+    int run = 0;
+    for (int t = 0; t < ntiles; ++t) {
+      const int c = a.tile_base[t * nb + b];
+      a.tile_base[t * nb + b] = run;
+      run += c;
+    }
+    total[b] = run;
+  }
+  __syncthreads();
+  if (b == 0) {
+    int s = 0, batches = 0;
+    for (int q = 0; q < nb; ++q) {
+      start[q] = s;
+      batch_base[q] = batches;
+      const int cap = max(1, a.token_budget / (2 * a.width * (q + 1)));
+      batches += (total[q] + cap - 1) / cap;
+      s += total[q];
+    }
+    start[nb] = s;
+    batch_base[nb] = batches;
+    *a.n_batches = batches;
+  }
+  __syncthreads();
+  if (b <= nb) a.bucket_start[b] = start[b];
+  int *tail = a.tile_base + (size_t)ntiles_max * nb;  // [nb] starts, [nb] batch bases
+  if (b < nb) {
+    tail[b] = start[b];
+    tail[nb + b] = batch_base[b];
+    for (int t = 0; t < ntiles; ++t) a.tile_base[t * nb + b] += start[b];
+  }
+}
+
+__global__ __launch_bounds__(256) void k_bucket_scatter(const BucketArgs a, int ntiles_max) {
+  __shared__ int wave_tot[4][kMaxBuckets];
+  __shared__ int wave_run[4][kMaxBuckets];
+  const int m = min(max(*a.m_dev, 0), a.m_max);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nb = a.n_buckets;
+  const int seg = blockIdx.x * kBucketTile + wave * (kBucketTile / 4);
+  int bk[8];
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    const int row = seg + r * kWave + lane;
+    bk[r] = row < m ? bucket_of(a.len_s[row], a.len_t[row], a.width, nb) : -1;
+  }
+  // totals of this wave per bucket
+  for (int b = 0; b < nb; ++b) {
+    int tot = 0;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) tot += __popcll(__ballot(bk[r] == b));
+    if (lane == 0) wave_tot[wave][b] = tot;
+  }
+  __syncthreads();
+  if (lane < nb) {
+    int base = a.tile_base[blockIdx.x * nb + lane];
+    for (int w = 0; w < wave; ++w) base += wave_tot[w][lane];
+    wave_run[wave][lane] = base;
+  }
+  __builtin_amdgcn_wave_barrier();
+  const int *tail = a.tile_base + (size_t)ntiles_max * nb;
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    for (int b = 0; b < nb; ++b) {
+      const unsigned long long mask = __ballot(bk[r] == b);
+      if (mask == 0) continue;
+      const int base = wave_run[wave][b];
+      if (bk[r] == b) {
+        const int pos = base + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                                         __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+        const int cap = max(1, a.token_budget / (2 * a.width * (b + 1)));
+        a.order[pos] = seg + r * kWave + lane;
+        a.batch_of[pos] = tail[nb + b] + (pos - tail[b]) / cap;
+      }
+      __builtin_amdgcn_wave_barrier();
+      if (lane == 0) wave_run[wave][b] = base + __popcll(mask);
+      __builtin_amdgcn_wave_barrier();
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_threshold_update(const ThresholdArgs &a, hipStream_t st) {
+  hipLaunchKernelGGL(k_threshold_update, dim3(1), dim3(1024), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_bucket_batches(const BucketArgs &a, hipStream_t st) {
+  const int ntiles = (a.m_max + kBucketTile - 1) / kBucketTile;
+  if (ntiles > 0) {
+    hipLaunchKernelGGL(k_bucket_counts, dim3(ntiles), dim3(256), 0, st, a);
+    if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+  }
+  hipLaunchKernelGGL(k_bucket_scan, dim3(1), dim3(64), 0, st, a, ntiles);
+  if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+  if (ntiles > 0) hipLaunchKernelGGL(k_bucket_scatter, dim3(ntiles), dim3(256), 0, st, a, ntiles);
+  return hipGetLastError();
+}
+
+}  // namespace aa

@@ -66,7 +66,8 @@ __global__ __launch_bounds__(256) void k_rows_general(const GenArgs a) {
       const bool live = li < cnt;
       const int j = base + li;
       const long long e0 = __shfl(e0_l, li, kWave);
-      const int len = live ? __shfl(len_l, li, kWave) : 0;
+      const int len_any = __shfl(len_l, li, kWave);  // every lane takes part in the shuffle
+      const int len = live ? len_any : 0;
       const float u = __shfl(u_l, li, kWave);
       const float yy = __shfl(y_l, li, kWave);
       const float lin = __shfl(lin_l, li, kWave);

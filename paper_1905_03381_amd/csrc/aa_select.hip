@@ -105,6 +105,22 @@ __global__ __launch_bounds__(256) void k_gather_rows(const GatherArgs a, int cpr
   }
 }
 
+// Short rows (labels, lengths, a few words): one thread per 32-bit word.
+__global__ __launch_bounds__(256) void k_gather_words(const GatherArgs a, int words_per_row) {
+  const int m = min(max(*a.kept_count, 0), a.max_rows);
+  const long long total = (long long)m * words_per_row;
+  const uint32_t *src = reinterpret_cast<const uint32_t *>(a.src);
+  uint32_t *dst = reinterpret_cast<uint32_t *>(a.dst);
+  for (long long t = (long long)blockIdx.x * 256 + threadIdx.x; t < total;
+       t += (long long)gridDim.x * 256) {
+    const int r = (int)(t / words_per_row), k = (int)(t % words_per_row);
+    const int pos = a.kept_pos ? a.kept_pos[r] : r;
+    const long long id = a.idx ? a.idx[pos] : pos;
+    if (k == 0 && a.kept_ids) a.kept_ids[r] = (int32_t)id;
+    dst[t] = src[id * words_per_row + k];
+  }
+}
+
 __global__ __launch_bounds__(256) void k_gather_ids(const GatherArgs a) {
   const int m = min(max(*a.kept_count, 0), a.max_rows);
   for (int r = blockIdx.x * 256 + threadIdx.x; r < m; r += gridDim.x * 256) {
@@ -194,6 +210,13 @@ hipError_t launch_gather(const GatherArgs &a, hipStream_t st) {
   }
   const uintptr_t bits = reinterpret_cast<uintptr_t>(a.src) | reinterpret_cast<uintptr_t>(a.dst) |
                          (uintptr_t)a.row_bytes;
+  if ((bits & 3) == 0 && a.row_bytes <= 256) {
+    const int words = (int)(a.row_bytes / 4);
+    long long nb = ((long long)a.max_rows * words + 255) / 256;
+    if (nb > 256 * 16) nb = 256 * 16;
+    hipLaunchKernelGGL(k_gather_words, dim3((unsigned)nb), dim3(256), 0, st, a, words);
+    return hipGetLastError();
+  }
   const int vec = (bits & 15) == 0 ? 16 : ((bits & 3) == 0 ? 4 : 1);
   const int unroll = (vec == 16 && a.row_bytes > 8192) ? 4 : 1;
   const long long chunk = vec == 16 ? 4096ll * unroll : 4096ll;

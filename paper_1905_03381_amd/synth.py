@@ -180,6 +180,27 @@ def image_bytes(image_ids, offsets, seed=1905):
     return (h & np.uint64(0xFF)).astype(np.uint8)
 
 
+def image_store_device(n_images, row_bytes, seed=1905, device="cuda", chunk=512):
+    """The whole image store [n_images, row_bytes] uint8 built on the device with the same
+    counter hash as image_bytes() (torch integer ops; 64-bit wrap-around arithmetic)."""
+    import torch
+
+    def s64(v):  # unsigned 64-bit constant as the signed value with the same bits
+        return v - (1 << 64) if v >= (1 << 63) else v
+
+    out = torch.empty((n_images, row_bytes), dtype=torch.uint8, device=device)
+    off = torch.arange(row_bytes, dtype=torch.int64, device=device) * s64(0xC2B2AE3D27D4EB4F) + seed
+    for lo in range(0, n_images, chunk):
+        hi = min(n_images, lo + chunk)
+        ids = torch.arange(lo, hi, dtype=torch.int64, device=device) * s64(0x9E3779B97F4A7C15)
+        h = ids[:, None] + off[None, :]
+        h ^= (h >> 29) & ((1 << 35) - 1)          # logical shift right by 29
+        h *= s64(0xBF58476D1CE4E5B9)
+        h ^= (h >> 32) & ((1 << 32) - 1)          # logical shift right by 32
+        out[lo:hi] = (h & 0xFF).to(torch.uint8)
+    return out
+
+
 def gamma_losses(count, shape=2.0, scale=0.5, seed=1905, batch=0):
     """Stand-in Boss per-instance losses for one batch."""
     return _rng(seed, 4, batch).gamma(shape, scale, count).astype(np.float32)

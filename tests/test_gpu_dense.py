@@ -19,7 +19,7 @@ def rng(seed):
 
 @pytest.fixture(scope="module")
 def ws():
-    return api.Workspace(1 << 17, 4100)
+    return api.Workspace(300_000, 4100)
 
 
 def make_dense(n, d, seed, ld=None, unit=False):
@@ -129,7 +129,10 @@ def test_shrink_threshold(ref, ws):
     assert np.array_equal(host(keep), keep_ref) and np.array_equal(host(pos)[:pos_ref.size], pos_ref)
 
 
-@pytest.mark.parametrize("n,d,ld,P", SCORE_SHAPES + [(70_000, 128, None, 70_000)])
+# the last two pools give a wave more than 64 rows (several groups of 64 per wave)
+@pytest.mark.parametrize("n,d,ld,P", SCORE_SHAPES + [(70_000, 128, None, 70_000),
+                                                     (300_000, 128, None, 300_000),
+                                                     (280_000, 130, None, 280_000)])
 def test_score_shrink_fused(ref, ws, n, d, ld, P):
     X, _ = make_dense(n, d, 11, ld)
     r = rng(12)
@@ -299,7 +302,7 @@ def _check_state(ref_out, w, phi, b, Fh, ids_kept, y, w0, phi0, b0, lr, lam, lr_
     assert abs(float(host(b)[0]) - ref_out["bias"]) <= RTOL * (abs(b0) + lr_a)
 
 
-@pytest.mark.parametrize("n,d,ld,P", SCORE_SHAPES)
+@pytest.mark.parametrize("n,d,ld,P", SCORE_SHAPES + [(300_000, 128, None, 300_000)])
 def test_fused_step_matches_oracle_step(ref, ws, n, d, ld, P):
     X, y = make_dense(n, d, 61, ld, unit=True)
     r = rng(62)

@@ -540,3 +540,25 @@ def test_bucket_batches_brute_force(ref):
         members = order[batch_of == q]
         width = 8 * (bucket[members[0]] + 1)
         assert members.size * 2 * width <= 4096 or members.size == 1
+
+
+# ---------------------------------------------------------------------------
+# Running-median threshold (estimator is this build's; the median itself is numpy's)
+
+
+def test_threshold_update_is_numpy_median_with_momentum(ref):
+    r = rng(22)
+    T, init = 0.0, False
+    want = None
+    for m in [255, 256, 1, 2, 1000]:
+        loss = r.gamma(2.0, 0.5, m).astype(np.float32)
+        T, init = ref.threshold_update(loss, 0.9, T, init)
+        med = np.float32(np.median(loss.astype(np.float64)))      # exact: mean of two floats
+        if want is None:
+            want = med
+        else:
+            want = np.float32(np.float32(np.float32(0.9) * want)
+                              + np.float32(np.float32(np.float32(1.0) - np.float32(0.9)) * med))
+        assert init and np.float32(T) == want
+    T2, init2 = ref.threshold_update(np.zeros(0, np.float32), 0.9, 1.25, True)
+    assert T2 == 1.25 and init2
