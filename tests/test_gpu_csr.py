@@ -203,3 +203,56 @@ def test_gather_csr(ref, ws, sparse):
     fits = int(np.searchsorted(want_ptr, small, side="right") - 1)
     assert np.array_equal(host(out_col2)[:want_ptr[fits]], want_col[:want_ptr[fits]])
     assert np.all(host(out_col2)[want_ptr[fits]:] == -1)
+
+
+def test_sparse_config_full_size_first_pools(ref):
+    """The sparse linear-SVM configuration at full size (n = 2,000,000, d = 2^20, about 100
+    entries per row, pools of 65,536): two chained whole steps against the oracle."""
+    n, d, P = 2_000_000, 1 << 20, 65536
+    rowptr, col, val, y, _ = synth.sparse_svm(n=n, d=d, threads=16)
+    Fh = ref.Features.csr(rowptr, col, val, d)
+    F = csr_features(rowptr, col, val, d)
+    ws = api.Workspace(P, d)
+    perm = synth.epoch_permutation(n, seed=7, epoch=0)
+    gamma, seed, lam, lr_a, T = 0.1, 42, 1e-4, 0.1, 0.0
+    w_r, phi_r, b_r = np.zeros(d, np.float32), np.zeros(d, np.float32), 0.0
+    w, phi, b = dev(w_r), dev(phi_r), scalar_dev(0.0)
+    yd, Tt = dev(y), scalar_dev(T)
+    for t in range(2):
+        idx = perm[t * P:(t + 1) * P]
+        lr = float(np.float32(1.0 / np.sqrt(t + 1)))
+        w_prev, phi_prev = w_r, phi_r
+        # the scores do not depend on the Philox key: take the first key under which no draw of
+        # this pool falls into the rounding band of its keep probability
+        for seed in range(42, 74):
+            out = ref.step(Fh, y, idx, P, w_r, phi_r, b_r, gamma, seed, t, lam, lr, T, lr_a)
+            if clear_draws(ref, out["prob"], gamma, seed, t).all():
+                break
+        else:
+            pytest.fail("no Philox key with every draw clear of the rounding band")
+        w_r, phi_r, b_r = out["w"], out["phi"], out["bias"]
+        m = out["m"]
+        cfg = api.step_config(gamma, lam, lr, lr_a, 0.0, seed, t, Tt)
+        prob = torch.zeros(P, device="cuda")
+        keep = torch.zeros(P, dtype=torch.uint8, device="cuda")
+        pos = torch.zeros(P, dtype=torch.int32, device="cuda")
+        ids = torch.zeros(P, dtype=torch.int32, device="cuda")
+        loss = torch.zeros(P, device="cuda")
+        cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+        api.fused_step(F, yd, dev(idx), P, w, phi, b, cfg, None, prob, keep, pos, ids, loss, cnt, ws)
+        assert int(host(cnt)[0]) == m
+        assert np.array_equal(host(keep), out["keep"])
+        assert np.array_equal(host(ids)[:m], out["kept_ids"])
+        kept = out["kept_ids"]
+        S = abs_dot_scale(Fh, kept, w_prev) + 1e-3
+        assert_close_scaled(host(loss)[:m], out["loss"], S, f"loss step {t}")
+        dots = _dots(Fh, kept, w_prev) * y[kept]
+        on_kink = np.abs(dots - 1) <= RTOL * S
+        absx_a = _col_abs_sum(Fh, kept[dots < 1], d)
+        assert_close_scaled(host(w), w_r, np.abs(w_prev.astype(np.float64)) + lr / m * absx_a,
+                            f"w step {t}", atol=lr / m * _col_abs_sum(Fh, kept[on_kink], d))
+        absx = _col_abs_sum(Fh, kept, d)
+        assert_close_scaled(host(phi), phi_r, np.abs(phi_prev.astype(np.float64)) + lr_a / m * absx,
+                            f"phi step {t}")
+        # the GPU state goes on from the oracle's bits so that step 2 is compared on equal inputs
+        w, phi, b = dev(w_r), dev(phi_r), scalar_dev(b_r)
