@@ -213,7 +213,7 @@ hipError_t run_pass(const PassSpec &s, const Ws &ws, int32_t *nblk_out, hipStrea
   a.acc_gb = acc + 1;
   a.acc_w = acc + 16;
   a.acc_p = acc + 16 + s.F->d;
-  const int32_t nblk = general_pass_blocks(s.count_max, csr);
+  const int32_t nblk = general_pass_blocks(s.count_max, csr, s.mode);
   *nblk_out = nblk;
   HookScope hook(st);
   return launch_general_pass(a, s.mode, csr, nblk, st);
