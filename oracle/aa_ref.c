@@ -360,6 +360,101 @@ done:
   return rc;
 }
 
+int32_t aa_ref_sk_step(const aa_ref_features *F, const float *y, const int32_t *idx, int32_t P,
+                       float *w, float lambda, float lr, float T, float *loss_pool,
+                       uint8_t *keep, int32_t *kept_pos, int32_t *kept_ids, float *loss,
+                       int32_t *kept_count) {
+  if (P < 0) return -2;
+  if (!kept_count) return -1;
+  *kept_count = 0;
+  if (P == 0) return 0;
+  if (!features_ok(F)) return F ? -2 : -1;
+  if (!y || !w) return -1;
+  float *crit = loss_pool ? loss_pool : (float *)malloc((size_t)P * sizeof(float));
+  int32_t *pos_l = kept_pos ? kept_pos : (int32_t *)malloc((size_t)P * sizeof(int32_t));
+  int32_t *ids_l = kept_ids ? kept_ids : (int32_t *)malloc((size_t)P * sizeof(int32_t));
+  int32_t rc = -2, m = 0;
+  if (!crit || !pos_l || !ids_l) goto done;
+  /* the criterion: every candidate's objective value at the current w */
+  for (int32_t j = 0; j < P; ++j) {
+    int64_t row = idx ? (int64_t)idx[j] : (int64_t)j;
+    if (row < 0 || row >= F->n) goto done;
+    float margin = (float)((double)y[row] * row_dot(F, row, w));
+    crit[j] = (float)fmax(0.0, 1.0 - (double)margin);
+  }
+  rc = aa_ref_shrink_threshold(crit, P, T, keep, pos_l, &m);
+  if (rc) goto done;
+  rc = aa_ref_gather(NULL, 0, idx, pos_l, m, NULL, ids_l);
+  if (rc) goto done;
+  rc = aa_ref_svm_sgd_step(F, y, ids_l, m, w, lambda, lr, 0.0f, loss);
+  *kept_count = m;
+done:
+  if (!loss_pool) free(crit);
+  if (!kept_pos) free(pos_l);
+  if (!kept_ids) free(ids_l);
+  return rc;
+}
+
+int32_t aa_ref_sk_sgd(const aa_ref_features *F, const float *y, double *w, double mu, double G,
+                      double D, uint64_t seed, int32_t K, const double *w_star, double *dist2,
+                      int32_t *picked, int32_t *dropped) {
+  if (K < 0) return -2;
+  if (!features_ok(F) || F->n <= 0 || F->n > 0x7fffffff) return F ? -2 : -1;
+  if (!y || !w) return -1;
+  if (!(mu > 0.0)) return -2;
+  const int32_t d = F->d;
+  double *g = (double *)malloc((size_t)d * sizeof(double));
+  if (!g) return -2;
+  int32_t n_dropped = 0;
+  for (int32_t k = 1; k <= K; ++k) {
+    if (w_star && dist2) {
+      double s = 0.0;
+      for (int32_t c = 0; c < d; ++c) s += (w[c] - w_star[c]) * (w[c] - w_star[c]);
+      dist2[k - 1] = s;
+    }
+    /* i ~ uniform{0..N-1}: second Philox word of counter (k, 0, 0, 0), scaled by N */
+    uint32_t ctr[4] = {(uint32_t)k, 0u, 0u, 0u}, out[4];
+    uint32_t key[2] = {(uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32)};
+    aa_ref_philox4x32_10(ctr, key, out);
+    int64_t i = (int64_t)(((uint64_t)out[1] * (uint64_t)F->n) >> 32);
+    if (picked) picked[k - 1] = (int32_t)i;
+    /* grad f_i(w) with f_i(w) = (mu/2)|w|^2 + max(0, 1 - y_i w.x_i) */
+    double wx = 0.0;
+    if (F->layout == AA_REF_DENSE) {
+      for (int32_t c = 0; c < d; ++c) wx += w[c] * (double)F->x[i * F->ld + c];
+    } else {
+      for (int64_t e = F->rowptr[i]; e < F->rowptr[i + 1]; ++e)
+        wx += w[F->col[e]] * (F->val ? (double)F->val[e] : 1.0);
+    }
+    for (int32_t c = 0; c < d; ++c) g[c] = mu * w[c];
+    if ((double)y[i] * wx < 1.0) row_axpy(F, i, -(double)y[i], g);
+    double nrm2 = 0.0;
+    for (int32_t c = 0; c < d; ++c) nrm2 += g[c] * g[c];
+    if (sqrt(nrm2) <= G / (double)k) { /* epsilon_k = grad f_i: the step is dropped */
+      ++n_dropped;
+      continue;
+    }
+    const double eta = 1.0 / (mu * (double)k);
+    for (int32_t c = 0; c < d; ++c) w[c] -= eta * g[c];
+    if (D > 0.0) {
+      double wn2 = 0.0;
+      for (int32_t c = 0; c < d; ++c) wn2 += w[c] * w[c];
+      if (sqrt(wn2) > D) {
+        const double f = D / sqrt(wn2);
+        for (int32_t c = 0; c < d; ++c) w[c] *= f;
+      }
+    }
+  }
+  if (w_star && dist2) {
+    double s = 0.0;
+    for (int32_t c = 0; c < d; ++c) s += (w[c] - w_star[c]) * (w[c] - w_star[c]);
+    dist2[K] = s;
+  }
+  if (dropped) *dropped = n_dropped;
+  free(g);
+  return 0;
+}
+
 static int cmp_float(const void *a, const void *b) {
   const float x = *(const float *)a, y = *(const float *)b;
   return (x > y) - (x < y);

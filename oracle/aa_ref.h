@@ -128,6 +128,29 @@ int32_t aa_ref_step(const aa_ref_features *F, const float *y, const int32_t *idx
                     float *logit, float *prob, uint8_t *keep, int32_t *kept_pos,
                     int32_t *kept_ids, float *loss, int32_t *kept_count);
 
+/* One step of hard-threshold shrinking (SK of Section 3.4; the update of eq.
+ * "shrinking_grad" with the objective value as the criterion) on pool
+ * idx[0..P-1]: crit_j = hinge loss of candidate j at the current w,
+ * keep_j = (crit_j > T), stable compaction, then the SVM step on the kept rows.
+ * Outputs (any may be NULL except kept_count): loss_pool[P] = crit, keep[P],
+ * kept_pos[P], kept_ids[P], loss[P] (kept rows, pre-update). */
+int32_t aa_ref_sk_step(const aa_ref_features *F, const float *y, const int32_t *idx, int32_t P,
+                       float *w, float lambda, float lr, float T, float *loss_pool,
+                       uint8_t *keep, int32_t *kept_pos, int32_t *kept_ids, float *loss,
+                       int32_t *kept_count);
+
+/* The iteration Theorem 1 (Section 4) is stated for, in double: K single-instance
+ * steps on f_i(w) = (mu/2)|w|^2 + max(0, 1 - y_i w.x_i), step size 1/(mu k),
+ * i_k uniform on the rows; step k is dropped when |grad f_i(w_k)| <= G/k.
+ * D > 0 projects onto the ball of radius D after every step (the boundedness
+ * assumption of the theorem, as in Pegasos); D = 0: no projection.
+ * i_k = (word 1 of Philox(counter (k,0,0,0), key seed) * N) >> 32, k = 1..K.
+ * Optional outputs: dist2[K+1] (|w_k - w_star|^2 for k = 1..K+1, needs
+ * w_star), picked[K] (the i_k), *dropped (number of dropped steps). */
+int32_t aa_ref_sk_sgd(const aa_ref_features *F, const float *y, double *w, double mu, double G,
+                      double D, uint64_t seed, int32_t K, const double *w_star, double *dist2,
+                      int32_t *picked, int32_t *dropped);
+
 /* Running-median shrinking threshold for the image batch generator ("loss above
  * the running median"): med = median of loss[0..m-1] (mean of the two middle
  * values for even m, in float); the first call sets *T = med, later calls

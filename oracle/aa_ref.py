@@ -252,6 +252,75 @@ def step(F, y, idx, P, w, phi, bias, gamma, seed, step_no, lam, lr, T, lr_a, l2_
                 loss=loss[:k].copy(), m=k)
 
 
+def sk_step(F, y, idx, P, w, lam, lr, T):
+    """One hard-threshold shrinking step (SK).  Returns a dict like step()."""
+    y, idx = _f32(y), _i32(idx)
+    w = np.array(w, dtype=np.float32, copy=True)
+    loss_pool = np.zeros(max(P, 1), dtype=np.float32)
+    keep = np.zeros(max(P, 1), dtype=np.uint8)
+    kept_pos = np.zeros(max(P, 1), dtype=np.int32)
+    kept_ids = np.zeros(max(P, 1), dtype=np.int32)
+    loss = np.zeros(max(P, 1), dtype=np.float32)
+    m = C.c_int32(0)
+    _check(lib().aa_ref_sk_step(F.ref(), _p(y), _p(idx), C.c_int32(P), _p(w), C.c_float(lam),
+                                C.c_float(lr), C.c_float(T), _p(loss_pool), _p(keep),
+                                _p(kept_pos), _p(kept_ids), _p(loss), C.byref(m)), "sk_step")
+    k = m.value
+    return dict(w=w, loss_pool=loss_pool[:P], keep=keep[:P], kept_pos=kept_pos[:k].copy(),
+                kept_ids=kept_ids[:k].copy(), loss=loss[:k].copy(), m=k)
+
+
+def sk_sgd(F, y, w0, mu, G, D, seed, K, w_star=None):
+    """K steps of the iteration of Theorem 1.  Returns (w, dist2 or None, picked, dropped)."""
+    y = _f32(y)
+    w = np.array(w0, dtype=np.float64, copy=True)
+    ws = None if w_star is None else np.ascontiguousarray(w_star, dtype=np.float64)
+    dist2 = None if ws is None else np.zeros(K + 1, dtype=np.float64)
+    picked = np.zeros(max(K, 1), dtype=np.int32)
+    dropped = C.c_int32(0)
+    _check(lib().aa_ref_sk_sgd(F.ref(), _p(y), _p(w), C.c_double(mu), C.c_double(G), C.c_double(D),
+                               C.c_uint64(seed), C.c_int32(K), _p(ws), _p(dist2), _p(picked),
+                               C.byref(dropped)), "sk_sgd")
+    return w, dist2, picked[:K], dropped.value
+
+
+def train_stale(F, y, perm, P, w, phi, bias, gamma, seed, step0, lam, lr0, T, lr_a, staleness,
+                l2_a=0.0):
+    """The asynchronous Boss/Assistant schedule of Section 5.3 made deterministic: the batch
+    of pool s is generated (score, keep draw, compaction) with the Assistant as it stood
+    after `s - staleness` updates, i.e. `staleness` batches wait in the Boss queue while the
+    Assistant keeps learning from the losses the Boss sends back.  Tick s: the Boss takes
+    batch s (losses at its current w, then its update, step size lr0 / sqrt(number of
+    updates so far)), then the Assistant learns from (ids, losses) of that batch at its
+    current parameters.  staleness = 0 is the synchronous step().  Returns a dict with the
+    final state and, per tick, the kept count and kept ids."""
+    perm = _i32(perm)
+    w = np.array(w, dtype=np.float32, copy=True)
+    versions = [(np.array(phi, dtype=np.float32, copy=True), float(bias))]  # Assistant after t ticks
+    ms, ids_hist, t_upd = [], [], 0
+    n = perm.shape[0]
+    for s in range((n + P - 1) // P):
+        idx = perm[s * P:(s + 1) * P]
+        phi_g, b_g = versions[max(0, s - staleness)]
+        _, prob = assistant_score(F, idx, idx.shape[0], phi_g, b_g)
+        _, pos = shrink(prob, gamma, seed, step0 + s)
+        m = pos.shape[0]
+        ids = idx[pos]
+        phi_c, b_c = versions[s]
+        if m > 0:
+            t_upd += 1
+            lr = np.float32(np.float32(lr0) / np.sqrt(np.float32(t_upd)))
+            w, loss = svm_sgd_step(F, y, ids, m, w, lam, lr)
+            phi_n, b_n = assistant_update(F, ids, m, loss, T, phi_c, b_c, lr_a, l2_a)
+        else:
+            phi_n, b_n = phi_c, b_c
+        versions.append((phi_n, b_n))
+        ms.append(m)
+        ids_hist.append(ids.copy())
+    phi_f, b_f = versions[-1]
+    return dict(w=w, phi=phi_f, bias=b_f, m=ms, kept_ids=ids_hist, t_upd=t_upd)
+
+
 def threshold_update(loss, momentum, T, initialised):
     """Returns (T_new, initialised_new)."""
     loss = _f32(loss)

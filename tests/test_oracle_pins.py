@@ -562,3 +562,217 @@ def test_threshold_update_is_numpy_median_with_momentum(ref):
         assert init and np.float32(T) == want
     T2, init2 = ref.threshold_update(np.zeros(0, np.float32), 0.9, 1.25, True)
     assert T2 == 1.25 and init2
+
+
+# ---------------------------------------------------------------------------
+# Hard-threshold shrinking (SK) and the iteration of Theorem 1
+
+
+def test_sk_step_against_its_definition(ref):
+    """keep = (hinge loss at the current w) > T, written out in numpy; the update is the SVM
+    step on exactly those rows; T below every loss is the plain mini-batch step bit for bit;
+    T above every loss changes nothing."""
+    r = rng(31)
+    n, d, P = 300, 12, 200
+    X = r.standard_normal((n, d)).astype(np.float32)
+    y = np.where(r.random(n) < 0.5, 1.0, -1.0).astype(np.float32)
+    w = (0.5 * r.standard_normal(d)).astype(np.float32)
+    idx = r.permutation(n)[:P].astype(np.int32)
+    F = ref.Features.dense(X)
+    lam, lr = 1e-2, 0.3
+    margins = (y[idx].astype(np.float64) * (X[idx].astype(np.float64) @ w.astype(np.float64))
+               ).astype(np.float32)
+    losses = np.maximum(0.0, 1.0 - margins.astype(np.float64)).astype(np.float32)
+    for T in (0.0, 0.7, 1.5):
+        out = ref.sk_step(F, y, idx, P, w, lam, lr, T)
+        want_keep = losses > np.float32(T)
+        assert 0 < want_keep.sum() < P
+        assert np.array_equal(out["keep"].astype(bool), want_keep)
+        assert np.array_equal(out["kept_pos"], np.flatnonzero(want_keep))
+        assert np.array_equal(out["kept_ids"], idx[want_keep])
+        assert np.array_equal(out["loss_pool"], losses)
+        assert np.array_equal(out["loss"], losses[want_keep])
+        m = int(want_keep.sum())
+        # every kept row has a positive loss, hence an active hinge: G = sum of y x over them
+        G = (y[idx][want_keep, None].astype(np.float64) * X[idx][want_keep].astype(np.float64)).sum(0)
+        want_w = (1 - np.float64(np.float32(lr)) * np.float64(np.float32(lam))) * w.astype(np.float64) \
+            + np.float64(np.float32(lr)) / m * G
+        assert np.allclose(out["w"], want_w, rtol=1e-6, atol=1e-7)
+    everything = ref.sk_step(F, y, idx, P, w, lam, lr, -1.0)
+    assert everything["m"] == P
+    assert np.array_equal(everything["w"], ref.vanilla_minibatch_sgd(F, y, idx, P, w, lam, lr))
+    nothing = ref.sk_step(F, y, idx, P, w, lam, lr, 1e9)
+    assert nothing["m"] == 0 and np.array_equal(nothing["w"], w)
+
+
+def test_sk_step_at_T0_is_the_vanilla_direction_rescaled(ref):
+    """With T = 0 the dropped rows are exactly those with zero subgradient, so the data term
+    of the step is the plain mini-batch one scaled by P/m."""
+    r = rng(32)
+    n, d = 400, 10
+    X = r.standard_normal((n, d)).astype(np.float32)
+    y = np.where(r.random(n) < 0.5, 1.0, -1.0).astype(np.float32)
+    w = r.standard_normal(d).astype(np.float32)
+    F = ref.Features.dense(X)
+    lam, lr = 1e-3, 0.2
+    sk = ref.sk_step(F, y, None, n, w, lam, lr, 0.0)
+    van = ref.vanilla_minibatch_sgd(F, y, None, n, w, lam, lr)
+    shrink = 1 - np.float64(np.float32(lr)) * np.float64(np.float32(lam))
+    data_sk = sk["w"].astype(np.float64) - shrink * w
+    data_van = van.astype(np.float64) - shrink * w
+    assert 0 < sk["m"] < n
+    assert np.allclose(data_sk * sk["m"], data_van * n, rtol=1e-4, atol=1e-5)
+
+
+def _svm_optimum(X, y, mu):
+    """argmin (mu/2)|w|^2 + mean hinge, as a smooth program in (w, slack) solved by SLSQP."""
+    import scipy.optimize as opt
+    n, d = X.shape
+    X64, y64 = X.astype(np.float64), y.astype(np.float64)
+
+    def obj(v):
+        return 0.5 * mu * v[:d] @ v[:d] + v[d:].mean()
+
+    def grad(v):
+        return np.concatenate([mu * v[:d], np.full(n, 1.0 / n)])
+
+    A = np.hstack([y64[:, None] * X64, np.eye(n)])          # y x.w + xi >= 1
+    cons = [{"type": "ineq", "fun": lambda v: A @ v - 1.0, "jac": lambda v: A}]
+    bounds = [(None, None)] * d + [(0, None)] * n
+    res = opt.minimize(obj, np.concatenate([np.zeros(d), np.ones(n)]), jac=grad, bounds=bounds,
+                       constraints=cons, method="SLSQP", options={"ftol": 1e-14, "maxiter": 500})
+    assert res.success
+    return res.x[:d]
+
+
+def _theorem_instance():
+    r = rng(33)
+    n, d = 16, 4
+    X = r.standard_normal((n, d)).astype(np.float32)
+    X /= np.linalg.norm(X, axis=1, keepdims=True)
+    y = np.where(X @ np.array([1.0, -1.0, 0.5, 0.0]) + 0.3 * r.standard_normal(n) > 0, 1.0, -1.0
+                 ).astype(np.float32)
+    return X, y
+
+
+def test_theorem_iteration_without_dropping_is_plain_sgd(ref):
+    """G = 0 drops nothing: the iterates equal a numpy loop over the same index sequence,
+    and that sequence is the second Philox word scaled to the row count."""
+    X, y = _theorem_instance()
+    n, d = X.shape
+    F = ref.Features.dense(X)
+    mu, K, seed = 0.5, 200, 9
+    w, _, picked, dropped = ref.sk_sgd(F, y, np.zeros(d), mu, 0.0, 0.0, seed, K)
+    assert dropped == 0
+    want_picked = [(int(ref.philox4x32_10((k, 0, 0, 0), (seed, 0))[1]) * n) >> 32 for k in range(1, K + 1)]
+    assert picked.tolist() == want_picked
+    assert len(set(want_picked)) == n                        # every row is drawn
+    v = np.zeros(d)
+    for k, i in enumerate(want_picked, start=1):
+        g = mu * v - (y[i] * X[i].astype(np.float64) if y[i] * (X[i].astype(np.float64) @ v) < 1 else 0.0)
+        v = v - g / (mu * k)
+    assert np.allclose(w, v, rtol=1e-12, atol=1e-14)
+
+
+def test_theorem_1_bound_holds_on_average(ref):
+    """Theorem 1: with step size 1/(mu k) and steps dropped when |grad f_i| <= G/k, the mean of
+    |w_k - w*|^2 over many index sequences stays below max(4 D^2, G^2/mu^2 + 4 D G/mu) / k.
+    The rule really drops steps here, and the iterates still reach the optimum."""
+    X, y = _theorem_instance()
+    n, d = X.shape
+    F = ref.Features.dense(X)
+    mu = 0.5
+    w_star = _svm_optimum(X, y, mu)
+    # the optimum found by SLSQP satisfies the subgradient optimality condition
+    marg = y * (X.astype(np.float64) @ w_star)
+    lo = mu * w_star - (y[:, None] * X)[marg < 1 - 1e-7].sum(0) / n
+    on = (y[:, None] * X)[np.abs(marg - 1) <= 1e-7]
+    resid = lo if len(on) == 0 else lo - on.T @ np.clip(np.linalg.lstsq(on.T, lo, rcond=None)[0], 0, 1.0 / n)
+    assert np.linalg.norm(resid) < 1e-6
+    D = 1.0 / np.sqrt(mu)                     # Pegasos: the optimum lies in this ball
+    assert np.linalg.norm(w_star) <= D
+    G = mu * D + 1.0                          # |mu w - y x| <= mu D + |x| on the ball, |x| = 1
+    bound = max(4 * D * D, G * G / (mu * mu) + 4 * D * G / mu)
+    K, seeds = 2000, 128
+    dist2 = np.zeros((seeds, K + 1))
+    dropped = np.zeros(seeds, dtype=int)
+    for s in range(seeds):
+        _, dist2[s], _, dropped[s] = ref.sk_sgd(F, y, np.zeros(d), mu, G, D, 1000 + s, K, w_star)
+    mean = dist2.mean(0)
+    k = np.arange(1, K + 2)
+    assert np.all(mean * k <= bound)
+    assert dropped.min() > 0                  # the shrinking rule takes part
+    assert mean[-1] < 0.02 * mean[0]          # and the iterates close in on w*
+    # without dropping (plain SGD) the same bound holds, and shrinking costs little accuracy
+    plain = np.array([ref.sk_sgd(F, y, np.zeros(d), mu, 0.0, D, 1000 + s, K, w_star)[1][-1]
+                      for s in range(seeds)])
+    assert mean[-1] < 3 * plain.mean() + 1e-3
+
+
+# ---------------------------------------------------------------------------
+# Deterministic stale-Assistant schedule
+
+
+def _stale_instance():
+    r = rng(41)
+    n, d = 1000, 16
+    X = r.standard_normal((n, d)).astype(np.float32)
+    X /= np.linalg.norm(X, axis=1, keepdims=True)
+    y = np.where(X @ r.standard_normal(d) > 0, 1.0, -1.0).astype(np.float32)
+    perm = r.permutation(n).astype(np.int32)
+    return X, y, perm
+
+
+def test_stale_schedule_with_zero_staleness_is_the_synchronous_step(ref):
+    X, y, perm = _stale_instance()
+    n, d = X.shape
+    F = ref.Features.dense(X)
+    P, gamma, seed, lam, lr0, T, lr_a = 128, 0.1, 3, 1e-3, 0.5, 0.0, 0.2
+    got = ref.train_stale(F, y, perm, P, np.zeros(d), np.zeros(d), 0.0, gamma, seed, 10, lam, lr0,
+                          T, lr_a, staleness=0)
+    w, phi, b, t_upd = np.zeros(d, np.float32), np.zeros(d, np.float32), 0.0, 0
+    for s in range((n + P - 1) // P):
+        idx = perm[s * P:(s + 1) * P]
+        lr = np.float32(np.float32(lr0) / np.sqrt(np.float32(t_upd + 1)))
+        out = ref.step(F, y, idx, idx.size, w, phi, b, gamma, seed, 10 + s, lam, lr, T, lr_a)
+        w, phi, b = out["w"], out["phi"], out["bias"]
+        t_upd += out["m"] > 0
+        assert out["m"] == got["m"][s] and np.array_equal(out["kept_ids"], got["kept_ids"][s])
+    assert np.array_equal(got["w"], w) and np.array_equal(got["phi"], phi) and got["bias"] == b
+
+
+def test_stale_schedule_uses_the_assistant_of_k_ticks_ago(ref):
+    """Batch s is drawn with the Assistant as it stood after s - k updates: with k beyond the
+    number of pools every batch comes from the initial Assistant; with k = 1 the first two
+    batches do, and the third from the Assistant after exactly one update."""
+    X, y, perm = _stale_instance()
+    n, d = X.shape
+    F = ref.Features.dense(X)
+    P, gamma, seed, lam, lr0, T, lr_a = 128, 0.0, 3, 1e-3, 0.5, 0.5, 2.0
+    phi0 = (0.5 * rng(42).standard_normal(d)).astype(np.float32)
+    S = (n + P - 1) // P
+
+    def batch(s, phi, b):
+        idx = perm[s * P:(s + 1) * P]
+        _, prob = ref.assistant_score(F, idx, idx.size, phi, b)
+        _, pos = ref.shrink(prob, gamma, seed, s)
+        return idx[pos]
+
+    far = ref.train_stale(F, y, perm, P, np.zeros(d), phi0, 0.1, gamma, seed, 0, lam, lr0, T, lr_a,
+                          staleness=S + 5)
+    for s in range(S):
+        assert np.array_equal(far["kept_ids"][s], batch(s, phi0, 0.1))
+    one = ref.train_stale(F, y, perm, P, np.zeros(d), phi0, 0.1, gamma, seed, 0, lam, lr0, T, lr_a,
+                          staleness=1)
+    sync = ref.train_stale(F, y, perm, P, np.zeros(d), phi0, 0.1, gamma, seed, 0, lam, lr0, T, lr_a,
+                           staleness=0)
+    assert np.array_equal(one["kept_ids"][0], batch(0, phi0, 0.1))
+    assert np.array_equal(one["kept_ids"][1], batch(1, phi0, 0.1))
+    # tick 0 by hand: Boss step on batch 0, then the Assistant update at phi0
+    ids0 = batch(0, phi0, 0.1)
+    w1, loss0 = ref.svm_sgd_step(F, y, ids0, ids0.size, np.zeros(d, np.float32), lam, np.float32(lr0))
+    phi1, b1 = ref.assistant_update(F, ids0, ids0.size, loss0, T, phi0, 0.1, lr_a)
+    assert np.array_equal(one["kept_ids"][2], batch(2, phi1, b1))
+    assert np.array_equal(sync["kept_ids"][1], batch(1, phi1, b1))
+    # the schedules really differ on this instance
+    assert not np.array_equal(one["kept_ids"][1], sync["kept_ids"][1])
