@@ -219,6 +219,20 @@ int32_t aa_fused_step(const aa_features *F, const float *y, const int32_t *idx, 
                       int32_t *kept_ids, float *loss, int32_t *kept_count, void *ws,
                       size_t ws_bytes, void *stream);
 
+/* ---- Hard-threshold shrinking (SK of Section 3.4; the update of eq.
+ * "shrinking_grad" with the objective value as the criterion), one step on the
+ * pool idx[0..P-1] with every feature row read once: crit_j = max(0, 1 - y w.x)
+ * of candidate j at the current w; keep_j = (crit_j > *T); stable compaction;
+ * w <- (1 - lr*lambda) w + (lr/m) sum over kept rows with margin < 1 of y x;
+ * m == 0 changes nothing.  No Assistant takes part.  T: device scalar.
+ * Outputs: loss_pool[P] = crit (may be NULL), keep[P] (may be NULL),
+ * kept_pos[<=P], kept_ids[<=P], loss[<=P] = crit of the kept rows in kept order
+ * (each may be NULL), *kept_count (device, required).  Errors as aa_fused_step. */
+int32_t aa_sk_step(const aa_features *F, const float *y, const int32_t *idx, int32_t P, float *w,
+                   const float *T, float lambda, float lr, float *loss_pool, uint8_t *keep,
+                   int32_t *kept_pos, int32_t *kept_ids, float *loss, int32_t *kept_count,
+                   void *ws, size_t ws_bytes, void *stream);
+
 /* One epoch of fused steps: pool t is perm[t*P : min((t+1)*P, n_perm)] (the
  * shuffled index list that replaces uniform sampling, Section 5.2), Philox
  * step = cfg->step + t, Boss step size lr_t = cfg->lr / sqrt(t_upd) where

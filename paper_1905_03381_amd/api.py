@@ -21,7 +21,7 @@ SYMBOLS = [
     "aa_version", "aa_status_string", "aa_workspace_bytes", "aa_workspace_init", "aa_profile_hook",
     "aa_assistant_score", "aa_shrink", "aa_score_shrink", "aa_shrink_threshold", "aa_gather",
     "aa_gather_csr", "aa_svm_sgd_step", "aa_assistant_update", "aa_boss_assistant_step",
-    "aa_fused_step", "aa_train_epoch", "aa_threshold_update", "aa_bucket_batches",
+    "aa_fused_step", "aa_sk_step", "aa_train_epoch", "aa_threshold_update", "aa_bucket_batches",
 ]
 
 
@@ -71,6 +71,7 @@ def lib():
         "aa_assistant_update": (i32, [FP, vp, vp, i32, vp, vp, vp, vp, f32, f32, vp, sz, vp]),
         "aa_boss_assistant_step": (i32, [FP, vp, vp, vp, i32, vp, vp, vp, CP, vp, vp, sz, vp]),
         "aa_fused_step": (i32, [FP, vp, vp, i32, vp, vp, vp, CP, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
+        "aa_sk_step": (i32, [FP, vp, vp, i32, vp, vp, f32, f32, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
         "aa_train_epoch": (i32, [FP, vp, vp, i64, i32, vp, vp, vp, CP, vp, vp, vp, sz, vp]),
         "aa_threshold_update": (i32, [vp, vp, i32, f32, vp, vp, vp]),
         "aa_bucket_batches": (i32, [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]),
@@ -216,6 +217,12 @@ def fused_step(F, y, idx, P, w, phi, bias, cfg, logit, prob, keep, kept_pos, kep
                                C.byref(cfg), _ptr(logit), _ptr(prob), _ptr(keep), _ptr(kept_pos),
                                _ptr(kept_ids), _ptr(loss), _ptr(kept_count), ws.ptr, ws.bytes,
                                _stream()), "aa_fused_step")
+
+
+def sk_step(F, y, idx, P, w, T, lam, lr, loss_pool, keep, kept_pos, kept_ids, loss, kept_count, ws):
+    _check(lib().aa_sk_step(F.ref(), _ptr(y), _ptr(idx), P, _ptr(w), _ptr(T), lam, lr,
+                            _ptr(loss_pool), _ptr(keep), _ptr(kept_pos), _ptr(kept_ids), _ptr(loss),
+                            _ptr(kept_count), ws.ptr, ws.bytes, _stream()), "aa_sk_step")
 
 
 def train_epoch(F, y, perm, n_perm, P, w, phi, bias, cfg, t_upd, kept_hist, ws):

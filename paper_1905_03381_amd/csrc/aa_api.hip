@@ -682,6 +682,48 @@ int32_t aa_fused_step(const aa_features *F, const float *y, const int32_t *idx, 
                          as_stream(stream));
 }
 
+int32_t aa_sk_step(const aa_features *F, const float *y, const int32_t *idx, int32_t P, float *w,
+                   const float *T, float lambda, float lr, float *loss_pool, uint8_t *keep,
+                   int32_t *kept_pos, int32_t *kept_ids, float *loss, int32_t *kept_count,
+                   void *ws_ptr, size_t ws_bytes, void *stream) {
+  if (P < 0) return AA_ERR_SHAPE;
+  if (!kept_count) return AA_ERR_NULL;
+  hipStream_t st = as_stream(stream);
+  if (P == 0) {
+    CompactArgs c{};
+    c.kept_count = kept_count;
+    return hip_status(launch_compact(c, nullptr, st));
+  }
+  if (int32_t rc = check_features(F)) return rc;
+  if (!y || !w || !T) return AA_ERR_NULL;
+  PassSpec s{};
+  s.F = F;
+  s.mode = kPool | kSvm | kHard;
+  s.y = y;
+  s.rows = idx;
+  s.count_max = P;
+  s.w = w;
+  s.T = T;
+  Ws ws = carve(ws_ptr, grad_bytes_for(s), P);
+  if (int32_t rc = check_ws(ws_ptr, ws_bytes, ws.total)) return rc;
+  s.flags = keep ? keep : ws.flags;
+  s.loss_out = loss_pool ? loss_pool : ws.loss_pool;
+  int32_t nblk = 0;
+  if (run_pass(s, ws, &nblk, st) != hipSuccess) return AA_ERR_HIP;
+  UpdateSpec u{};
+  u.lambda = lambda;
+  u.lr = lr;
+  u.flags = s.flags;
+  u.P = P;
+  u.idx = idx;
+  u.kept_pos = kept_pos;
+  u.kept_ids = kept_ids;
+  u.loss_pool = s.loss_out;
+  u.loss = loss;
+  u.kept_count = kept_count;
+  return hip_status(run_update(s, u, ws, nblk, st));
+}
+
 int32_t aa_threshold_update(const float *loss, const int32_t *m_dev, int32_t m_max, float momentum,
                             float *T, int32_t *initialised, void *stream) {
   if (m_max < 0 || m_max > kMedianMax) return AA_ERR_SHAPE;

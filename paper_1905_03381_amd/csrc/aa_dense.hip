@@ -106,8 +106,9 @@ __global__ __launch_bounds__(NW * 64)
   constexpr bool POOL = (MODE & kPool) != 0;
   constexpr bool SVM = (MODE & kSvm) != 0;
   constexpr bool ASSIST = (MODE & kAssist) != 0;
+  constexpr bool HARD = (MODE & kHard) != 0;  // keep by the row's own loss, no Assistant
   constexpr bool GRAD = SVM || ASSIST;
-  constexpr bool NEED_PHI = POOL || ASSIST;
+  constexpr bool NEED_PHI = (POOL && !HARD) || ASSIST;
   constexpr int G = kWave / LPR;  // rows per wave iteration
   constexpr int ROW4 = LPR * VPL;
   constexpr int NVEC = (SVM ? 1 : 0) + (ASSIST ? 1 : 0);
@@ -149,7 +150,7 @@ __global__ __launch_bounds__(NW * 64)
     st_p[q] = (NEED_PHI && c < a.d4) ? reinterpret_cast<const f4 *>(a.phi)[c] : zero4;
   }
   const float b = (NEED_PHI && a.bias) ? *a.bias : 0.f;
-  const float T = ASSIST ? *a.T : 0.f;
+  const float T = (ASSIST || HARD) ? *a.T : 0.f;
 
   f4 x[RIF][VPL];
   // Every load of the next RIF rows, before any is used.  When the row fills the lane layout
@@ -253,7 +254,11 @@ __global__ __launch_bounds__(NW * 64)
             dw = row_group_sum<LPR>(dw, lane);
             const float marg = yy * dw;
             loss = fmaxf(0.f, 1.f - marg);
-            if (sub == 0 && keep && a.loss_out) a.loss_out[j] = loss;
+            if (HARD) {  // shrinking by the objective value itself
+              keep = live && loss > T;
+              if (sub == 0 && live && a.flags) a.flags[j] = keep ? 1 : 0;
+            }
+            if (sub == 0 && (HARD ? live : keep) && a.loss_out) a.loss_out[j] = loss;
             const float cw = (keep && marg < 1.f) ? yy : 0.f;  // -d hinge / d margin, times y
 #pragma unroll
             for (int v = 0; v < VPL; ++v) gw[v] = axpy4(cw, x[r][v], gw[v]);
@@ -492,6 +497,10 @@ hipError_t launch_grad(const PassArgs &a, int mode, int nblk, hipStream_t st) {
       break;
     case kPool | kSvm | kAssist:
       hipLaunchKernelGGL((k_rows_pass<LPR, VPL, kPool | kSvm | kAssist, NW, RIF>), grid, block, 0,
+                         st, a);
+      break;
+    case kPool | kSvm | kHard:
+      hipLaunchKernelGGL((k_rows_pass<LPR, VPL, kPool | kSvm | kHard, NW, RIF>), grid, block, 0,
                          st, a);
       break;
     default:

@@ -5,11 +5,13 @@
 
 namespace aa {
 
-enum : int { kSvm = 1, kAssist = 2, kPool = 4 };
+enum : int { kSvm = 1, kAssist = 2, kPool = 4, kHard = 8 };
 
 // One pass over feature rows.  In pool mode (kPool) the pass walks the candidate
 // pool: score, keep draw and -- with kSvm|kAssist -- both gradient sums of the
 // kept rows.  Without kPool it walks rows already chosen (kept ids).
+// kPool|kSvm|kHard is the hard-threshold pool pass: no Assistant, a candidate is
+// kept when its own hinge loss at the current w exceeds *T.
 struct PassArgs {
   const float *x;
   int64_t ld;
@@ -21,7 +23,7 @@ struct PassArgs {
   const float *w;
   const float *phi;
   const float *bias;      // device scalar or NULL
-  const float *T;         // device scalar (kAssist)
+  const float *T;         // device scalar (kAssist, kHard)
   float gamma, one_minus_gamma;
   DrawKey key;
   int32_t do_keep;        // pool mode: draw keep flags

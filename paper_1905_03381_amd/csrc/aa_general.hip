@@ -32,8 +32,9 @@ __global__ __launch_bounds__(512) void k_rows_general(const GenArgs a) {
   constexpr bool POOL = (MODE & kPool) != 0;
   constexpr bool SVM = (MODE & kSvm) != 0;
   constexpr bool ASSIST = (MODE & kAssist) != 0;
+  constexpr bool HARD = (MODE & kHard) != 0;  // keep by the row's own loss, no Assistant
   constexpr bool GRAD = SVM || ASSIST;
-  constexpr bool NEED_PHI = POOL || ASSIST;
+  constexpr bool NEED_PHI = (POOL && !HARD) || ASSIST;
   constexpr int G = kWave / GL;
   constexpr int HEAD = GRAD ? kHeadBytes / 4 / ((SVM ? 1 : 0) + (ASSIST ? 1 : 0)) : 0;
   __shared__ float s_head[GRAD ? kHeadBytes / 4 : 1];
@@ -53,7 +54,7 @@ __global__ __launch_bounds__(512) void k_rows_general(const GenArgs a) {
   const int hi = lo + per + (gwave < rem ? 1 : 0);
 
   const float b = (NEED_PHI && a.bias) ? *a.bias : 0.f;
-  const float T = ASSIST ? *a.T : 0.f;
+  const float T = (ASSIST || HARD) ? *a.T : 0.f;
   float gb = 0.f;
   int kept = 0;
 
@@ -117,7 +118,11 @@ __global__ __launch_bounds__(512) void k_rows_general(const GenArgs a) {
           dw = gsum<GL>(dw);
           const float marg = yy * dw;
           loss = fmaxf(0.f, 1.f - marg);
-          if (sub == 0 && keep && a.loss_out) a.loss_out[j] = loss;
+          if (HARD) {  // shrinking by the objective value itself
+            keep = live && loss > T;
+            if (sub == 0 && live && a.flags) a.flags[j] = keep ? 1 : 0;
+          }
+          if (sub == 0 && (HARD ? live : keep) && a.loss_out) a.loss_out[j] = loss;
           cw = (keep && marg < 1.f) ? yy : 0.f;
         }
         if (ASSIST) {
@@ -228,6 +233,9 @@ hipError_t launch_gl(const GenArgs &a, int mode, int nblk, hipStream_t st) {
       break;
     case kPool | kSvm | kAssist:
       hipLaunchKernelGGL((k_rows_general<GL, kPool | kSvm | kAssist, CSR>), grid, block, 0, st, a);
+      break;
+    case kPool | kSvm | kHard:
+      hipLaunchKernelGGL((k_rows_general<GL, kPool | kSvm | kHard, CSR>), grid, block, 0, st, a);
       break;
     default:
       return hipErrorInvalidValue;

@@ -71,6 +71,33 @@ def abs_dot_scale(F_host, ids, v):
     return out
 
 
+def row_dots(F_host, ids, v):
+    """x_r . v in float64 for each listed row (dense or CSR)."""
+    ids = np.asarray(ids, dtype=np.int64)
+    v = np.asarray(v, dtype=np.float64)
+    if F_host.c.layout == 0:
+        return F_host.x[ids, :F_host.d].astype(np.float64) @ v
+    out = np.zeros(ids.size)
+    for r, i in enumerate(ids):
+        lo, hi = F_host.rowptr[i], F_host.rowptr[i + 1]
+        xv = np.ones(hi - lo) if F_host.val is None else F_host.val[lo:hi].astype(np.float64)
+        out[r] = np.sum(xv * v[F_host.col[lo:hi]])
+    return out
+
+
+def col_abs_sum(F_host, ids):
+    """sum over the listed rows of |x_r|, per column, float64."""
+    ids = np.asarray(ids, dtype=np.int64)
+    if F_host.c.layout == 0:
+        return np.abs(F_host.x[ids, :F_host.d].astype(np.float64)).sum(axis=0)
+    out = np.zeros(F_host.d)
+    for i in ids:
+        lo, hi = F_host.rowptr[i], F_host.rowptr[i + 1]
+        xv = np.ones(hi - lo) if F_host.val is None else np.abs(F_host.val[lo:hi].astype(np.float64))
+        np.add.at(out, F_host.col[lo:hi], xv)
+    return out
+
+
 def assert_close_scaled(got, ref, scale, what, rtol=RTOL, atol=0.0):
     got, ref = np.asarray(got, dtype=np.float64), np.asarray(ref, dtype=np.float64)
     bound = rtol * np.maximum(np.abs(ref), scale) + atol
