@@ -247,6 +247,32 @@ int32_t aa_train_epoch(const aa_features *F, const float *y, const int32_t *perm
                        const aa_step_config *cfg, int32_t *t_upd, int32_t *kept_hist, void *ws,
                        size_t ws_bytes, void *stream);
 
+/* ---- The asynchronous Boss / Assistant schedule of Section 5.3 in a deterministic
+ * form, on two streams.  Pool s is perm[s*P : min((s+1)*P, n_perm)].  The
+ * generator (stream_gen) makes batch s -- score, keep draw with Philox step
+ * cfg->step + s, stable compaction to kept ids -- with the Assistant as it stood
+ * after max(0, s - staleness) updates, so `staleness` batches wait in the Boss
+ * queue while the Assistant keeps learning.  The Boss (stream_boss), tick s: SVM
+ * step on batch s (losses at the pre-update w, lr_t = cfg->lr / sqrt(t_upd) as in
+ * aa_train_epoch), then the Assistant update from those losses at its current
+ * parameters.  Generation of batch s + staleness overlaps Boss tick s; events
+ * order the two streams, the result does not depend on timing.  staleness = 0 is
+ * the synchronous schedule (the generator then waits for every Boss tick).
+ * On return all work is enqueued; the last Boss tick waits for every generator
+ * launch, so synchronising stream_boss is enough.  The caller makes its inputs
+ * visible to stream_boss; stream_gen must be a different stream with no
+ * unrelated work pending.  0 <= staleness <= 15.
+ * kept_hist[steps] (may be NULL): kept count of each tick.  kept_ids_hist
+ * [steps][P] (may be NULL): the kept ids of each batch, row s holding
+ * kept_hist[s] entries.  ws must hold aa_pipeline_workspace_bytes(P, d,
+ * staleness) bytes.  t_upd needs the fast dense layout (AA_ERR_SHAPE). */
+size_t aa_pipeline_workspace_bytes(int32_t P_max, int32_t d_max, int32_t staleness);
+int32_t aa_train_epoch_stale(const aa_features *F, const float *y, const int32_t *perm,
+                             int64_t n_perm, int32_t P, int32_t staleness, float *w, float *phi,
+                             float *bias, const aa_step_config *cfg, int32_t *t_upd,
+                             int32_t *kept_hist, int32_t *kept_ids_hist, void *ws,
+                             size_t ws_bytes, void *stream_boss, void *stream_gen);
+
 #ifdef __cplusplus
 }
 #endif

@@ -285,19 +285,20 @@ def sk_sgd(F, y, w0, mu, G, D, seed, K, w_star=None):
 
 
 def train_stale(F, y, perm, P, w, phi, bias, gamma, seed, step0, lam, lr0, T, lr_a, staleness,
-                l2_a=0.0):
+                l2_a=0.0, schedule=True):
     """The asynchronous Boss/Assistant schedule of Section 5.3 made deterministic: the batch
     of pool s is generated (score, keep draw, compaction) with the Assistant as it stood
     after `s - staleness` updates, i.e. `staleness` batches wait in the Boss queue while the
     Assistant keeps learning from the losses the Boss sends back.  Tick s: the Boss takes
     batch s (losses at its current w, then its update, step size lr0 / sqrt(number of
     updates so far)), then the Assistant learns from (ids, losses) of that batch at its
-    current parameters.  staleness = 0 is the synchronous step().  Returns a dict with the
-    final state and, per tick, the kept count and kept ids."""
+    current parameters.  staleness = 0 is the synchronous step().  schedule=False keeps the
+    Boss step size at lr0.  Returns a dict with the final state and, per tick, the kept
+    count, the kept ids and the keep probabilities the batch was drawn with."""
     perm = _i32(perm)
     w = np.array(w, dtype=np.float32, copy=True)
     versions = [(np.array(phi, dtype=np.float32, copy=True), float(bias))]  # Assistant after t ticks
-    ms, ids_hist, t_upd = [], [], 0
+    ms, ids_hist, prob_hist, t_upd = [], [], [], 0
     n = perm.shape[0]
     for s in range((n + P - 1) // P):
         idx = perm[s * P:(s + 1) * P]
@@ -309,7 +310,7 @@ def train_stale(F, y, perm, P, w, phi, bias, gamma, seed, step0, lam, lr0, T, lr
         phi_c, b_c = versions[s]
         if m > 0:
             t_upd += 1
-            lr = np.float32(np.float32(lr0) / np.sqrt(np.float32(t_upd)))
+            lr = np.float32(np.float32(lr0) / np.sqrt(np.float32(t_upd))) if schedule else np.float32(lr0)
             w, loss = svm_sgd_step(F, y, ids, m, w, lam, lr)
             phi_n, b_n = assistant_update(F, ids, m, loss, T, phi_c, b_c, lr_a, l2_a)
         else:
@@ -317,8 +318,9 @@ def train_stale(F, y, perm, P, w, phi, bias, gamma, seed, step0, lam, lr0, T, lr
         versions.append((phi_n, b_n))
         ms.append(m)
         ids_hist.append(ids.copy())
+        prob_hist.append(prob)
     phi_f, b_f = versions[-1]
-    return dict(w=w, phi=phi_f, bias=b_f, m=ms, kept_ids=ids_hist, t_upd=t_upd)
+    return dict(w=w, phi=phi_f, bias=b_f, m=ms, kept_ids=ids_hist, prob=prob_hist, t_upd=t_upd)
 
 
 def threshold_update(loss, momentum, T, initialised):

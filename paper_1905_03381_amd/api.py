@@ -22,6 +22,7 @@ SYMBOLS = [
     "aa_assistant_score", "aa_shrink", "aa_score_shrink", "aa_shrink_threshold", "aa_gather",
     "aa_gather_csr", "aa_svm_sgd_step", "aa_assistant_update", "aa_boss_assistant_step",
     "aa_fused_step", "aa_sk_step", "aa_train_epoch", "aa_threshold_update", "aa_bucket_batches",
+    "aa_pipeline_workspace_bytes", "aa_train_epoch_stale",
 ]
 
 
@@ -74,6 +75,8 @@ def lib():
         "aa_sk_step": (i32, [FP, vp, vp, i32, vp, vp, f32, f32, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
         "aa_train_epoch": (i32, [FP, vp, vp, i64, i32, vp, vp, vp, CP, vp, vp, vp, sz, vp]),
         "aa_threshold_update": (i32, [vp, vp, i32, f32, vp, vp, vp]),
+        "aa_pipeline_workspace_bytes": (sz, [i32, i32, i32]),
+        "aa_train_epoch_stale": (i32, [FP, vp, vp, i64, i32, i32, vp, vp, vp, CP, vp, vp, vp, vp, sz, vp, vp]),
         "aa_bucket_batches": (i32, [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]),
     }
     for name, (res, args) in sig.items():
@@ -132,8 +135,12 @@ class Features:
 class Workspace:
     """Device scratch for pools up to P_max candidates and d_max features."""
 
-    def __init__(self, P_max, d_max, device="cuda"):
-        self.bytes = int(lib().aa_workspace_bytes(P_max, d_max))
+    def __init__(self, P_max, d_max, device="cuda", staleness=None):
+        """staleness: size the workspace for aa_train_epoch_stale with up to that staleness."""
+        if staleness is None:
+            self.bytes = int(lib().aa_workspace_bytes(P_max, d_max))
+        else:
+            self.bytes = int(lib().aa_pipeline_workspace_bytes(P_max, d_max, staleness))
         self.buf = torch.empty(self.bytes + 256, dtype=torch.uint8, device=device)
         off = (-self.buf.data_ptr()) % 256
         self.ptr = self.buf.data_ptr() + off
@@ -229,6 +236,15 @@ def train_epoch(F, y, perm, n_perm, P, w, phi, bias, cfg, t_upd, kept_hist, ws):
     _check(lib().aa_train_epoch(F.ref(), _ptr(y), _ptr(perm), n_perm, P, _ptr(w), _ptr(phi),
                                 _ptr(bias), C.byref(cfg), _ptr(t_upd), _ptr(kept_hist), ws.ptr,
                                 ws.bytes, _stream()), "aa_train_epoch")
+
+
+def train_epoch_stale(F, y, perm, n_perm, P, staleness, w, phi, bias, cfg, t_upd, kept_hist,
+                      kept_ids_hist, ws, stream_gen):
+    """stream_gen: a torch.cuda.Stream other than the current one (the Boss runs on the current)."""
+    _check(lib().aa_train_epoch_stale(F.ref(), _ptr(y), _ptr(perm), n_perm, P, staleness, _ptr(w),
+                                      _ptr(phi), _ptr(bias), C.byref(cfg), _ptr(t_upd),
+                                      _ptr(kept_hist), _ptr(kept_ids_hist), ws.ptr, ws.bytes,
+                                      _stream(), stream_gen.cuda_stream), "aa_train_epoch_stale")
 
 
 def threshold_update(loss, m_dev, m_max, momentum, T, initialised):

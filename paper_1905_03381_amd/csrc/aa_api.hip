@@ -223,6 +223,8 @@ struct UpdateSpec {
   float lambda, lr, lr_a, l2_a;
   int32_t *t_upd;
   int32_t *kept_hist;
+  float *phi_copy;   // optional second destination of the updated Assistant
+  float *bias_copy;
   // compaction of a pool pass (flags == NULL: none)
   const uint8_t *flags;
   int32_t P;
@@ -258,6 +260,8 @@ hipError_t run_update(const PassSpec &s, const UpdateSpec &u, const Ws &ws, int3
     f.l2_a = u.l2_a;
     f.t_upd = u.t_upd;
     f.kept_hist = u.kept_hist;
+    f.phi_copy = u.phi_copy;
+    f.bias_copy = u.bias_copy;
     f.t_snap = ws.ctl + kCtlUpdateSnapshot;
     f.flags = u.flags;
     f.P = u.P;
@@ -286,6 +290,8 @@ hipError_t run_update(const PassSpec &s, const UpdateSpec &u, const Ws &ws, int3
   p.lr_a = u.lr_a;
   p.l2_a = u.l2_a;
   p.kept_hist = u.kept_hist;
+  p.phi_copy = u.phi_copy;
+  p.bias_copy = u.bias_copy;
   p.flags = u.flags;
   p.P = u.P;
   p.idx = u.idx;
@@ -380,6 +386,37 @@ int32_t fused_step_impl(const aa_features *F, const float *y, const int32_t *idx
   }
   return hip_status(run_update(s, u, ws, nblk, st));
 }
+
+// Extra workspace of the two-stream pipeline behind the common layout: `ring` batch slots
+// (kept ids + kept count) and `ring` Assistant snapshots (phi, then the bias).
+struct PipeWs {
+  size_t ids_stride, slot_stride, snap_stride;
+  char *slots, *snaps;
+  size_t total;
+  int32_t *ids(int r) const { return reinterpret_cast<int32_t *>(slots + r * slot_stride); }
+  int32_t *count(int r) const { return reinterpret_cast<int32_t *>(slots + r * slot_stride + ids_stride); }
+  float *phi(int r) const { return reinterpret_cast<float *>(snaps + r * snap_stride); }
+};
+
+PipeWs carve_pipeline(char *base, size_t off, int32_t P, int32_t d, int32_t ring) {
+  PipeWs p;
+  p.ids_stride = align_up(sizeof(int32_t) * (size_t)(P > 0 ? P : 0), 256);
+  p.slot_stride = p.ids_stride + 256;
+  p.snap_stride = align_up(sizeof(float) * ((size_t)d + 4), 256);
+  p.slots = base + off;
+  p.snaps = p.slots + (size_t)ring * p.slot_stride;
+  p.total = off + (size_t)ring * (p.slot_stride + p.snap_stride);
+  return p;
+}
+
+__global__ void k_copy_model(const float *phi, const float *bias, int32_t d, float *phi_out,
+                             float *bias_out) {
+  for (int k = blockIdx.x * blockDim.x + threadIdx.x; k < d; k += gridDim.x * blockDim.x)
+    phi_out[k] = phi[k];
+  if (blockIdx.x == 0 && threadIdx.x == 0 && bias) *bias_out = *bias;
+}
+
+constexpr int kMaxStaleness = 15;
 
 }  // namespace
 
@@ -779,6 +816,135 @@ int32_t aa_train_epoch(const aa_features *F, const float *y, const int32_t *perm
     if (rc != AA_OK) return rc;
   }
   return AA_OK;
+}
+
+size_t aa_pipeline_workspace_bytes(int32_t P_max, int32_t d_max, int32_t staleness) {
+  if (staleness < 0) staleness = 0;
+  if (staleness > kMaxStaleness) staleness = kMaxStaleness;
+  const size_t base = aa_workspace_bytes(P_max, d_max);
+  return carve_pipeline(nullptr, base, P_max, d_max < 1 ? 1 : d_max, staleness + 1).total;
+}
+
+int32_t aa_train_epoch_stale(const aa_features *F, const float *y, const int32_t *perm,
+                             int64_t n_perm, int32_t P, int32_t staleness, float *w, float *phi,
+                             float *bias, const aa_step_config *cfg, int32_t *t_upd,
+                             int32_t *kept_hist, int32_t *kept_ids_hist, void *ws_ptr,
+                             size_t ws_bytes, void *stream_boss, void *stream_gen) {
+  if (P <= 0 || n_perm < 0 || staleness < 0 || staleness > kMaxStaleness) return AA_ERR_SHAPE;
+  if (n_perm == 0) return AA_OK;
+  if (int32_t rc = check_features(F)) return rc;
+  if (!y || !w || !phi || !cfg || !cfg->T || !perm) return AA_ERR_NULL;
+  hipStream_t sb = as_stream(stream_boss), sg = as_stream(stream_gen);
+  if (sb == sg) return AA_ERR_SHAPE;  // the generator needs a stream of its own
+  const int ring = staleness + 1;
+  const int64_t steps = (n_perm + P - 1) / P;
+
+  // Boss pass over kept rows: the description every tick shares
+  PassSpec boss{};
+  boss.F = F;
+  boss.mode = kSvm | kAssist;
+  boss.y = y;
+  boss.count_max = P;
+  boss.w = w;
+  boss.phi = phi;
+  boss.bias = bias;
+  boss.T = cfg->T;
+  boss.t_upd = t_upd;
+  if (t_upd && !use_fast(boss)) return AA_ERR_SHAPE;  // device-side step-size schedule: fast dense only
+  const size_t need_common = aa_workspace_bytes(P, F->d);
+  Ws ws = carve(ws_ptr, grad_bytes_for(boss), P, true);
+  if (ws.total > need_common) return AA_ERR_WORKSPACE;
+  PipeWs pw = carve_pipeline(static_cast<char *>(ws_ptr), need_common, P, F->d, ring);
+  if (int32_t rc = check_ws(ws_ptr, ws_bytes, pw.total)) return rc;
+  boss.loss_out = ws.loss;
+
+  hipEvent_t ev_boss[kMaxStaleness + 1], ev_gen[kMaxStaleness + 1], ev_start;
+  if (hipEventCreateWithFlags(&ev_start, hipEventDisableTiming) != hipSuccess) return AA_ERR_HIP;
+  int made = 0;  // complete (Boss, generator) event pairs
+  int32_t rc = AA_OK;
+  while (made < ring) {
+    if (hipEventCreateWithFlags(&ev_boss[made], hipEventDisableTiming) != hipSuccess) break;
+    if (hipEventCreateWithFlags(&ev_gen[made], hipEventDisableTiming) != hipSuccess) {
+      (void)hipEventDestroy(ev_boss[made]);
+      break;
+    }
+    ++made;
+  }
+  if (made < ring) rc = AA_ERR_HIP;
+  auto hip_ok = [&rc](hipError_t e) {
+    if (e != hipSuccess && rc == AA_OK) rc = AA_ERR_HIP;
+    return rc == AA_OK;
+  };
+
+  if (rc == AA_OK) {
+    // version 0 of the Assistant: what every batch made before the first feedback is drawn with
+    hipLaunchKernelGGL(k_copy_model, dim3((F->d + 1023) / 1024 > 64 ? 64 : (F->d + 1023) / 1024),
+                       dim3(1024), 0, sb, phi, bias, F->d, pw.phi(0), pw.phi(0) + F->d);
+    hip_ok(hipGetLastError());
+    hip_ok(hipEventRecord(ev_start, sb));
+    hip_ok(hipStreamWaitEvent(sg, ev_start, 0));
+  }
+  for (int64_t s = 0; s < steps && rc == AA_OK; ++s) {
+    const int64_t lo = s * P;
+    const int32_t Ps = (int32_t)((n_perm - lo) < P ? (n_perm - lo) : P);
+    const int slot = (int)(s % ring);
+    int32_t *ids = kept_ids_hist ? kept_ids_hist + s * (int64_t)P : pw.ids(slot);
+    int32_t *count = pw.count(slot);
+
+    // ---- generator: batch s from the Assistant as it stood after s - staleness updates
+    const int64_t version = s > staleness ? s - staleness : 0;
+    // that version is written by the Boss tick before it, which also is the last reader of
+    // the batch slot and the writer of the snapshot slot reused here
+    if (version > 0) hip_ok(hipStreamWaitEvent(sg, ev_boss[(version - 1) % ring], 0));
+    PassSpec g{};
+    g.F = F;
+    g.mode = kPool;
+    g.rows = perm + lo;
+    g.count_max = Ps;
+    g.phi = pw.phi((int)(version % ring));
+    g.bias = bias ? g.phi + F->d : nullptr;
+    g.gamma = cfg->gamma;
+    g.seed = cfg->seed;
+    g.step = cfg->step + (uint64_t)s;
+    g.do_keep = 1;
+    g.flags = ws.flags;
+    int32_t nblk = 0;
+    if (rc == AA_OK) hip_ok(run_pass(g, ws, &nblk, sg));
+    CompactArgs c{};
+    c.flags = ws.flags;
+    c.P = Ps;
+    c.idx = perm + lo;
+    c.kept_ids = ids;
+    c.kept_count = count;
+    if (rc == AA_OK) hip_ok(launch_compact(c, ws.tile_off, sg));
+    if (rc == AA_OK) hip_ok(hipEventRecord(ev_gen[slot], sg));
+
+    // ---- Boss tick s, then the Assistant update from its losses; the updated Assistant is
+    // also stored as version s + 1
+    if (rc == AA_OK) hip_ok(hipStreamWaitEvent(sb, ev_gen[slot], 0));
+    boss.rows = ids;
+    boss.count_max = Ps;
+    boss.m_dev = count;
+    if (rc == AA_OK) hip_ok(run_pass(boss, ws, &nblk, sb));
+    UpdateSpec u{};
+    u.lambda = cfg->lambda;
+    u.lr = cfg->lr;
+    u.lr_a = cfg->lr_a;
+    u.l2_a = cfg->l2_a;
+    u.t_upd = t_upd;
+    u.kept_hist = kept_hist ? kept_hist + s : nullptr;
+    u.phi_copy = pw.phi((int)((s + 1) % ring));
+    u.bias_copy = u.phi_copy + F->d;
+    if (rc == AA_OK) hip_ok(run_update(boss, u, ws, nblk, sb));
+    if (rc == AA_OK) hip_ok(hipEventRecord(ev_boss[slot], sb));
+  }
+  // every generator launch is waited for by a Boss tick, so the Boss stream ends the epoch
+  (void)hipEventDestroy(ev_start);
+  for (int i = 0; i < made; ++i) {
+    (void)hipEventDestroy(ev_boss[i]);
+    (void)hipEventDestroy(ev_gen[i]);
+  }
+  return rc;
 }
 
 }  // extern "C"

@@ -414,6 +414,10 @@ __global__ __launch_bounds__(256) void k_finalize(const FinalizeArgs a) {
   float lr = a.lr;
   if (a.t_upd && m > 0) lr = a.lr / sqrtf((float)t_new);
 
+  float p_new[4] = {p_old[0], p_old[1], p_old[2], p_old[3]};
+  float b_new = 0.f;
+  const bool bias_thread = blockIdx.x == 0 && tid == 0 && a.phi && a.bias;
+  if (bias_thread) b_new = *a.bias;
   if (m > 0) {
     const float inv_m = 1.f / (float)m;
     if (pg == 0) {
@@ -432,16 +436,25 @@ __global__ __launch_bounds__(256) void k_finalize(const FinalizeArgs a) {
         const float gv[4] = {gp.x, gp.y, gp.z, gp.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-          if (k0 + i < a.d)
-            a.phi[k0 + i] = p_old[i] - a.lr_a * __fmaf_rn(a.l2_a, p_old[i], gv[i] * inv_m);
+          if (k0 + i < a.d) {
+            p_new[i] = p_old[i] - a.lr_a * __fmaf_rn(a.l2_a, p_old[i], gv[i] * inv_m);
+            a.phi[k0 + i] = p_new[i];
+          }
       }
     }
-    if (blockIdx.x == 0 && tid == 0 && a.phi && a.bias) {
+    if (bias_thread) {
       // bias gradient: per-wave sums of the block partials, added in wave order
       const float gb = (s_flt[0] + s_flt[1]) + (s_flt[2] + s_flt[3]);
-      *a.bias = *a.bias - a.lr_a * (gb * inv_m);
+      b_new = b_new - a.lr_a * (gb * inv_m);
+      *a.bias = b_new;
     }
   }
+  if (a.phi_copy && a.phi && pg == 0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (k0 + i < a.d) a.phi_copy[k0 + i] = p_new[i];
+  }
+  if (a.bias_copy && bias_thread) *a.bias_copy = b_new;
   if (blockIdx.x == 0 && tid == 0 && a.kept_hist) *a.kept_hist = m;
 
   if (blockIdx.x == 0 && tid == 0 && a.t_upd) *a.t_upd = t_new;

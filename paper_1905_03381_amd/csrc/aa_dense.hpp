@@ -49,6 +49,8 @@ struct FinalizeArgs {
   float *w;                // updated if non-NULL (vector 0)
   float *phi;              // updated if non-NULL (next vector)
   float *bias;
+  float *phi_copy;         // optional: the Assistant after this update is also stored here
+  float *bias_copy;        //   (even when m == 0 and nothing changed)
   float lambda, lr, lr_a, l2_a;
   int32_t *t_upd;          // optional device update counter driving lr/sqrt(t)
   const int32_t *t_snap;   // its value before this step (written by the pass kernel)

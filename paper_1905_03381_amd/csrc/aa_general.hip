@@ -201,18 +201,30 @@ __global__ __launch_bounds__(256) void k_apply_general(const ApplyArgs a) {
   }
   int m = a.m_dev ? min(max(*a.m_dev, 0), a.m_max) : *a.acc_cnt;
   if (blockIdx.x == 0 && threadIdx.x == 0 && a.kept_hist) *a.kept_hist = m;
-  if (m <= 0) return;
+  if (m <= 0) {  // nothing kept: the model stays, its copy is still due
+    if (a.phi && a.phi_copy)
+      for (int k = blockIdx.x * blockDim.x + threadIdx.x; k < a.d; k += nb * blockDim.x)
+        a.phi_copy[k] = a.phi[k];
+    if (blockIdx.x == 0 && threadIdx.x == 0 && a.phi && a.bias && a.bias_copy)
+      *a.bias_copy = *a.bias;
+    return;
+  }
   const float inv_m = 1.f / (float)m;
   const float shrink = 1.f - a.lr * a.lambda, scale = a.lr * inv_m;
   for (int k = blockIdx.x * blockDim.x + threadIdx.x; k < a.d; k += nb * blockDim.x) {
     if (a.w) a.w[k] = __fmaf_rn(scale, a.acc_w[k], shrink * a.w[k]);
     if (a.phi) {
       const float ph = a.phi[k];
-      a.phi[k] = ph - a.lr_a * __fmaf_rn(a.l2_a, ph, a.acc_p[k] * inv_m);
+      const float pn = ph - a.lr_a * __fmaf_rn(a.l2_a, ph, a.acc_p[k] * inv_m);
+      a.phi[k] = pn;
+      if (a.phi_copy) a.phi_copy[k] = pn;
     }
   }
-  if (blockIdx.x == 0 && threadIdx.x == 0 && a.phi && a.bias)
-    *a.bias = *a.bias - a.lr_a * (*a.acc_gb * inv_m);
+  if (blockIdx.x == 0 && threadIdx.x == 0 && a.phi && a.bias) {
+    const float bn = *a.bias - a.lr_a * (*a.acc_gb * inv_m);
+    *a.bias = bn;
+    if (a.bias_copy) *a.bias_copy = bn;
+  }
 }
 
 template <int GL, bool CSR>

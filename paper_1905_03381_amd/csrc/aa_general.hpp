@@ -48,6 +48,8 @@ struct ApplyArgs {
   float *w;
   float *phi;
   float *bias;
+  float *phi_copy;   // optional second destination of the updated Assistant (written even if m == 0)
+  float *bias_copy;
   float lambda, lr, lr_a, l2_a;
   int32_t *kept_hist;
   const uint8_t *flags;

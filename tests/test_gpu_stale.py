@@ -1,0 +1,132 @@
+"""GPU parity of the two-stream Boss / Assistant pipeline with a fixed staleness against the
+oracle's schedule: every tick's batch bit for bit, the final model within tolerance."""
+import numpy as np
+import pytest
+import torch
+
+from paper_1905_03381_amd import api, synth
+
+from gpu_util import clear_draws, csr_features, dense_features, dev, host, scalar_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+def _run_gpu(F, y, perm, n, P, d, k, gamma, seed, step0, lam, lr0, T, lr_a, w0, phi0, b0, schedule):
+    ws = api.Workspace(P, d, staleness=k)
+    w, phi, b = dev(w0), dev(phi0), scalar_dev(b0)
+    Tt = scalar_dev(T)
+    cfg = api.step_config(gamma, lam, lr0, lr_a, 0.0, seed, step0, Tt)
+    steps = (n + P - 1) // P
+    tu = torch.zeros(1, dtype=torch.int32, device="cuda") if schedule else None
+    hist = torch.full((steps,), -1, dtype=torch.int32, device="cuda")
+    ids = torch.full((steps, P), -1, dtype=torch.int32, device="cuda")
+    gen = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    api.train_epoch_stale(F, dev(y), dev(perm), n, P, k, w, phi, b, cfg, tu, hist, ids, ws, gen)
+    torch.cuda.synchronize()
+    return host(w), host(phi), float(host(b)[0]), host(hist), host(ids), (None if tu is None else int(host(tu)[0]))
+
+
+def _compare(ref, got, want, P, gamma, seed, step0, rtol=2e-4, atol=2e-6):
+    w, phi, b, hist, ids, tu = got
+    for s, prob in enumerate(want["prob"]):
+        assert clear_draws(ref, prob, gamma, seed, step0 + s).all(), "choose another Philox key"
+    assert hist.tolist() == want["m"]
+    for s, m in enumerate(want["m"]):
+        assert np.array_equal(ids[s, :m], want["kept_ids"][s]), f"batch {s}"
+        assert np.all(ids[s, m:] == -1)
+    if tu is not None:
+        assert tu == want["t_upd"]
+    assert np.allclose(w, want["w"], rtol=rtol, atol=atol)
+    assert np.allclose(phi, want["phi"], rtol=rtol, atol=atol)
+    assert abs(b - want["bias"]) < 1e-5
+
+
+@pytest.mark.parametrize("k", [0, 1, 3])
+def test_tiny_config_epoch(ref, k):
+    X, y, _ = synth.tiny_svm()
+    n, d = X.shape
+    P, lam, gamma, lr_a, T, lr0, step0 = 256, 1e-4, 0.1, 0.1, 0.0, 0.01, 100
+    perm = synth.epoch_permutation(n, seed=7, epoch=0)
+    Fh = ref.Features.dense(X)
+    z = np.zeros(d, np.float32)
+    for seed in range(42, 52):
+        want = ref.train_stale(Fh, y, perm, P, z, z, 0.0, gamma, seed, step0, lam, lr0, T, lr_a, k)
+        if all(clear_draws(ref, p, gamma, seed, step0 + s).all() for s, p in enumerate(want["prob"])):
+            break
+    got = _run_gpu(dense_features(X), y, perm, n, P, d, k, gamma, seed, step0, lam, lr0, T, lr_a, z, z,
+                   0.0, True)
+    _compare(ref, got, want, P, gamma, seed, step0)
+
+
+def test_staleness_changes_the_batches(ref):
+    """On a problem where the Assistant moves quickly the stale and the synchronous schedules
+    draw different batches; the GPU follows the oracle in both."""
+    n, d, P = 6000, 1024, 1000
+    r = rng(3)
+    X = r.standard_normal((n, d)).astype(np.float32)
+    X /= np.linalg.norm(X, axis=1, keepdims=True)
+    y = np.where(X @ r.standard_normal(d) > 0, 1.0, -1.0).astype(np.float32)
+    perm = r.permutation(n).astype(np.int32)
+    Fh, F = ref.Features.dense(X), dense_features(X)
+    w0 = np.zeros(d, np.float32)
+    phi0 = (0.5 * r.standard_normal(d)).astype(np.float32)
+    gamma, lam, lr0, T, lr_a, step0 = 0.05, 1e-4, 1.0, 0.9, 4.0, 0
+    outs = {}
+    for k in (0, 2):
+        for seed in range(11, 31):
+            want = ref.train_stale(Fh, y, perm, P, w0, phi0, 0.2, gamma, seed, step0, lam, lr0, T, lr_a, k)
+            if all(clear_draws(ref, p, gamma, seed, step0 + s).all() for s, p in enumerate(want["prob"])):
+                break
+        got = _run_gpu(F, y, perm, n, P, d, k, gamma, seed, step0, lam, lr0, T, lr_a, w0, phi0, 0.2, True)
+        _compare(ref, got, want, P, gamma, seed, step0)
+        outs[k] = (seed, want)
+    if outs[0][0] == outs[2][0]:
+        assert any(not np.array_equal(a, b) for a, b in zip(outs[0][1]["kept_ids"], outs[2][1]["kept_ids"]))
+
+
+def test_sparse_rows_constant_step(ref):
+    rowptr, col, val, y, _ = synth.sparse_svm(n=12_000, d=1 << 14, mean_nnz=60, threads=4)
+    n, d, P, k = rowptr.size - 1, 1 << 14, 3000, 1
+    perm = synth.epoch_permutation(n, seed=7, epoch=0)
+    Fh = ref.Features.csr(rowptr, col, val, d)
+    z = np.zeros(d, np.float32)
+    gamma, lam, lr0, T, lr_a, step0 = 0.1, 1e-4, 0.5, 0.0, 0.5, 5
+    for seed in range(42, 62):
+        want = ref.train_stale(Fh, y, perm, P, z, z, 0.0, gamma, seed, step0, lam, lr0, T, lr_a, k,
+                               schedule=False)
+        if all(clear_draws(ref, p, gamma, seed, step0 + s).all() for s, p in enumerate(want["prob"])):
+            break
+    got = _run_gpu(csr_features(rowptr, col, val, d), y, perm, n, P, d, k, gamma, seed, step0, lam, lr0,
+                   T, lr_a, z, z, 0.0, False)
+    _compare(ref, got, want, P, gamma, seed, step0, rtol=5e-4, atol=5e-6)
+
+
+def test_runs_are_bit_identical_and_arguments_are_checked():
+    n, d, P, k = 5000, 1024, 1000, 2
+    r = rng(4)
+    X = r.standard_normal((n, d)).astype(np.float32)
+    y = np.where(r.random(n) < 0.5, 1.0, -1.0).astype(np.float32)
+    perm = r.permutation(n).astype(np.int32)
+    F = dense_features(X)
+    z = np.zeros(d, np.float32)
+    a = _run_gpu(F, y, perm, n, P, d, k, 0.1, 1, 0, 1e-4, 0.5, 0.0, 0.1, z, z, 0.0, True)
+    b = _run_gpu(F, y, perm, n, P, d, k, 0.1, 1, 0, 1e-4, 0.5, 0.0, 0.1, z, z, 0.0, True)
+    for u, v in zip(a[:5], b[:5]):
+        assert np.array_equal(u, v)
+    ws = api.Workspace(P, d, staleness=k)
+    w, phi, bb = dev(z), dev(z), scalar_dev(0.0)
+    cfg = api.step_config(0.1, 1e-4, 0.5, 0.1, 0.0, 1, 0, scalar_dev(0.0))
+    cur = torch.cuda.current_stream()
+    with pytest.raises(api.AAError):      # the generator needs its own stream
+        api.train_epoch_stale(F, dev(y), dev(perm), n, P, k, w, phi, bb, cfg, None, None, None, ws, cur)
+    with pytest.raises(api.AAError):      # workspace sized for a smaller staleness
+        api.train_epoch_stale(F, dev(y), dev(perm), n, P, 9, w, phi, bb, cfg, None, None, None, ws,
+                              torch.cuda.Stream())
+    with pytest.raises(api.AAError):
+        api.train_epoch_stale(F, dev(y), dev(perm), n, P, 16, w, phi, bb, cfg, None, None, None, ws,
+                              torch.cuda.Stream())
