@@ -2,12 +2,16 @@
 // cannot take (d > 2048, d % 4 != 0, unaligned).  A group of GL lanes walks the
 // stored entries of a row; phi and w are read through the caches (they are the
 // only reused data); gradient sums go into dense fp32 accumulators that a second
-// kernel folds into the model.  Columns below kHead* are first summed in LDS, one
-// private copy per block, and flushed with one atomic per touched column: with
-// frequency-ranked columns (the usual layout of bag-of-words data) a few hot columns
-// take most of the entries, and device-wide atomics on one address run one after
-// the other, about 13 ns each on MI355X.  The remaining columns take fp32 atomics
-// in HBM directly, which the chip sustains at about 20 G/s on scattered addresses.
+// kernel folds into the model.  Every block first sums what it can in an LDS table
+// of its own -- the first columns have a slot each (frequency-ranked column ids,
+// the usual layout of bag-of-words data, put the hot columns there), any other
+// column claims a slot by hash, first come first served -- and flushes one atomic
+// per used slot at the end.
+// In bag-of-words data a few hot columns take most of the entries, and device-wide
+// atomics on one address run one after the other, about 13 ns each on MI355X: the
+// table turns the thousands of adds a block would send to a hot column into one.
+// Columns that find their slots taken add to HBM directly, which the chip
+// sustains at about 20 G atomics/s on scattered addresses.
 #include "aa_compact.hpp"
 #include "aa_general.hpp"
 
@@ -22,13 +26,15 @@ __device__ __forceinline__ float gsum(float v) {
   return v;
 }
 
-// LDS head of the gradient accumulators: 64 KB per block, split between the two
-// vectors when both are updated in one pass.
-constexpr int kHeadBytes = 64 * 1024;
-constexpr int kGradThreads = 512, kPoolThreads = 256;
+// Per-block LDS table: kDirect* slots for columns 0..kDirect*-1, then kHashed* slots
+// claimed by hash (a column tag each); one sum per slot and updated vector.
+// 80 KB with both vectors, 96 KB with one: one block of 16 waves per compute unit.
+constexpr int kDirectTwoVec = 4096, kHashedTwoVec = 4096;
+constexpr int kDirectOneVec = 8192, kHashedOneVec = 8192;
+constexpr int kGradThreads = 1024, kPoolThreads = 256;
 
 template <int GL, int MODE, bool CSR>
-__global__ __launch_bounds__(512) void k_rows_general(const GenArgs a) {
+__global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
   constexpr bool POOL = (MODE & kPool) != 0;
   constexpr bool SVM = (MODE & kSvm) != 0;
   constexpr bool ASSIST = (MODE & kAssist) != 0;
@@ -36,11 +42,16 @@ __global__ __launch_bounds__(512) void k_rows_general(const GenArgs a) {
   constexpr bool GRAD = SVM || ASSIST;
   constexpr bool NEED_PHI = (POOL && !HARD) || ASSIST;
   constexpr int G = kWave / GL;
-  constexpr int HEAD = GRAD ? kHeadBytes / 4 / ((SVM ? 1 : 0) + (ASSIST ? 1 : 0)) : 0;
-  __shared__ float s_head[GRAD ? kHeadBytes / 4 : 1];
-  float *const s_w = s_head, *const s_p = s_head + (SVM ? HEAD : 0);
+  constexpr int NVEC = (SVM ? 1 : 0) + (ASSIST ? 1 : 0);
+  constexpr int D = NVEC == 2 ? kDirectTwoVec : kDirectOneVec;  // slots 0..D-1: column = slot
+  constexpr int H = NVEC == 2 ? kHashedTwoVec : kHashedOneVec;  // slots D..D+H-1: by hash
+  __shared__ int s_tag[GRAD ? H : 1];
+  __shared__ float s_sum[GRAD ? NVEC * (D + H) : 1];
+  float *const s_w = s_sum, *const s_p = s_sum + (SVM ? D + H : 0);
+  const int salt = (int)((blockIdx.x * 0x9E3779B1u) >> 19) & (H - 1);
   if (GRAD) {
-    for (int k = threadIdx.x; k < kHeadBytes / 4; k += blockDim.x) s_head[k] = 0.f;
+    for (int k = threadIdx.x; k < H; k += blockDim.x) s_tag[k] = -1;
+    for (int k = threadIdx.x; k < NVEC * (D + H); k += blockDim.x) s_sum[k] = 0.f;
     __syncthreads();
   }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
@@ -135,9 +146,23 @@ __global__ __launch_bounds__(512) void k_rows_general(const GenArgs a) {
           for (int e = sub; e < len; e += GL) {
             const int c = CSR ? a.col[e0 + e] : e;
             const float xv = CSR ? (a.val ? a.val[e0 + e] : 1.f) : a.x[e0 + e];
-            if (c < HEAD) {  // LDS and HBM atomics are different instructions: branch, not select
-              if (SVM && cw != 0.f) unsafeAtomicAdd(s_w + c, cw * xv);
-              if (ASSIST && resid != 0.f) unsafeAtomicAdd(s_p + c, resid * xv);
+            int slot = -1;
+            if (c < D) {
+              slot = c;
+            } else {  // claim a slot for this column, or find the one it already holds
+              int h = (c ^ (c >> 13) ^ salt) & (H - 1);
+              int old = atomicCAS(s_tag + h, -1, c);
+              if (old == -1 || old == c) {
+                slot = D + h;
+              } else {
+                h = (h + 1) & (H - 1);
+                old = atomicCAS(s_tag + h, -1, c);
+                if (old == -1 || old == c) slot = D + h;
+              }
+            }
+            if (slot >= 0) {  // LDS and HBM atomics are different instructions: branch, not select
+              if (SVM && cw != 0.f) unsafeAtomicAdd(s_w + slot, cw * xv);
+              if (ASSIST && resid != 0.f) unsafeAtomicAdd(s_p + slot, resid * xv);
             } else {
               if (SVM && cw != 0.f) unsafeAtomicAdd(a.acc_w + c, cw * xv);
               if (ASSIST && resid != 0.f) unsafeAtomicAdd(a.acc_p + c, resid * xv);
@@ -150,15 +175,16 @@ __global__ __launch_bounds__(512) void k_rows_general(const GenArgs a) {
 
   if (GRAD) {
     __syncthreads();
-    const int head = min(HEAD, a.d);
-    for (int k = threadIdx.x; k < head; k += blockDim.x) {
+    for (int k = threadIdx.x; k < D + H; k += blockDim.x) {
+      const int c = k < D ? (k < a.d ? k : -1) : s_tag[k - D];
+      if (c < 0) continue;
       if (SVM) {
         const float v = s_w[k];
-        if (v != 0.f) unsafeAtomicAdd(a.acc_w + k, v);
+        if (v != 0.f) unsafeAtomicAdd(a.acc_w + c, v);
       }
       if (ASSIST) {
         const float v = s_p[k];
-        if (v != 0.f) unsafeAtomicAdd(a.acc_p + k, v);
+        if (v != 0.f) unsafeAtomicAdd(a.acc_p + c, v);
       }
     }
     // scalars[0] = kept count (int), scalars[1] = bias gradient (float bits via atomics)
@@ -258,12 +284,12 @@ hipError_t launch_gl(const GenArgs &a, int mode, int nblk, hipStream_t st) {
 }  // namespace
 
 int32_t general_pass_blocks(int32_t count, bool csr, int mode) {
-  // Gradient passes flush a private LDS head per block, so they take few, fat blocks (two
-  // fit a compute unit); the scoring pass has no such cost and takes many thin ones.
+  // Gradient passes flush a private LDS table per block, so they take few, fat blocks (one
+  // per compute unit); the scoring pass has no such cost and takes many thin ones.
   const bool grad = (mode & (kSvm | kAssist)) != 0;
   const int waves = (grad ? kGradThreads : kPoolThreads) / kWave;
   const int rows_per_block = waves * (csr ? 4 : 1);
-  const int cap = grad ? 256 * 2 : 256 * 8;
+  const int cap = grad ? 256 : 256 * 8;
   int64_t want = ((int64_t)count + rows_per_block - 1) / rows_per_block;
   if (want > cap) want = cap;
   if (want < 1) want = 1;
