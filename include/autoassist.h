@@ -144,7 +144,8 @@ int32_t aa_gather(const void *src, int64_t row_bytes, const int32_t *idx,
 /* CSR batch assembly: out_rowptr[0..m], out_col/out_val hold the kept rows in
  * order.  Rows that would not fit in out_nnz_cap entries are not copied, but
  * out_rowptr is always complete: the caller checks out_rowptr[m] <= cap.
- * out_val may be NULL iff F->val is NULL. */
+ * out_val may be NULL iff F->val is NULL.  ws (sized for P_max >= max_rows) is
+ * needed when max_rows > 1024: AA_ERR_WORKSPACE otherwise. */
 int32_t aa_gather_csr(const aa_features *F, const int32_t *idx, const int32_t *kept_pos,
                       const int32_t *kept_count, int32_t max_rows, int64_t *out_rowptr,
                       int32_t *out_col, float *out_val, int64_t out_nnz_cap, void *ws,

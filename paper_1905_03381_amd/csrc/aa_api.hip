@@ -584,8 +584,6 @@ int32_t aa_gather_csr(const aa_features *F, const int32_t *idx, const int32_t *k
                       const int32_t *kept_count, int32_t max_rows, int64_t *out_rowptr,
                       int32_t *out_col, float *out_val, int64_t out_nnz_cap, void *ws_ptr,
                       size_t ws_bytes, void *stream) {
-  (void)ws_ptr;
-  (void)ws_bytes;
   if (max_rows < 0 || out_nnz_cap < 0) return AA_ERR_SHAPE;
   if (int32_t rc = check_features(F)) return rc;
   if (F->layout != AA_CSR) return AA_ERR_SHAPE;
@@ -604,7 +602,14 @@ int32_t aa_gather_csr(const aa_features *F, const int32_t *idx, const int32_t *k
   g.out_col = out_col;
   g.out_val = out_val;
   g.out_nnz_cap = out_nnz_cap;
-  return hip_status(launch_gather_csr(g, as_stream(stream)));
+  // many rows: the row-pointer scan runs tile by tile and keeps its tile offsets in the workspace
+  long long *tiles = nullptr;
+  if (max_rows > 1024) {
+    Ws ws = carve(ws_ptr, 0, max_rows);
+    if (int32_t rc = check_ws(ws_ptr, ws_bytes, ws.total)) return rc;
+    tiles = reinterpret_cast<long long *>(ws.bucket_tiles);
+  }
+  return hip_status(launch_gather_csr(g, tiles, as_stream(stream)));
 }
 
 int32_t aa_svm_sgd_step(const aa_features *F, const float *y, const int32_t *rows,

@@ -101,11 +101,24 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
       const float yy = __shfl(y_l, li, kWave);
       const float lin = __shfl(lin_l, li, kWave);
       float dp = 0.f, dw = 0.f;
-      for (int e = sub; e < len; e += GL) {
-        const int c = CSR ? a.col[e0 + e] : e;
-        const float xv = CSR ? (a.val ? a.val[e0 + e] : 1.f) : a.x[e0 + e];
-        if (NEED_PHI) dp = __fmaf_rn(a.phi[c], xv, dp);
-        if (SVM) dw = __fmaf_rn(a.w[c], xv, dw);
+      // kUnroll entries per lane at a time: their column and value loads leave together, then
+      // the model gathers that depend on the columns (the chain that bounds this loop)
+      constexpr int kUnroll = 8;
+      for (int e = sub; e < len; e += GL * kUnroll) {
+        int c[kUnroll];
+        float xv[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+          const int eu = e + u * GL;
+          const bool in = eu < len;
+          c[u] = CSR ? (in ? a.col[e0 + eu] : 0) : (in ? eu : 0);
+          xv[u] = in ? (CSR ? (a.val ? a.val[e0 + eu] : 1.f) : a.x[e0 + eu]) : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+          if (NEED_PHI) dp = __fmaf_rn(a.phi[c[u]], xv[u], dp);
+          if (SVM) dw = __fmaf_rn(a.w[c[u]], xv[u], dw);
+        }
       }
       float g = 0.f;
       bool keep = live;

@@ -151,6 +151,64 @@ __global__ __launch_bounds__(1024) void k_csr_rowptr(const GatherCsrArgs a) {
   }
 }
 
+// Row pointers of many kept rows in three launches: entry count of every tile of 1024 rows,
+// exclusive scan of the tile counts (one block), then the scan inside each tile.
+constexpr int kCsrTile = 1024;
+
+__device__ __forceinline__ int kept_row_len(const GatherCsrArgs &a, int r, int m) {
+  if (r >= m) return 0;
+  const int pos = a.kept_pos ? a.kept_pos[r] : r;
+  const long long id = a.idx ? a.idx[pos] : pos;
+  return (int)(a.rowptr[id + 1] - a.rowptr[id]);
+}
+
+__global__ __launch_bounds__(kCsrTile) void k_csr_tile_sums(const GatherCsrArgs a,
+                                                            long long *tile_sum) {
+  __shared__ int s_int[40];
+  const int m = min(max(*a.kept_count, 0), a.max_rows);
+  int total;
+  (void)block_exclusive_scan(kept_row_len(a, blockIdx.x * kCsrTile + threadIdx.x, m), s_int, &total);
+  if (threadIdx.x == 0) tile_sum[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(1024) void k_csr_scan_tiles(long long *tile_sum, int ntiles) {
+  __shared__ long long s_part[16];
+  long long running = 0;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int t0 = 0; t0 < ntiles; t0 += 1024) {
+    const int t = t0 + threadIdx.x;
+    const long long v = t < ntiles ? tile_sum[t] : 0;
+    long long incl = v;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+      const long long up = __shfl_up(incl, off, kWave);
+      if (lane >= off) incl += up;
+    }
+    if (lane == 63) s_part[wave] = incl;
+    __syncthreads();
+    long long base = 0, sum = 0;
+    for (int i = 0; i < 16; ++i) {
+      if (i < wave) base += s_part[i];
+      sum += s_part[i];
+    }
+    __syncthreads();
+    if (t < ntiles) tile_sum[t] = running + base + incl - v;
+    running += sum;
+  }
+}
+
+__global__ __launch_bounds__(kCsrTile) void k_csr_rowptr_tiles(const GatherCsrArgs a,
+                                                               const long long *tile_off) {
+  __shared__ int s_int[40];
+  const int m = min(max(*a.kept_count, 0), a.max_rows);
+  const int r = blockIdx.x * kCsrTile + threadIdx.x;
+  const int len = kept_row_len(a, r, m);
+  int total;
+  const int excl = block_exclusive_scan(len, s_int, &total);
+  if (r == 0) a.out_rowptr[0] = 0;
+  if (r < m) a.out_rowptr[r + 1] = tile_off[blockIdx.x] + excl + len;
+}
+
 // 16 lanes copy the entries of one kept row.
 __global__ __launch_bounds__(256) void k_csr_copy(const GatherCsrArgs a) {
   const int m = min(max(*a.kept_count, 0), a.max_rows);
@@ -235,8 +293,15 @@ hipError_t launch_gather(const GatherArgs &a, hipStream_t st) {
   return hipGetLastError();
 }
 
-hipError_t launch_gather_csr(const GatherCsrArgs &a, hipStream_t st) {
-  hipLaunchKernelGGL(k_csr_rowptr, dim3(1), dim3(1024), 0, st, a);
+hipError_t launch_gather_csr(const GatherCsrArgs &a, long long *tile_scratch, hipStream_t st) {
+  if (a.max_rows <= kCsrTile || !tile_scratch) {
+    hipLaunchKernelGGL(k_csr_rowptr, dim3(1), dim3(1024), 0, st, a);
+  } else {
+    const int ntiles = (a.max_rows + kCsrTile - 1) / kCsrTile;
+    hipLaunchKernelGGL(k_csr_tile_sums, dim3(ntiles), dim3(kCsrTile), 0, st, a, tile_scratch);
+    hipLaunchKernelGGL(k_csr_scan_tiles, dim3(1), dim3(1024), 0, st, tile_scratch, ntiles);
+    hipLaunchKernelGGL(k_csr_rowptr_tiles, dim3(ntiles), dim3(kCsrTile), 0, st, a, tile_scratch);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || a.max_rows <= 0) return e;
   int nb = (a.max_rows + 15) / 16;

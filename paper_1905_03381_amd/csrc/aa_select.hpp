@@ -49,6 +49,7 @@ hipError_t launch_keep_flags(const KeepArgs &a, int source, hipStream_t stream);
 // Compact c.flags (c.tile_off is set here).  tile_off_scratch: P/2048 + 1 ints of workspace.
 hipError_t launch_compact(CompactArgs c, int32_t *tile_off_scratch, hipStream_t stream);
 hipError_t launch_gather(const GatherArgs &a, hipStream_t stream);
-hipError_t launch_gather_csr(const GatherCsrArgs &a, hipStream_t stream);
+// tile_scratch: max_rows / 1024 + 1 64-bit words of workspace (NULL: one block scans all rows).
+hipError_t launch_gather_csr(const GatherCsrArgs &a, long long *tile_scratch, hipStream_t stream);
 
 }  // namespace aa
