@@ -241,12 +241,17 @@ int32_t aa_sk_step(const aa_features *F, const float *y, const int32_t *idx, int
  * updates made so far including this one; t_upd == NULL keeps lr constant.
  * kept_hist[t] (device, may be NULL) receives each step's kept count.  Each
  * step assembles its batch (keep probabilities, keep flags, kept positions,
- * kept ids, per-instance losses) inside ws, where the same step consumes it.
- * Needs the fast dense layout when t_upd is given. */
+ * kept ids, per-instance losses): the kept ids of step t go to
+ * kept_ids_hist[t*P ..] and their losses to loss_hist[t*P ..] (kept_hist[t]
+ * entries each; either may be NULL: the batch then lives in ws until the next
+ * step replaces it).  With the fast dense layout the compaction of step t is
+ * carried by the row pass of step t+1 (every output is complete when the
+ * call's work has drained).  Needs the fast dense layout when t_upd is given. */
 int32_t aa_train_epoch(const aa_features *F, const float *y, const int32_t *perm,
                        int64_t n_perm, int32_t P, float *w, float *phi, float *bias,
-                       const aa_step_config *cfg, int32_t *t_upd, int32_t *kept_hist, void *ws,
-                       size_t ws_bytes, void *stream);
+                       const aa_step_config *cfg, int32_t *t_upd, int32_t *kept_hist,
+                       int32_t *kept_ids_hist, float *loss_hist, void *ws, size_t ws_bytes,
+                       void *stream);
 
 /* ---- The asynchronous Boss / Assistant schedule of Section 5.3 in a deterministic
  * form, on two streams.  Pool s is perm[s*P : min((s+1)*P, n_perm)].  The

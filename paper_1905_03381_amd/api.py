@@ -73,7 +73,7 @@ def lib():
         "aa_boss_assistant_step": (i32, [FP, vp, vp, vp, i32, vp, vp, vp, CP, vp, vp, sz, vp]),
         "aa_fused_step": (i32, [FP, vp, vp, i32, vp, vp, vp, CP, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
         "aa_sk_step": (i32, [FP, vp, vp, i32, vp, vp, f32, f32, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
-        "aa_train_epoch": (i32, [FP, vp, vp, i64, i32, vp, vp, vp, CP, vp, vp, vp, sz, vp]),
+        "aa_train_epoch": (i32, [FP, vp, vp, i64, i32, vp, vp, vp, CP, vp, vp, vp, vp, vp, sz, vp]),
         "aa_threshold_update": (i32, [vp, vp, i32, f32, vp, vp, vp]),
         "aa_pipeline_workspace_bytes": (sz, [i32, i32, i32]),
         "aa_train_epoch_stale": (i32, [FP, vp, vp, i64, i32, i32, vp, vp, vp, CP, vp, vp, vp, vp, sz, vp, vp]),
@@ -232,10 +232,12 @@ def sk_step(F, y, idx, P, w, T, lam, lr, loss_pool, keep, kept_pos, kept_ids, lo
                             _ptr(kept_count), ws.ptr, ws.bytes, _stream()), "aa_sk_step")
 
 
-def train_epoch(F, y, perm, n_perm, P, w, phi, bias, cfg, t_upd, kept_hist, ws):
+def train_epoch(F, y, perm, n_perm, P, w, phi, bias, cfg, t_upd, kept_hist, ws, kept_ids_hist=None,
+                loss_hist=None):
     _check(lib().aa_train_epoch(F.ref(), _ptr(y), _ptr(perm), n_perm, P, _ptr(w), _ptr(phi),
-                                _ptr(bias), C.byref(cfg), _ptr(t_upd), _ptr(kept_hist), ws.ptr,
-                                ws.bytes, _stream()), "aa_train_epoch")
+                                _ptr(bias), C.byref(cfg), _ptr(t_upd), _ptr(kept_hist),
+                                _ptr(kept_ids_hist), _ptr(loss_hist), ws.ptr, ws.bytes, _stream()),
+           "aa_train_epoch")
 
 
 def train_epoch_stale(F, y, perm, n_perm, P, staleness, w, phi, bias, cfg, t_upd, kept_hist,

@@ -29,6 +29,8 @@ struct Ws {
   int32_t *kept_pos;  // [P]
   int32_t *kept_ids;  // [P]
   float *loss;        // [P]
+  uint8_t *flags_odd;    // [P]   second keep-flag / loss buffers of the epoch driver: a step's
+  float *loss_pool_odd;  // [P]   flags stay valid while the next step compacts them
   size_t total;
 };
 
@@ -56,7 +58,9 @@ Ws carve(void *ws, size_t grad_bytes, int32_t P, bool epoch_outputs = false) {
   w.kept_pos = reinterpret_cast<int32_t *>(w.base + off + per);
   w.kept_ids = reinterpret_cast<int32_t *>(w.base + off + 2 * per);
   w.loss = reinterpret_cast<float *>(w.base + off + 3 * per);
-  if (epoch_outputs) off += 4 * per;
+  w.flags_odd = reinterpret_cast<uint8_t *>(w.base + off + 4 * per);
+  w.loss_pool_odd = reinterpret_cast<float *>(w.base + off + 5 * per);
+  if (epoch_outputs) off += 6 * per;
   w.total = off;
   return w;
 }
@@ -126,6 +130,7 @@ struct PassSpec {
   float *loss_out;
   const float *loss_in;
   const int32_t *t_upd;
+  CompactArgs prev;  // compaction of the previous pool carried by this pass (fast dense pool pass only)
 };
 
 bool use_fast(const PassSpec &s) {
@@ -174,7 +179,11 @@ hipError_t run_pass(const PassSpec &s, const Ws &ws, int32_t *nblk_out, hipStrea
     a.blk_gb = ws.blk_gb;
     a.t_upd = s.t_upd;
     a.t_snap = ws.ctl + kCtlUpdateSnapshot;
+    a.prev = s.prev;
     const int32_t nblk = dense_pass_blocks(s.F->d, s.count_max, s.mode);
+    if (a.prev.flags && (a.prev.P > dense_carry_capacity(nblk) ||
+                         (reinterpret_cast<uintptr_t>(a.prev.flags) & 15) != 0))
+      return hipErrorInvalidValue;  // the caller plans carried compactions within capacity
     *nblk_out = nblk;
     HookScope hook(st);
     return launch_dense_pass(a, s.mode, s.F->d, nblk, st);
@@ -329,18 +338,32 @@ __global__ void k_zero_i32(int32_t *p, int n) {
   for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = 0;
 }
 
+// Epoch driver state handed to a step: where its batch goes, which of the two flag buffers
+// it uses, the compaction it carries for the step before, and whether its own compaction
+// may be left to the next step's pass.
+struct EpochCtl {
+  int32_t P_layout;          // pool size the workspace is laid out for (the epoch's P)
+  int parity;
+  int32_t *ids_dst;
+  float *loss_dst;
+  const CompactArgs *carry;  // NULL: nothing to carry
+  bool may_defer;
+  CompactArgs *deferred;     // out: filled when this step's compaction was left to the next pass
+  bool did_defer;
+};
+
 int32_t fused_step_impl(const aa_features *F, const float *y, const int32_t *idx, int32_t P,
                         float *w, float *phi, float *bias, const aa_step_config *cfg,
                         uint64_t step, float *logit, float *prob, uint8_t *keep,
                         int32_t *kept_pos, int32_t *kept_ids, float *loss, int32_t *kept_count,
-                        int32_t *t_upd, int32_t *kept_hist, bool epoch_outputs, void *ws_ptr,
+                        int32_t *t_upd, int32_t *kept_hist, EpochCtl *ep, void *ws_ptr,
                         size_t ws_bytes, hipStream_t st) {
   PassSpec s{};
   s.F = F;
   s.mode = kPool | kSvm | kAssist;
   s.y = y;
   s.rows = idx;
-  s.count_max = P;
+  s.count_max = ep ? ep->P_layout : P;  // sizes the gradient partials for the whole epoch
   s.w = w;
   s.phi = phi;
   s.bias = bias;
@@ -352,18 +375,27 @@ int32_t fused_step_impl(const aa_features *F, const float *y, const int32_t *idx
   s.logit = logit;
   s.prob = prob;
   s.t_upd = t_upd;
-  if (t_upd && !use_fast(s)) return AA_ERR_SHAPE;  // device-side step-size schedule: fast dense only
+  const bool fast = use_fast(s);
+  if (t_upd && !fast) return AA_ERR_SHAPE;  // device-side step-size schedule: fast dense only
   const size_t gbytes = grad_bytes_for(s);
-  Ws ws = carve(ws_ptr, gbytes, P, epoch_outputs);
+  Ws ws = carve(ws_ptr, gbytes, s.count_max, ep != nullptr);
   if (int32_t rc = check_ws(ws_ptr, ws_bytes, ws.total)) return rc;
-  if (epoch_outputs) {  // the batch of each step is assembled in the workspace
+  s.count_max = P;
+  float *loss_pool = ws.loss_pool;
+  s.flags = keep ? keep : ws.flags;
+  if (ep) {  // the batch of each step is assembled in the workspace (or the caller's history)
     s.prob = ws.prob;
     kept_pos = ws.kept_pos;
-    kept_ids = ws.kept_ids;
-    loss = ws.loss;
+    kept_ids = ep->ids_dst ? ep->ids_dst : ws.kept_ids;
+    loss = ep->loss_dst ? ep->loss_dst : ws.loss;
+    if (ep->parity & 1) {
+      s.flags = ws.flags_odd;
+      loss_pool = ws.loss_pool_odd;
+    }
+    if (ep->carry && fast) s.prev = *ep->carry;
+    ep->did_defer = false;
   }
-  s.flags = keep ? keep : ws.flags;
-  s.loss_out = ws.loss_pool;
+  s.loss_out = loss_pool;
   int32_t nblk = 0;
   hipError_t e = run_pass(s, ws, &nblk, st);
   if (e != hipSuccess) return AA_ERR_HIP;
@@ -375,14 +407,28 @@ int32_t fused_step_impl(const aa_features *F, const float *y, const int32_t *idx
   u.t_upd = t_upd;
   u.kept_hist = kept_hist;
   if (kept_pos || kept_ids || loss || kept_count) {
-    u.flags = s.flags;
-    u.P = P;
-    u.idx = idx;
-    u.kept_pos = kept_pos;
-    u.kept_ids = kept_ids;
-    u.loss_pool = ws.loss_pool;
-    u.loss = loss;
-    u.kept_count = kept_count;
+    CompactArgs c{};
+    c.flags = s.flags;
+    c.P = P;
+    c.idx = idx;
+    c.kept_pos = kept_pos;
+    c.kept_ids = kept_ids;
+    c.loss_pool = loss_pool;
+    c.loss = loss;
+    c.kept_count = kept_count;
+    if (ep && ep->may_defer && fast) {  // the next step's pass compacts this pool
+      *ep->deferred = c;
+      ep->did_defer = true;
+    } else {
+      u.flags = c.flags;
+      u.P = c.P;
+      u.idx = c.idx;
+      u.kept_pos = c.kept_pos;
+      u.kept_ids = c.kept_ids;
+      u.loss_pool = c.loss_pool;
+      u.loss = c.loss;
+      u.kept_count = c.kept_count;
+    }
   }
   return hip_status(run_update(s, u, ws, nblk, st));
 }
@@ -720,7 +766,7 @@ int32_t aa_fused_step(const aa_features *F, const float *y, const int32_t *idx, 
   if (int32_t rc = check_features(F)) return rc;
   if (!y || !w || !phi || !cfg || !cfg->T) return AA_ERR_NULL;
   return fused_step_impl(F, y, idx, P, w, phi, bias, cfg, cfg->step, logit, prob, keep, kept_pos,
-                         kept_ids, loss, kept_count, nullptr, nullptr, false, ws, ws_bytes,
+                         kept_ids, loss, kept_count, nullptr, nullptr, nullptr, ws, ws_bytes,
                          as_stream(stream));
 }
 
@@ -804,21 +850,41 @@ int32_t aa_bucket_batches(const int32_t *len_s, const int32_t *len_t, const int3
 
 int32_t aa_train_epoch(const aa_features *F, const float *y, const int32_t *perm, int64_t n_perm,
                        int32_t P, float *w, float *phi, float *bias, const aa_step_config *cfg,
-                       int32_t *t_upd, int32_t *kept_hist, void *ws, size_t ws_bytes,
-                       void *stream) {
+                       int32_t *t_upd, int32_t *kept_hist, int32_t *kept_ids_hist,
+                       float *loss_hist, void *ws, size_t ws_bytes, void *stream) {
   if (P <= 0 || n_perm < 0) return AA_ERR_SHAPE;
   if (n_perm == 0) return AA_OK;
   if (int32_t rc = check_features(F)) return rc;
   if (!y || !w || !phi || !cfg || !cfg->T || !perm) return AA_ERR_NULL;
   const int64_t steps = (n_perm + P - 1) / P;
+  const int mode = kPool | kSvm | kAssist;
+  CompactArgs pending{};
+  bool have_pending = false;
   for (int64_t t = 0; t < steps; ++t) {
     const int64_t lo = t * P;
     const int32_t Pt = (int32_t)((n_perm - lo) < P ? (n_perm - lo) : P);
+    EpochCtl ep{};
+    ep.P_layout = P;
+    ep.parity = (int)(t & 1);
+    ep.ids_dst = kept_ids_hist ? kept_ids_hist + t * (int64_t)P : nullptr;
+    ep.loss_dst = loss_hist ? loss_hist + t * (int64_t)P : nullptr;
+    ep.carry = have_pending ? &pending : nullptr;
+    CompactArgs mine{};
+    ep.deferred = &mine;
+    // This pool's compaction rides on the next step's pass when that pass has a block for
+    // every 64 positions of this pool; the last step compacts in its own update kernel.
+    if (t + 1 < steps) {
+      const int64_t left = n_perm - (lo + P);
+      const int32_t P_next = (int32_t)(left < P ? left : P);
+      ep.may_defer = Pt <= dense_carry_capacity(dense_pass_blocks(F->d, P_next, mode));
+    }
     const int32_t rc = fused_step_impl(F, y, perm + lo, Pt, w, phi, bias, cfg, cfg->step + t,
                                        nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
-                                       nullptr, t_upd, kept_hist ? kept_hist + t : nullptr, true,
-                                       ws, ws_bytes, as_stream(stream));
+                                       nullptr, t_upd, kept_hist ? kept_hist + t : nullptr, &ep, ws,
+                                       ws_bytes, as_stream(stream));
     if (rc != AA_OK) return rc;
+    have_pending = ep.did_defer;
+    pending = mine;
   }
   return AA_OK;
 }

@@ -117,6 +117,7 @@ __global__ __launch_bounds__(NW * 64)
 
   __shared__ int s_int[20];
   __shared__ float s_flt[20];
+  __shared__ int s_carry[NW];
   __shared__ f4 s_w[SVM ? ROW4 : 1];
   __shared__ f4 s_phi[NEED_PHI ? ROW4 : 1];
   __shared__ f4 s_red[GRAD ? NW * NVEC * ROW4 : 1];  // one slot per wave and vector
@@ -192,6 +193,26 @@ __global__ __launch_bounds__(NW * 64)
     issue_rows(0);
     lane_inputs();
   }
+  // Carried compaction of the previous pool: its loads leave behind the first rows, the
+  // count of the flags before this block's 64 positions rides on the start-up barrier,
+  // and the last wave places the survivors while the rows are still arriving.
+  const bool carry = POOL && GRAD && a.prev.flags != nullptr && (int)blockIdx.x * kWave < a.prev.P;
+  int carry_cnt = 0, carry_id = 0;
+  uint8_t carry_flag = 0;
+  float carry_loss = 0.f;
+  if (POOL && GRAD && carry) {
+    const int j0 = blockIdx.x * kWave;
+    const uint4 *p16 = reinterpret_cast<const uint4 *>(a.prev.flags);
+    for (int q = threadIdx.x; q < (j0 >> 4); q += NT) {
+      const uint4 v = p16[q];
+      carry_cnt += __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w);  // bytes are 0 or 1
+    }
+    if (wave == NW - 1 && j0 + lane < a.prev.P) {
+      carry_flag = a.prev.flags[j0 + lane];
+      carry_id = a.prev.idx ? a.prev.idx[j0 + lane] : j0 + lane;
+      if (a.prev.loss) carry_loss = a.prev.loss_pool[j0 + lane];
+    }
+  }
 #pragma unroll
   for (int q = 0; q < STG; ++q) {
     const int c = q * NT + threadIdx.x;
@@ -200,7 +221,26 @@ __global__ __launch_bounds__(NW * 64)
       if (NEED_PHI) s_phi[c] = st_p[q];
     }
   }
+  if (POOL && GRAD && carry) {
+    carry_cnt = wave_sum_int(carry_cnt);
+    if (lane == 0) s_carry[wave] = carry_cnt;
+  }
   __syncthreads();
+  if (POOL && GRAD && carry && wave == NW - 1) {
+    int before = 0;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) before += s_carry[i];
+    const unsigned long long mask = __ballot(carry_flag != 0);
+    if (carry_flag != 0) {
+      const int pos = before + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                                         __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+      if (a.prev.kept_pos) a.prev.kept_pos[pos] = blockIdx.x * kWave + lane;
+      if (a.prev.kept_ids) a.prev.kept_ids[pos] = carry_id;
+      if (a.prev.loss) a.prev.loss[pos] = carry_loss;
+    }
+    if (lane == 0 && a.prev.kept_count && (int)(blockIdx.x + 1) * kWave >= a.prev.P)
+      *a.prev.kept_count = before + __popcll(mask);
+  }
 
   f4 gw[VPL], gp[VPL];
 #pragma unroll

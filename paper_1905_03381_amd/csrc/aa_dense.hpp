@@ -2,6 +2,7 @@
 #pragma once
 
 #include "aa_common.hpp"
+#include "aa_compact.hpp"
 
 namespace aa {
 
@@ -37,7 +38,15 @@ struct PassArgs {
   float *blk_gb;          // [nblk] bias-gradient partial (kAssist)
   const int32_t *t_upd;   // optional update counter; block 0 snapshots it into *t_snap
   int32_t *t_snap;
+  // Compaction of the pool before this one, carried by a pool pass with gradient sums
+  // (prev.flags == NULL: none): block b compacts positions [64 b, 64 b + 64) of that pool
+  // while its own rows are in flight.  Needs ceil(prev.P / 64) <= blocks of this launch and
+  // 16-byte aligned prev.flags; prev.tile_off is not used.
+  CompactArgs prev;
 };
+
+// Largest pool whose compaction a pass of `nblk` blocks can carry.
+inline int64_t dense_carry_capacity(int32_t nblk) { return (int64_t)nblk * kWave; }
 
 struct FinalizeArgs {
   const float *partial;

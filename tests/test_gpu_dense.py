@@ -484,13 +484,15 @@ def test_train_epoch_matches_oracle_driver(ref, ws):
     perm = synth.epoch_permutation(n, seed=7, epoch=0)
     Fh = ref.Features.dense(X)
     w_r, phi_r, b_r = np.zeros(d, np.float32), np.zeros(d, np.float32), 0.0
-    ms, t_upd = [], 0
+    ms, t_upd, batches = [], 0, []
     for t, idx in enumerate(synth.pools(perm, P)):
         lr = np.float32(np.float32(lr0) / np.sqrt(np.float32(t_upd + 1)))
         out = ref.step(Fh, y, idx, idx.shape[0], w_r, phi_r, b_r, gamma, seed + 0, 100 + t, lam, lr,
                        T, lr_a)
+        assert clear_draws(ref, out["prob"], gamma, seed, 100 + t).all()
         w_r, phi_r, b_r = out["w"], out["phi"], out["bias"]
         ms.append(out["m"])
+        batches.append((out["kept_ids"], out["loss"]))
         t_upd += 1 if out["m"] > 0 else 0
     F = dense_features(X)
     w, phi, b = dev(np.zeros(d, np.float32)), dev(np.zeros(d, np.float32)), scalar_dev(0.0)
@@ -498,9 +500,18 @@ def test_train_epoch_matches_oracle_driver(ref, ws):
     cfg = api.step_config(gamma, lam, lr0, lr_a, 0.0, seed, 100, Tt)
     tu = torch.zeros(1, dtype=torch.int32, device="cuda")
     hist = torch.full((len(ms),), -1, dtype=torch.int32, device="cuda")
-    api.train_epoch(F, dev(y), dev(perm), n, P, w, phi, b, cfg, tu, hist, ws)
+    ids_hist = torch.full((len(ms), P), -1, dtype=torch.int32, device="cuda")
+    loss_hist = torch.full((len(ms), P), -3.0, device="cuda")
+    api.train_epoch(F, dev(y), dev(perm), n, P, w, phi, b, cfg, tu, hist, ws, ids_hist, loss_hist)
     assert np.array_equal(host(hist), np.array(ms))
     assert int(host(tu)[0]) == t_upd
+    # every step's batch: compaction carried by the next step's pass, except where the next
+    # pool is too short to carry it (the 16-row last pool) and for the last step itself
+    for t, (ids_ref, loss_ref) in enumerate(batches):
+        assert np.array_equal(host(ids_hist)[t, :ms[t]], ids_ref), f"batch {t}"
+        assert np.all(host(ids_hist)[t, ms[t]:] == -1)
+        assert np.allclose(host(loss_hist)[t, :ms[t]], loss_ref, rtol=1e-4, atol=1e-6)
+        assert np.all(host(loss_hist)[t, ms[t]:] == -3.0)
     assert np.allclose(host(w), w_r, rtol=1e-4, atol=1e-6)
     assert np.allclose(host(phi), phi_r, rtol=1e-4, atol=1e-6)
     assert abs(float(host(b)[0]) - b_r) < 1e-5
@@ -545,19 +556,21 @@ def test_graph_replays_match_eager(ws):
     w, phi, b = torch.zeros(d, device="cuda"), torch.zeros(d, device="cuda"), scalar_dev(0.0)
     tu = torch.zeros(1, dtype=torch.int32, device="cuda")
     hist = torch.zeros(4, dtype=torch.int32, device="cuda")
+    ids = torch.zeros((4, P), dtype=torch.int32, device="cuda")
+    loss = torch.zeros((4, P), device="cuda")
 
     def reset():
-        for t in (w, phi, b, tu, hist):
+        for t in (w, phi, b, tu, hist, ids, loss):
             t.zero_()
 
     reset()
-    api.train_epoch(F, yd, perm, n, P, w, phi, b, cfg, tu, hist, ws)
-    eager = [host(t).copy() for t in (w, phi, b, tu, hist)]
+    api.train_epoch(F, yd, perm, n, P, w, phi, b, cfg, tu, hist, ws, ids, loss)
+    eager = [host(t).copy() for t in (w, phi, b, tu, hist, ids, loss)]
     g = torch.cuda.CUDAGraph()
     reset()
     torch.cuda.synchronize()
     with torch.cuda.graph(g):
-        api.train_epoch(F, yd, perm, n, P, w, phi, b, cfg, tu, hist, ws)
+        api.train_epoch(F, yd, perm, n, P, w, phi, b, cfg, tu, hist, ws, ids, loss)
     for _ in range(3):
         reset()
         scratch = torch.randn(1 << 16, device="cuda").sum()      # unrelated eager work
@@ -565,5 +578,5 @@ def test_graph_replays_match_eager(ws):
         g.replay()
         torch.cuda.synchronize()
         del scratch
-        for got, want in zip((w, phi, b, tu, hist), eager):
+        for got, want in zip((w, phi, b, tu, hist, ids, loss), eager):
             assert np.array_equal(host(got), want)

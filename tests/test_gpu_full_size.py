@@ -36,7 +36,7 @@ def test_first_pools_and_last_short_pool(ref, workload):
     steps = 3
     # oracle trajectory over the first pools
     w_r, phi_r, b_r = np.zeros(D, np.float32), np.zeros(D, np.float32), 0.0
-    ms = []
+    ms, batches = [], []
     for t in range(steps):
         idx = perm[t * P:(t + 1) * P]
         lr = np.float32(np.float32(LR0) / np.sqrt(np.float32(t + 1)))
@@ -45,12 +45,22 @@ def test_first_pools_and_last_short_pool(ref, workload):
         assert out["m"] > 0
         w_r, phi_r, b_r = out["w"], out["phi"], out["bias"]
         ms.append(out["m"])
+        batches.append((out["kept_ids"], out["loss"]))
     w, phi, b = torch.zeros(D, device="cuda"), torch.zeros(D, device="cuda"), scalar_dev(0.0)
     tu = torch.zeros(1, dtype=torch.int32, device="cuda")
     hist = torch.zeros(steps, dtype=torch.int32, device="cuda")
     cfg = api.step_config(GAMMA, LAM, LR0, LR_A, 0.0, SEED, 0, Tt)
-    api.train_epoch(F, yd, dev(perm), steps * P, P, w, phi, b, cfg, tu, hist, ws)
+    ids_hist = torch.full((steps, P), -1, dtype=torch.int32, device="cuda")
+    loss_hist = torch.full((steps, P), -3.0, device="cuda")
+    api.train_epoch(F, yd, dev(perm), steps * P, P, w, phi, b, cfg, tu, hist, ws, ids_hist, loss_hist)
     assert np.array_equal(host(hist), np.array(ms))      # kept counts: exact
+    # the batch of every step (the first two compacted by the pass of the step after them,
+    # at exactly the 64 positions per block that pass can carry): ids exact, losses close
+    for t, (ids_ref, loss_ref) in enumerate(batches):
+        assert np.array_equal(host(ids_hist)[t, :ms[t]], ids_ref), f"batch {t}"
+        assert np.all(host(ids_hist)[t, ms[t]:] == -1)
+        assert np.allclose(host(loss_hist)[t, :ms[t]], loss_ref, rtol=1e-4, atol=1e-5)
+        assert np.all(host(loss_hist)[t, ms[t]:] == -3.0)
     assert np.allclose(host(w), w_r, rtol=1e-4, atol=1e-7)
     assert np.allclose(host(phi), phi_r, rtol=1e-4, atol=1e-7)
     assert abs(float(host(b)[0]) - b_r) < 1e-5
