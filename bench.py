@@ -105,16 +105,19 @@ class Job:
     def cfg(self, g, lr):
         return self.api.step_config(self.gamma, self.lam, lr, self.lr_a, 0.0, self.seed, g, self.T)
 
-    def run(self, g0, g1, hook=None):
+    def run(self, g0, g1, hook=None, hooks=None):
         """Enqueue global steps [g0, g1) on the current stream.  hook(g): called before a step
-        whose row-pass kernel should be bracketed by events."""
+        whose row-pass kernel should be bracketed by events (per-step pipelines); hooks(g, last):
+        the same for the steps [g, last) of one epoch call of the fused pipeline."""
         api, a = self.api, self.a
-        if a.pipeline == "fused" and hook is None:
+        if a.pipeline == "fused":
             g = g0
             while g < g1:   # one C call per epoch slice; step size lr0/sqrt(t) lives on the device
                 e, lo, _ = self.pool_of(g)
                 last = min(g1, (e + 1) * self.steps_per_epoch)
                 rows = min(a.n - lo, (last - g) * a.pool)
+                if hooks:
+                    hooks(g, last)
                 api.train_epoch(self.F, self.y, self.perms[e][lo:], rows, a.pool, self.w, self.phi,
                                 self.b, self.cfg(g, a.lr0), self.t_upd, self.hist[g:], self.ws)
                 g = last
@@ -127,11 +130,7 @@ class Job:
             cfg = self.cfg(g, lr)
             if hook:
                 hook(g)
-            if a.pipeline == "fused":
-                api.fused_step(self.F, self.y, idx, P, self.w, self.phi, self.b, cfg, None,
-                               self.prob, self.keep, self.pos, self.ids, self.loss, self.cnt,
-                               self.ws)
-            elif a.pipeline == "two_pass":
+            if a.pipeline == "two_pass":
                 api.score_shrink(self.F, idx, P, self.phi, self.b, self.gamma, self.seed, g, None,
                                  self.prob, self.keep, self.pos, self.cnt, self.ws)
                 api.gather(None, 0, idx, self.pos, self.cnt, P, None, self.ids)
@@ -247,20 +246,27 @@ def main():
     # ---- dominant kernel: the row pass, timed live with HIP events around every launch
     # (torch events are hipEvent_t underneath: recorded once here so that they exist, then
     # re-recorded by the library's hook on the stream the kernel is launched on)
-    pairs = {}
+    pairs, keepalive = {}, []
 
-    def hook(g):
+    def new_pair(g):
         e0 = torch.cuda.Event(enable_timing=True)
         e1 = torch.cuda.Event(enable_timing=True)
         e0.record()
         e1.record()
         pairs[g] = (e0, e1)
-        api.profile_hook(e0.cuda_event, e1.cuda_event)
+        return e0.cuda_event, e1.cuda_event
+
+    def hook(g):
+        api.profile_hook(*new_pair(g))
+
+    def hooks(g, last):   # one event pair per step of the coming epoch call
+        handles = [new_pair(k) for k in range(g, last)]
+        keepalive.append(api.profile_hooks([h[0] for h in handles], [h[1] for h in handles]))
 
     job.reset()
     saved_pipeline = a.pipeline
     job.run(0, W)
-    job.run(W, W + K, hook=hook)
+    job.run(W, W + K, hook=hook, hooks=hooks)
     torch.cuda.synchronize()
     durs = np.array([pairs[g][0].elapsed_time(pairs[g][1]) for g in range(W, W + K)]) * 1e-3
     sizes = np.array([job.pool_of(g)[2] for g in range(W, W + K)], dtype=np.float64)

@@ -95,6 +95,12 @@ int32_t aa_workspace_init(void *ws, size_t ws_bytes, void *stream);
  * thread safe. */
 int32_t aa_profile_hook(void *event_before, void *event_after);
 
+/* The same for the next `count` row-pass launches, pair i around the i-th of
+ * them (e.g. every step of one aa_train_epoch call).  The two arrays are host
+ * arrays of hipEvent_t handles that must stay valid until those launches have
+ * been issued.  count == 0 disarms. */
+int32_t aa_profile_hooks(void *const *events_before, void *const *events_after, int32_t count);
+
 /* ---- a1: Assistant score (Section 5.2: g(x_i; phi); Algorithm 1 evaluates it
  * once per drawn candidate).  For pool position j in [0, P):
  *   logit[j] = phi . x_{idx[j]} + *bias,   prob[j] = 1 / (1 + exp(-logit[j])).

@@ -19,6 +19,7 @@ AA_DENSE, AA_CSR = 0, 1
 
 SYMBOLS = [
     "aa_version", "aa_status_string", "aa_workspace_bytes", "aa_workspace_init", "aa_profile_hook",
+    "aa_profile_hooks",
     "aa_assistant_score", "aa_shrink", "aa_score_shrink", "aa_shrink_threshold", "aa_gather",
     "aa_gather_csr", "aa_svm_sgd_step", "aa_assistant_update", "aa_boss_assistant_step",
     "aa_fused_step", "aa_sk_step", "aa_train_epoch", "aa_threshold_update", "aa_bucket_batches",
@@ -62,6 +63,7 @@ def lib():
         "aa_workspace_bytes": (sz, [i32, i32]),
         "aa_workspace_init": (i32, [vp, sz, vp]),
         "aa_profile_hook": (i32, [vp, vp]),
+        "aa_profile_hooks": (i32, [vp, vp, i32]),
         "aa_assistant_score": (i32, [FP, vp, i32, vp, vp, vp, vp, vp]),
         "aa_shrink": (i32, [vp, i32, f32, u64, u64, vp, vp, vp, vp, sz, vp]),
         "aa_score_shrink": (i32, [FP, vp, i32, vp, vp, f32, u64, u64, vp, vp, vp, vp, vp, vp, sz, vp]),
@@ -163,6 +165,17 @@ def workspace_bytes(P_max, d_max):
 def profile_hook(event_before, event_after):
     """Raw hipEvent_t handles (ints) or two Nones to disarm."""
     _check(lib().aa_profile_hook(event_before, event_after), "aa_profile_hook")
+
+
+def profile_hooks(events_before, events_after):
+    """Lists of raw hipEvent_t handles: pair i brackets the i-th row-pass launch from now on.
+    Returns the two ctypes arrays, which the caller keeps alive until those launches are issued."""
+    n = len(events_before)
+    assert n == len(events_after)
+    arr_b = (C.c_void_p * max(n, 1))(*events_before)
+    arr_a = (C.c_void_p * max(n, 1))(*events_after)
+    _check(lib().aa_profile_hooks(arr_b, arr_a, n), "aa_profile_hooks")
+    return arr_b, arr_a
 
 
 def assistant_score(F, idx, P, phi, bias, logit, prob):

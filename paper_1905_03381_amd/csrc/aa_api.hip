@@ -93,19 +93,24 @@ bool vec_ok(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; 
 
 hipStream_t as_stream(void *s) { return static_cast<hipStream_t>(s); }
 
-// One-shot timing hook: the next row-pass launch is bracketed by two caller events.
-hipEvent_t g_hook_before = nullptr, g_hook_after = nullptr;
-bool g_hook_armed = false;
+// Timing hook: the next row-pass launches are bracketed by caller events, one pair each
+// (the caller's arrays must outlive the launches they arm).
+void *const *g_hook_before = nullptr, *const *g_hook_after = nullptr;
+void *g_hook_single[2] = {nullptr, nullptr};
+int32_t g_hook_left = 0;
 
 struct HookScope {
   hipStream_t st;
-  bool on;
-  explicit HookScope(hipStream_t s) : st(s), on(g_hook_armed) {
-    g_hook_armed = false;
-    if (on) (void)hipEventRecord(g_hook_before, st);
+  hipEvent_t after;
+  explicit HookScope(hipStream_t s) : st(s), after(nullptr) {
+    if (g_hook_left > 0) {
+      --g_hook_left;
+      after = static_cast<hipEvent_t>(*g_hook_after++);
+      (void)hipEventRecord(static_cast<hipEvent_t>(*g_hook_before++), st);
+    }
   }
   ~HookScope() {
-    if (on) (void)hipEventRecord(g_hook_after, st);
+    if (after) (void)hipEventRecord(after, st);
   }
 };
 
@@ -494,13 +499,26 @@ size_t aa_workspace_bytes(int32_t P_max, int32_t d_max) {
 }
 
 int32_t aa_profile_hook(void *event_before, void *event_after) {
-  if (!event_before || !event_after) {
-    g_hook_armed = false;
-    return event_before || event_after ? AA_ERR_NULL : AA_OK;
-  }
-  g_hook_before = static_cast<hipEvent_t>(event_before);
-  g_hook_after = static_cast<hipEvent_t>(event_after);
-  g_hook_armed = true;
+  g_hook_left = 0;
+  if (!event_before || !event_after) return event_before || event_after ? AA_ERR_NULL : AA_OK;
+  g_hook_single[0] = event_before;
+  g_hook_single[1] = event_after;
+  g_hook_before = &g_hook_single[0];
+  g_hook_after = &g_hook_single[1];
+  g_hook_left = 1;
+  return AA_OK;
+}
+
+int32_t aa_profile_hooks(void *const *events_before, void *const *events_after, int32_t count) {
+  g_hook_left = 0;
+  if (count < 0) return AA_ERR_SHAPE;
+  if (count == 0) return AA_OK;
+  if (!events_before || !events_after) return AA_ERR_NULL;
+  for (int32_t i = 0; i < count; ++i)
+    if (!events_before[i] || !events_after[i]) return AA_ERR_NULL;
+  g_hook_before = events_before;
+  g_hook_after = events_after;
+  g_hook_left = count;
   return AA_OK;
 }
 

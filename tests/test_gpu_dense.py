@@ -580,3 +580,36 @@ def test_graph_replays_match_eager(ws):
         del scratch
         for got, want in zip((w, phi, b, tu, hist, ids, loss), eager):
             assert np.array_equal(host(got), want)
+
+
+def test_profile_hooks_bracket_every_step_of_an_epoch(ws):
+    """aa_profile_hooks arms one event pair per row-pass launch: after an epoch call every pair has
+    been recorded on the launch stream, in step order, and the hook is disarmed again."""
+    n, d, P = 3000, 1024, 1000
+    X, y = make_dense(n, d, 111, unit=True)
+    F = dense_features(X)
+    perm = dev(rng(112).permutation(n).astype(np.int32))
+    w, phi, b = torch.zeros(d, device="cuda"), torch.zeros(d, device="cuda"), scalar_dev(0.0)
+    cfg = api.step_config(0.1, 1e-4, 1.0, 0.1, 0.0, 9, 0, scalar_dev(0.0))
+    hist = torch.zeros(3, dtype=torch.int32, device="cuda")
+    pairs = []
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        e1.record()
+        pairs.append((e0, e1))
+    torch.cuda.synchronize()
+    keepalive = api.profile_hooks([p[0].cuda_event for p in pairs], [p[1].cuda_event for p in pairs])
+    api.train_epoch(F, dev(y), perm, n, P, w, phi, b, cfg, None, hist, ws)
+    torch.cuda.synchronize()
+    durs = [p[0].elapsed_time(p[1]) for p in pairs]
+    assert all(0.001 < t < 50.0 for t in durs), durs            # milliseconds: each pair holds a kernel
+    assert pairs[0][1].elapsed_time(pairs[1][0]) > 0 and pairs[1][1].elapsed_time(pairs[2][0]) > 0
+    # disarmed: another call leaves the events alone
+    before = [p[0].elapsed_time(p[1]) for p in pairs]
+    api.train_epoch(F, dev(y), perm, n, P, w, phi, b, cfg, None, hist, ws)
+    torch.cuda.synchronize()
+    assert [p[0].elapsed_time(p[1]) for p in pairs] == before
+    del keepalive
+    with pytest.raises(api.AAError):
+        api.profile_hooks([None], [pairs[0][1].cuda_event])
