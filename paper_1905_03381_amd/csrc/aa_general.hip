@@ -302,7 +302,7 @@ int32_t general_pass_blocks(int32_t count, bool csr, int mode) {
   const bool grad = (mode & (kSvm | kAssist)) != 0;
   const int waves = (grad ? kGradThreads : kPoolThreads) / kWave;
   const int rows_per_block = waves * (csr ? 4 : 1);
-  const int cap = grad ? 256 : 256 * 8;
+  const int cap = grad ? 256 : 256 * 16;
   int64_t want = ((int64_t)count + rows_per_block - 1) / rows_per_block;
   if (want > cap) want = cap;
   if (want < 1) want = 1;
