@@ -14,45 +14,87 @@ namespace aa {
 
 namespace {
 
+// Batches up to this size find the two middle values by rank counting (every thread ranks one
+// loss against all others read as LDS broadcasts: two barriers); larger ones are sorted.
+constexpr int kRankSelectMax = 512;
+
 __global__ __launch_bounds__(1024) void k_threshold_update(const ThresholdArgs a) {
-  __shared__ float s[kMedianMax];
+  __shared__ __attribute__((aligned(16))) float s[kMedianMax];
+  __shared__ float s_mid[2];
+  // every load that does not depend on another leaves at once: the count, the first losses,
+  // the state (one memory round trip for a small batch instead of three)
+  const int i0 = threadIdx.x;
+  const float x0 = i0 < a.m_max ? a.loss[i0] : 0.f;
+  const float T_old = *a.T;
+  const int init_old = *a.initialised;
   const int m = min(max(*a.m_dev, 0), a.m_max);
   if (m == 0) return;
-  int n = 1;
-  while (n < m) n <<= 1;
-  for (int i = threadIdx.x; i < n; i += blockDim.x) s[i] = i < m ? a.loss[i] : __builtin_inff();
-  __syncthreads();
-  for (int k = 2; k <= n; k <<= 1) {
-    for (int j = k >> 1; j > 0; j >>= 1) {
-      for (int i = threadIdx.x; i < n; i += blockDim.x) {
-        const int p = i ^ j;
-        if (p > i) {
-          const float x = s[i], y = s[p];
-          const bool up = (i & k) == 0;
-          if (up ? (x > y) : (x < y)) {
-            s[i] = y;
-            s[p] = x;
+  float lo_mid, hi_mid;  // sorted[(m-1)/2] and sorted[m/2]
+  if (m <= kRankSelectMax) {
+    const int i = i0;
+    const float x = x0;
+    if (i < m) s[i] = x;
+    __syncthreads();
+    if (i < m) {
+      int rank = 0;  // position of x in the stable sorted order
+      const int m4 = m & ~3;
+#pragma unroll 4
+      for (int j = 0; j < m4; j += 4) {  // 128-bit LDS broadcasts, several in flight
+        const float4 v = *reinterpret_cast<const float4 *>(s + j);
+        rank += (v.x < x || (v.x == x && j < i)) ? 1 : 0;
+        rank += (v.y < x || (v.y == x && j + 1 < i)) ? 1 : 0;
+        rank += (v.z < x || (v.z == x && j + 2 < i)) ? 1 : 0;
+        rank += (v.w < x || (v.w == x && j + 3 < i)) ? 1 : 0;
+      }
+      for (int j = m4; j < m; ++j) {
+        const float v = s[j];
+        rank += (v < x || (v == x && j < i)) ? 1 : 0;
+      }
+      if (rank == (m - 1) / 2) s_mid[0] = x;
+      if (rank == m / 2) s_mid[1] = x;
+    }
+    __syncthreads();
+    lo_mid = s_mid[0];
+    hi_mid = s_mid[1];
+  } else {
+    int n = 1;
+    while (n < m) n <<= 1;
+    for (int i = threadIdx.x; i < n; i += blockDim.x) s[i] = i < m ? a.loss[i] : __builtin_inff();
+    __syncthreads();
+    for (int k = 2; k <= n; k <<= 1) {
+      for (int j = k >> 1; j > 0; j >>= 1) {
+        for (int i = threadIdx.x; i < n; i += blockDim.x) {
+          const int p = i ^ j;
+          if (p > i) {
+            const float x = s[i], y = s[p];
+            const bool up = (i & k) == 0;
+            if (up ? (x > y) : (x < y)) {
+              s[i] = y;
+              s[p] = x;
+            }
           }
         }
+        __syncthreads();
       }
-      __syncthreads();
     }
+    lo_mid = s[(m - 1) / 2];
+    hi_mid = s[m / 2];
   }
   if (threadIdx.x == 0) {
     // every product and sum below is rounded to fp32 on its own: no fused multiply-add
 #pragma clang fp contract(off)
     float med;
     if (m & 1) {
-      med = s[m / 2];
+      med = hi_mid;
     } else {
-      const float sum = s[m / 2 - 1] + s[m / 2];
+      const float sum = lo_mid + hi_mid;
       med = sum * 0.5f;
     }
-    if (*a.initialised == 0) {
+    if (init_old == 0) {
       *a.T = med;
       *a.initialised = 1;
     } else {
-      const float keep_part = a.momentum * *a.T;
+      const float keep_part = a.momentum * T_old;
       const float one_minus = 1.0f - a.momentum;
       const float new_part = one_minus * med;
       *a.T = keep_part + new_part;

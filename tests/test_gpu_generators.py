@@ -18,7 +18,7 @@ def rng(seed):
     return np.random.default_rng(seed)
 
 
-@pytest.mark.parametrize("sizes", [[255, 256, 1, 2, 1000], [16384, 16383, 7]])
+@pytest.mark.parametrize("sizes", [[255, 256, 1, 2, 1000], [16384, 16383, 7], [512, 513, 3, 4]])
 def test_threshold_update_bit_exact(ref, sizes):
     r = rng(1)
     T_ref, init_ref = 0.0, False
@@ -33,6 +33,20 @@ def test_threshold_update_bit_exact(ref, sizes):
         assert np.float32(T_ref) == host(T)[0] and int(host(init)[0]) == 1
     api.threshold_update(buf, scalar_dev(0, torch.int32), 10, 0.9, T, init)   # empty batch
     assert np.float32(T_ref) == host(T)[0]
+
+
+@pytest.mark.parametrize("m", [6, 256, 511, 2000])
+def test_threshold_update_with_ties(ref, m):
+    """Losses drawn from three values: the middle elements are found among equal keys."""
+    r = rng(2)
+    T_ref, init_ref = 0.0, False
+    T = scalar_dev(0.0)
+    init = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for _ in range(3):
+        loss = r.choice(np.array([0.25, 0.5, 2.0], np.float32), m)
+        T_ref, init_ref = ref.threshold_update(loss, 0.8, T_ref, init_ref)
+        api.threshold_update(dev(loss), scalar_dev(m, torch.int32), m, 0.8, T, init)
+        assert np.float32(T_ref) == host(T)[0]
 
 
 @pytest.mark.parametrize("m", [0, 1, 500, 2048, 2049, 100_003])
