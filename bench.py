@@ -242,6 +242,13 @@ def main():
     cands = job.candidates(W, W + K)
     hist = job.hist.cpu().numpy()
     kept = int(hist[W:W + K].sum()) if a.pipeline == "fused" else None
+    keep_by_epoch = None
+    if a.pipeline == "fused":   # keep rate of each epoch the run touches (warm-up included)
+        keep_by_epoch = []
+        for e in range(job.n_epochs):
+            g_lo, g_hi = e * job.steps_per_epoch, min((e + 1) * job.steps_per_epoch, W + K)
+            if g_hi > g_lo:
+                keep_by_epoch.append(float(hist[g_lo:g_hi].sum()) / job.candidates(g_lo, g_hi))
 
     # ---- dominant kernel: the row pass, timed live with HIP events around every launch
     # (torch events are hipEvent_t underneath: recorded once here so that they exist, then
@@ -309,6 +316,7 @@ def main():
                    "lambda": job.lam, "lr0": a.lr0, "lr_a": job.lr_a, "T": 0.0},
         "regions_ms": [r * 1e3 for r in regions],
         "keep_rate": (kept / cands) if kept is not None else None,
+        "keep_rate_by_epoch": keep_by_epoch,
         "end_to_end_GBps": float(alg.sum() / elapsed / 1e9),
         "setup_s": {"generate": job.gen_s, "h2d": job.h2d_s},
         "roofline": roofline,

@@ -5,6 +5,7 @@
     python -m paper_1905_03381_amd.workloads translation   # translation batch generator
     python -m paper_1905_03381_amd.workloads sk            # hard-threshold shrinking, dense rows
     python -m paper_1905_03381_amd.workloads stale         # two-stream Boss / Assistant pipeline
+    python -m paper_1905_03381_amd.workloads rho           # dense fused step at fixed keep rates
 
 Each prints one JSON line: the stages of the workload with their time per call (HIP events
 on the launch stream, median of the repeats), the bytes each stage has to move and the
@@ -273,7 +274,41 @@ def stale(a, torch, api, synth):
             "stages": stages}
 
 
-WORKLOADS = {"sparse": sparse, "images": images, "translation": translation, "sk": sk,
+def rho(a, torch, api, synth):
+    """Fixed keep rates on the dense configuration: phi = 0 and lr_a = 0 hold every keep
+    probability at sigmoid(b), gamma = 0, so the keep rate is set by the bias alone and the
+    step time is decoupled from the learning dynamics."""
+    n, d, P, F, Xd, yd, perm = _dense_job(a, torch, api, synth)
+    steps = (n + P - 1) // P
+    T = torch.zeros(1, device="cuda")
+    w, phi, b = (torch.zeros(d, device="cuda"), torch.zeros(d, device="cuda"),
+                 torch.zeros(1, device="cuda"))
+    tu = torch.zeros(1, dtype=torch.int32, device="cuda")
+    hist = torch.zeros(steps, dtype=torch.int32, device="cuda")
+    ws = api.Workspace(P, d)
+    cfg = api.step_config(0.0, 1e-4, 1.0, 0.0, 0.0, 42, 0, T)
+    stages = []
+    for target in (0.1, 0.25, 0.5, 1.0):
+        bias = 40.0 if target >= 1.0 else float(np.log(target / (1.0 - target)))
+
+        def reset():
+            w.zero_(), phi.zero_(), tu.zero_(), b.fill_(bias)
+
+        reset()
+        g = torch.cuda.CUDAGraph()
+        api.train_epoch(F, yd, perm, n, P, w, phi, b, cfg, tu, hist, ws)    # loads the kernels
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g):
+            api.train_epoch(F, yd, perm, n, P, w, phi, b, cfg, tu, hist, ws)
+        us = _timed(torch, g.replay, a.repeats, reset) / steps
+        kept = float(hist.sum().item()) / n
+        stages.append(_stage(f"fused step at keep probability {target}", us, P * (4 * d + 9) + 4 * kept * P,
+                             note=f"measured keep rate {kept:.3f}, {P / us:.0f} M candidates/s"))
+    return {"workload": f"dense n={n} d={d}, pool {P}: fused step at fixed keep rates (hipGraph replay of one epoch)",
+            "stages": stages}
+
+
+WORKLOADS = {"rho": rho, "sparse": sparse, "images": images, "translation": translation, "sk": sk,
              "stale": stale}
 
 
