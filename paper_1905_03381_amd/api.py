@@ -150,8 +150,11 @@ class Workspace:
 
 
 def step_config(gamma, lam, lr, lr_a, l2_a, seed, step, T):
-    """T: 1-element float32 CUDA tensor (device scalar)."""
-    return aa_step_config(gamma, lam, lr, lr_a, l2_a, 0, seed, step, T.data_ptr())
+    """T: 1-element float32 CUDA tensor (device scalar).  The returned structure holds a
+    reference to it, so the address stays valid as long as the configuration lives."""
+    cfg = aa_step_config(gamma, lam, lr, lr_a, l2_a, 0, seed, step, T.data_ptr())
+    cfg._threshold = T
+    return cfg
 
 
 def version():

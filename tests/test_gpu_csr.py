@@ -256,3 +256,44 @@ def test_sparse_config_full_size_first_pools(ref):
                             f"phi step {t}")
         # the GPU state goes on from the oracle's bits so that step 2 is compared on equal inputs
         w, phi, b = dev(w_r), dev(phi_r), scalar_dev(b_r)
+
+
+def test_train_epoch_on_csr_rows(ref, ws, sparse):
+    """aa_train_epoch over CSR rows (general kernels, constant step size): kept counts and the
+    batch of every step against the oracle loop, the model within tolerance."""
+    rowptr, col, val, y, d = sparse
+    n, P = 9000, 2048
+    perm = rng(21).permutation(rowptr.size - 1)[:n].astype(np.int32)
+    Fh = ref.Features.csr(rowptr, col, val, d)
+    F = csr_features(rowptr, col, val, d)
+    gamma, lam, lr, lr_a, T, step0 = 0.1, 1e-4, 0.5, 0.3, 0.0, 3
+    steps = (n + P - 1) // P
+    for seed in range(42, 62):
+        w_r, phi_r, b_r = np.zeros(d, np.float32), np.zeros(d, np.float32), 0.0
+        ms, batches, ok = [], [], True
+        for t in range(steps):
+            idx = perm[t * P:(t + 1) * P]
+            out = ref.step(Fh, y, idx, idx.size, w_r, phi_r, b_r, gamma, seed, step0 + t, lam, lr, T, lr_a)
+            ok = ok and clear_draws(ref, out["prob"], gamma, seed, step0 + t).all()
+            w_r, phi_r, b_r = out["w"], out["phi"], out["bias"]
+            ms.append(out["m"])
+            batches.append(out["kept_ids"])
+        if ok:
+            break
+    assert ok
+    w, phi, b = dev(np.zeros(d, np.float32)), dev(np.zeros(d, np.float32)), scalar_dev(0.0)
+    Tt = scalar_dev(T)     # stays alive: the configuration holds its address
+    cfg = api.step_config(gamma, lam, lr, lr_a, 0.0, seed, step0, Tt)
+    hist = torch.full((steps,), -1, dtype=torch.int32, device="cuda")
+    ids = torch.full((steps, P), -1, dtype=torch.int32, device="cuda")
+    api.train_epoch(F, dev(y), dev(perm), n, P, w, phi, b, cfg, None, hist, ws, ids, None)
+    assert host(hist).tolist() == ms
+    for t, want in enumerate(batches):
+        assert np.array_equal(host(ids)[t, :ms[t]], want), f"batch {t}"
+    assert np.allclose(host(w), w_r, rtol=5e-4, atol=5e-6)
+    assert np.allclose(host(phi), phi_r, rtol=5e-4, atol=5e-6)
+    assert abs(float(host(b)[0]) - b_r) < 1e-5
+    # the device-side step-size schedule needs the register-resident dense kernels
+    with pytest.raises(api.AAError):
+        api.train_epoch(F, dev(y), dev(perm), n, P, w, phi, b, cfg,
+                        torch.zeros(1, dtype=torch.int32, device="cuda"), hist, ws)

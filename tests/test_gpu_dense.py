@@ -302,14 +302,20 @@ def _check_state(ref_out, w, phi, b, Fh, ids_kept, y, w0, phi0, b0, lr, lam, lr_
     assert abs(float(host(b)[0]) - ref_out["bias"]) <= RTOL * (abs(b0) + lr_a)
 
 
-@pytest.mark.parametrize("n,d,ld,P", SCORE_SHAPES + [(300_000, 128, None, 300_000)])
-def test_fused_step_matches_oracle_step(ref, ws, n, d, ld, P):
+@pytest.mark.parametrize("n,d,ld,P,gamma", [s + (0.1,) for s in SCORE_SHAPES] + [
+    (300_000, 128, None, 300_000, 0.1),
+    (700, 1024, None, 613, 0.0),     # no smoothing: the Assistant alone decides
+    (700, 1024, None, 613, 0.5),
+    (700, 1024, None, 613, 1.0),     # every candidate kept: the plain mini-batch step
+    (300, 130, None, 250, 1.0),      # the same through the general kernel
+])
+def test_fused_step_matches_oracle_step(ref, ws, n, d, ld, P, gamma):
     X, y = make_dense(n, d, 61, ld, unit=True)
     r = rng(62)
     w0 = (1.2 * r.standard_normal(d)).astype(np.float32)
     phi0 = (2.0 * r.standard_normal(d)).astype(np.float32)
     idx = r.permutation(n)[:P].astype(np.int32)
-    b0, gamma, seed, step, lam, lr, T, lr_a = 0.1, 0.1, 5, 17, 1e-3, 0.5, 0.2, 0.3
+    b0, seed, step, lam, lr, T, lr_a = 0.1, 5, 17, 1e-3, 0.5, 0.2, 0.3
     Fh = ref.Features.dense(X, d=d)
     for seed in range(5, 25):   # first Philox key with no draw inside the rounding band
         out = ref.step(Fh, y, idx, P, w0, phi0, b0, gamma, seed, step, lam, lr, T, lr_a)
@@ -341,6 +347,10 @@ def test_fused_step_matches_oracle_step(ref, ws, n, d, ld, P):
     assert_close_scaled(host(loss)[:m], out["loss"], Sw, "loss")
     assert np.all(host(loss)[m:] == -3.0)
     _check_state(out, w, phi, b, Fh, out["kept_ids"], y, w0, phi0, b0, lr, lam, lr_a, T)
+    if gamma == 1.0:   # Algorithm 1 with gamma = 1 is plain mini-batch SGD on the pool
+        assert m == P
+        w_van = ref.vanilla_minibatch_sgd(Fh, y, idx, P, w0, lam, lr)
+        assert np.array_equal(out["w"], w_van)
 
 
 def test_boss_assistant_step_equals_the_two_staged_calls(ref, ws):
@@ -590,7 +600,8 @@ def test_profile_hooks_bracket_every_step_of_an_epoch(ws):
     F = dense_features(X)
     perm = dev(rng(112).permutation(n).astype(np.int32))
     w, phi, b = torch.zeros(d, device="cuda"), torch.zeros(d, device="cuda"), scalar_dev(0.0)
-    cfg = api.step_config(0.1, 1e-4, 1.0, 0.1, 0.0, 9, 0, scalar_dev(0.0))
+    Tt = scalar_dev(0.0)
+    cfg = api.step_config(0.1, 1e-4, 1.0, 0.1, 0.0, 9, 0, Tt)
     hist = torch.zeros(3, dtype=torch.int32, device="cuda")
     pairs = []
     for _ in range(3):

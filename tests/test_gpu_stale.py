@@ -120,7 +120,8 @@ def test_runs_are_bit_identical_and_arguments_are_checked():
         assert np.array_equal(u, v)
     ws = api.Workspace(P, d, staleness=k)
     w, phi, bb = dev(z), dev(z), scalar_dev(0.0)
-    cfg = api.step_config(0.1, 1e-4, 0.5, 0.1, 0.0, 1, 0, scalar_dev(0.0))
+    Tt = scalar_dev(0.0)
+    cfg = api.step_config(0.1, 1e-4, 0.5, 0.1, 0.0, 1, 0, Tt)
     cur = torch.cuda.current_stream()
     with pytest.raises(api.AAError):      # the generator needs its own stream
         api.train_epoch_stale(F, dev(y), dev(perm), n, P, k, w, phi, bb, cfg, None, None, None, ws, cur)
