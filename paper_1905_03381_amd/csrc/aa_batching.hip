@@ -123,23 +123,24 @@ __global__ __launch_bounds__(256) void k_bucket_counts(const BucketArgs a) {
   if (threadIdx.x < a.n_buckets) a.tile_base[blockIdx.x * a.n_buckets + threadIdx.x] = hist[threadIdx.x];
 }
 
-__global__ __launch_bounds__(64) void k_bucket_scan(const BucketArgs a, int ntiles_max) {
+// One block, one wave per bucket (16 waves, each taking buckets w, w + 16): per-bucket totals over
+// the tiles, then the bucket starts and batch bases, then each tile's count becomes the position
+// where that tile's share of the bucket begins.
+__global__ __launch_bounds__(1024) void k_bucket_scan(const BucketArgs a, int ntiles_max) {
   __shared__ int total[kMaxBuckets], start[kMaxBuckets + 1], batch_base[kMaxBuckets + 1];
   const int m = min(max(*a.m_dev, 0), a.m_max);
   const int ntiles = (m + kBucketTile - 1) / kBucketTile;
-  const int b = threadIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
   const int nb = a.n_buckets;
-  if (b < nb) {
-    int run = 0;
-    for (int t = 0; t < ntiles; ++t) {
-      const int c = a.tile_base[t * nb + b];
-      a.tile_base[t * nb + b] = run;
-      run += c;
-    }
-    total[b] = run;
+  for (int b = wave; b < nb; b += nw) {
+    int sum = 0;
+    for (int t = lane; t < ntiles; t += kWave) sum += a.tile_base[t * nb + b];
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) sum += __shfl_xor(sum, off, kWave);
+    if (lane == 0) total[b] = sum;
   }
   __syncthreads();
-  if (b == 0) {
+  if (threadIdx.x == 0) {
     int s = 0, batches = 0;
     for (int q = 0; q < nb; ++q) {
       start[q] = s;
@@ -153,12 +154,27 @@ __global__ __launch_bounds__(64) void k_bucket_scan(const BucketArgs a, int ntil
     *a.n_batches = batches;
   }
   __syncthreads();
-  if (b <= nb) a.bucket_start[b] = start[b];
+  const int tid = threadIdx.x;
+  if (tid <= nb) a.bucket_start[tid] = start[tid];
   int *tail = a.tile_base + (size_t)ntiles_max * nb;  // [nb] starts, [nb] batch bases
-  if (b < nb) {
-    tail[b] = start[b];
-    tail[nb + b] = batch_base[b];
-    for (int t = 0; t < ntiles; ++t) a.tile_base[t * nb + b] += start[b];
+  if (tid < nb) {
+    tail[tid] = start[tid];
+    tail[nb + tid] = batch_base[tid];
+  }
+  for (int b = wave; b < nb; b += nw) {
+    int run = start[b];
+    for (int t0 = 0; t0 < ntiles; t0 += kWave) {
+      const int t = t0 + lane;
+      const int c = t < ntiles ? a.tile_base[t * nb + b] : 0;
+      int incl = c;
+#pragma unroll
+      for (int off = 1; off < kWave; off <<= 1) {
+        const int up = __shfl_up(incl, off, kWave);
+        if (lane >= off) incl += up;
+      }
+      if (t < ntiles) a.tile_base[t * nb + b] = run + incl - c;
+      run += __shfl(incl, kWave - 1, kWave);
+    }
   }
 }
 
@@ -223,7 +239,7 @@ hipError_t launch_bucket_batches(const BucketArgs &a, hipStream_t st) {
     hipLaunchKernelGGL(k_bucket_counts, dim3(ntiles), dim3(256), 0, st, a);
     if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
   }
-  hipLaunchKernelGGL(k_bucket_scan, dim3(1), dim3(64), 0, st, a, ntiles);
+  hipLaunchKernelGGL(k_bucket_scan, dim3(1), dim3(1024), 0, st, a, ntiles);
   if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
   if (ntiles > 0) hipLaunchKernelGGL(k_bucket_scatter, dim3(ntiles), dim3(256), 0, st, a, ntiles);
   return hipGetLastError();
