@@ -209,21 +209,49 @@ __global__ __launch_bounds__(kCsrTile) void k_csr_rowptr_tiles(const GatherCsrAr
   if (r < m) a.out_rowptr[r + 1] = tile_off[blockIdx.x] + excl + len;
 }
 
-// 16 lanes copy the entries of one kept row.
+// A wave takes 64 kept rows at a time: every lane fetches the extent of one row (position, id,
+// row pointers, output offset: one dependent chain for all 64), then groups of 16 lanes copy the
+// rows four at a time, four entries per lane in flight.
 __global__ __launch_bounds__(256) void k_csr_copy(const GatherCsrArgs a) {
   const int m = min(max(*a.kept_count, 0), a.max_rows);
-  const int sub = threadIdx.x & 15;
-  const int g0 = (blockIdx.x * 256 + threadIdx.x) >> 4, ng = (gridDim.x * 256) >> 4;
-  for (int r = g0; r < m; r += ng) {
-    const int pos = a.kept_pos ? a.kept_pos[r] : r;
-    const long long id = a.idx ? a.idx[pos] : pos;
-    const long long e0 = a.rowptr[id];
-    const int len = (int)(a.rowptr[id + 1] - e0);
-    const long long o0 = a.out_rowptr[r];
-    if (o0 + len > a.out_nnz_cap) continue;
-    for (int e = sub; e < len; e += 16) {
-      a.out_col[o0 + e] = a.col[e0 + e];
-      if (a.val && a.out_val) a.out_val[o0 + e] = a.val[e0 + e];
+  const int lane = threadIdx.x & 63, grp = lane >> 4, sub = lane & 15;
+  const int wave = (blockIdx.x * 256 + threadIdx.x) >> 6, nwaves = (gridDim.x * 256) >> 6;
+  const bool with_val = a.val && a.out_val;
+  for (int base = wave * kWave; base < m; base += nwaves * kWave) {
+    const int r = base + lane;
+    long long e0_l = 0, o0_l = 0;
+    int len_l = 0;
+    if (r < m) {
+      const int pos = a.kept_pos ? a.kept_pos[r] : r;
+      const long long id = a.idx ? a.idx[pos] : pos;
+      e0_l = a.rowptr[id];
+      len_l = (int)(a.rowptr[id + 1] - e0_l);
+      o0_l = a.out_rowptr[r];
+      if (o0_l + len_l > a.out_nnz_cap) len_l = 0;  // a row that does not fit is not copied
+    }
+    const int cnt = min(kWave, m - base);
+    for (int it = 0; it * 4 < cnt; ++it) {
+      const int li = it * 4 + grp;
+      const long long e0 = __shfl(e0_l, li, kWave), o0 = __shfl(o0_l, li, kWave);
+      const int len = __shfl(len_l, li, kWave);  // rows past the batch's end have length 0
+      for (int e = sub; e < len; e += 64) {
+        int c[4];
+        float v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int eu = e + 16 * u;
+          c[u] = eu < len ? a.col[e0 + eu] : 0;
+          v[u] = (with_val && eu < len) ? a.val[e0 + eu] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int eu = e + 16 * u;
+          if (eu < len) {
+            a.out_col[o0 + eu] = c[u];
+            if (with_val) a.out_val[o0 + eu] = v[u];
+          }
+        }
+      }
     }
   }
 }
@@ -304,7 +332,7 @@ hipError_t launch_gather_csr(const GatherCsrArgs &a, long long *tile_scratch, hi
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || a.max_rows <= 0) return e;
-  int nb = (a.max_rows + 15) / 16;
+  int nb = (a.max_rows + 255) / 256;   // 64 rows per wave, four waves per block
   if (nb > 256 * 8) nb = 256 * 8;
   hipLaunchKernelGGL(k_csr_copy, dim3(nb), dim3(256), 0, st, a);
   return hipGetLastError();
