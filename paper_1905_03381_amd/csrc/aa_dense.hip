@@ -17,7 +17,7 @@
 #define AA_NW_D1024 16   // waves per block of the gradient passes at 512 < d <= 1024
 #endif
 #ifndef AA_RIF_D1024
-#define AA_RIF_D1024 2   // rows in flight per wave there
+#define AA_RIF_D1024 1   // rows in flight per wave there
 #endif
 
 // Feature rows are read once per step: non-temporal loads keep them from displacing the
