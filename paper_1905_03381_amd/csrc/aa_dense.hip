@@ -603,7 +603,7 @@ hipError_t launch_dense_pass(const PassArgs &a, int mode, int32_t d, int32_t nbl
     switch (s.vpl) {
       case 1: return launch_pool<64, 1, 4>(a, nblk, st);
       case 2: return launch_pool<64, 2, 4>(a, nblk, st);
-      case 4: return launch_pool<64, 4, 4>(a, nblk, st);
+      case 4: return launch_pool<64, 4, 2>(a, nblk, st);
       default: return launch_pool<64, 8, 2>(a, nblk, st);
     }
   }
