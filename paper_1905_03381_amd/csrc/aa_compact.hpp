@@ -31,9 +31,18 @@ __device__ inline int count_flags_before(const uint8_t *flags, int j0, int *smem
   int cnt = 0;
   if ((reinterpret_cast<uintptr_t>(flags) & 15) == 0) {
     const uint4 *p = reinterpret_cast<const uint4 *>(flags);
-    for (int q = threadIdx.x; q < (j0 >> 4); q += blockDim.x) {
+    const int n16 = j0 >> 4, stride = blockDim.x;
+    int q = threadIdx.x;
+    for (; q + 3 * stride < n16; q += 4 * stride) {  // four loads in flight per thread
+      const uint4 v0 = p[q], v1 = p[q + stride], v2 = p[q + 2 * stride], v3 = p[q + 3 * stride];
+      cnt += __popc(v0.x) + __popc(v0.y) + __popc(v0.z) + __popc(v0.w);  // bytes are 0 or 1
+      cnt += __popc(v1.x) + __popc(v1.y) + __popc(v1.z) + __popc(v1.w);
+      cnt += __popc(v2.x) + __popc(v2.y) + __popc(v2.z) + __popc(v2.w);
+      cnt += __popc(v3.x) + __popc(v3.y) + __popc(v3.z) + __popc(v3.w);
+    }
+    for (; q < n16; q += stride) {
       const uint4 v = p[q];
-      cnt += __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w);  // bytes are 0 or 1
+      cnt += __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w);
     }
   } else {
     for (int j = threadIdx.x; j < j0; j += blockDim.x) cnt += flags[j] != 0;
