@@ -34,7 +34,11 @@ struct Ws {
   size_t total;
 };
 
-size_t general_acc_bytes(int32_t d) { return (16 + 2 * (size_t)d) * sizeof(float); }
+// General kernels: 16 scalars, the two atomic accumulators, then the per-block sums of the
+// first columns.
+size_t general_acc_bytes(int32_t d) {
+  return (16 + 2 * (size_t)d + general_part_floats(d)) * sizeof(float);
+}
 
 Ws carve(void *ws, size_t grad_bytes, int32_t P, bool epoch_outputs = false) {
   Ws w;
@@ -227,6 +231,8 @@ hipError_t run_pass(const PassSpec &s, const Ws &ws, int32_t *nblk_out, hipStrea
   a.acc_gb = acc + 1;
   a.acc_w = acc + 16;
   a.acc_p = acc + 16 + s.F->d;
+  a.part = acc + 16 + 2 * (size_t)s.F->d;
+  a.head = general_head_columns(s.F->d, ((s.mode & kSvm) ? 1 : 0) + ((s.mode & kAssist) ? 1 : 0));
   const int32_t nblk = general_pass_blocks(s.count_max, csr, s.mode);
   *nblk_out = nblk;
   HookScope hook(st);
@@ -294,6 +300,10 @@ hipError_t run_update(const PassSpec &s, const UpdateSpec &u, const Ws &ws, int3
   p.acc_gb = acc + 1;
   p.acc_w = acc + 16;
   p.acc_p = acc + 16 + s.F->d;
+  p.part = acc + 16 + 2 * (size_t)s.F->d;
+  p.nvec = ((s.mode & kSvm) ? 1 : 0) + ((s.mode & kAssist) ? 1 : 0);
+  p.head = general_head_columns(s.F->d, p.nvec);
+  p.nblk_pass = nblk;
   p.m_dev = pool ? nullptr : s.m_dev;
   p.m_max = s.count_max;
   p.w = (s.mode & kSvm) ? s.w : nullptr;

@@ -5,8 +5,10 @@
 // kernel folds into the model.  Every block first sums what it can in an LDS table
 // of its own -- the first columns have a slot each (frequency-ranked column ids,
 // the usual layout of bag-of-words data, put the hot columns there), any other
-// column claims a slot by hash, first come first served -- and flushes one atomic
-// per used slot at the end.
+// column claims a slot by hash, first come first served.  At the end the first
+// columns leave the block as plain stores into a per-block array that the second
+// kernel sums (nearly every block touches nearly every one of them, so atomics
+// would buy nothing), the hashed slots as one atomic each.
 // In bag-of-words data a few hot columns take most of the entries, and device-wide
 // atomics on one address run one after the other, about 13 ns each on MI355X: the
 // table turns the thousands of adds a block would send to a hot column into one.
@@ -28,9 +30,9 @@ __device__ __forceinline__ float gsum(float v) {
 
 // Per-block LDS table: kDirect* slots for columns 0..kDirect*-1, then kHashed* slots
 // claimed by hash (a column tag each); one sum per slot and updated vector.
-// 80 KB with both vectors, 96 KB with one: one block of 16 waves per compute unit.
-constexpr int kDirectTwoVec = 4096, kHashedTwoVec = 4096;
-constexpr int kDirectOneVec = 8192, kHashedOneVec = 8192;
+// 112 KB with both vectors, 128 KB with one: one block of 16 waves per compute unit.
+constexpr int kDirectTwoVec = 8192, kHashedTwoVec = 4096;
+constexpr int kDirectOneVec = 16384, kHashedOneVec = 8192;
 constexpr int kGradThreads = 1024, kPoolThreads = 256;
 
 template <int GL, int MODE, bool CSR>
@@ -188,8 +190,14 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
 
   if (GRAD) {
     __syncthreads();
-    for (int k = threadIdx.x; k < D + H; k += blockDim.x) {
-      const int c = k < D ? (k < a.d ? k : -1) : s_tag[k - D];
+    // the first columns: this block's sums, zeros included, as plain stores
+    float *const mine = a.part + (size_t)blockIdx.x * NVEC * a.head;
+    for (int k = threadIdx.x; k < a.head; k += blockDim.x) {
+      if (SVM) mine[k] = s_w[k];
+      if (ASSIST) mine[(SVM ? a.head : 0) + k] = s_p[k];
+    }
+    for (int k = D + threadIdx.x; k < D + H; k += blockDim.x) {
+      const int c = s_tag[k - D];
       if (c < 0) continue;
       if (SVM) {
         const float v = s_w[k];
@@ -221,10 +229,16 @@ __global__ __launch_bounds__(256) void k_zero_f32(float *p, size_t count) {
     p[i] = 0.f;
 }
 
-__global__ __launch_bounds__(256) void k_apply_general(const ApplyArgs a) {
+// Folds the gradient sums into the model.  Blocks [0, nh): 16 of the first `head` columns each,
+// 16 threads per column adding the per-block sums of the pass in a fixed order; blocks after
+// them: the other columns, whose sums are the atomic accumulators; then one block per
+// compaction tile.
+constexpr int kHeadCols = 16;
+
+__global__ __launch_bounds__(256) void k_apply_general(const ApplyArgs a, int nh, int nrest) {
   __shared__ int s_int[40];
-  const int nb = (int)gridDim.x - (a.flags ? compact_tiles(a.P) : 0);
-  if ((int)blockIdx.x >= nb) {
+  __shared__ float s_part[2][16][kHeadCols];
+  if ((int)blockIdx.x >= nh + nrest) {
     CompactArgs c;
     c.flags = a.flags;
     c.P = a.P;
@@ -235,33 +249,59 @@ __global__ __launch_bounds__(256) void k_apply_general(const ApplyArgs a) {
     c.loss = a.loss;
     c.kept_count = a.kept_count;
     c.tile_off = nullptr;
-    tile_compact(c, (int)blockIdx.x - nb, s_int);
+    tile_compact(c, (int)blockIdx.x - nh - nrest, s_int);
     return;
   }
-  int m = a.m_dev ? min(max(*a.m_dev, 0), a.m_max) : *a.acc_cnt;
+  const int m = a.m_dev ? min(max(*a.m_dev, 0), a.m_max) : *a.acc_cnt;
   if (blockIdx.x == 0 && threadIdx.x == 0 && a.kept_hist) *a.kept_hist = m;
-  if (m <= 0) {  // nothing kept: the model stays, its copy is still due
-    if (a.phi && a.phi_copy)
-      for (int k = blockIdx.x * blockDim.x + threadIdx.x; k < a.d; k += nb * blockDim.x)
-        a.phi_copy[k] = a.phi[k];
-    if (blockIdx.x == 0 && threadIdx.x == 0 && a.phi && a.bias && a.bias_copy)
-      *a.bias_copy = *a.bias;
-    return;
-  }
-  const float inv_m = 1.f / (float)m;
+  const float inv_m = m > 0 ? 1.f / (float)m : 0.f;
   const float shrink = 1.f - a.lr * a.lambda, scale = a.lr * inv_m;
-  for (int k = blockIdx.x * blockDim.x + threadIdx.x; k < a.d; k += nb * blockDim.x) {
-    if (a.w) a.w[k] = __fmaf_rn(scale, a.acc_w[k], shrink * a.w[k]);
+  // one column: sums gw / gp -> new w, new phi (m == 0: the model stays, its copy is still due)
+  auto fold = [&](int k, float gw, float gp) {
+    if (m <= 0) {
+      if (a.phi && a.phi_copy) a.phi_copy[k] = a.phi[k];
+      return;
+    }
+    if (a.w) a.w[k] = __fmaf_rn(scale, gw, shrink * a.w[k]);
     if (a.phi) {
       const float ph = a.phi[k];
-      const float pn = ph - a.lr_a * __fmaf_rn(a.l2_a, ph, a.acc_p[k] * inv_m);
+      const float pn = ph - a.lr_a * __fmaf_rn(a.l2_a, ph, gp * inv_m);
       a.phi[k] = pn;
       if (a.phi_copy) a.phi_copy[k] = pn;
     }
+  };
+  if ((int)blockIdx.x < nh) {
+    const int cl = threadIdx.x & (kHeadCols - 1), q = threadIdx.x >> 4;
+    const int k = blockIdx.x * kHeadCols + cl;
+    float sw = 0.f, sp = 0.f;
+    if (k < a.head && m > 0) {
+      const size_t stride = (size_t)a.nvec * a.head;
+      const float *pw = a.part + k, *pp = a.part + (a.w ? a.head : 0) + k;
+#pragma unroll 4
+      for (int b = q; b < a.nblk_pass; b += 16) {
+        if (a.w) sw += pw[b * stride];
+        if (a.phi) sp += pp[b * stride];
+      }
+    }
+    s_part[0][q][cl] = sw;
+    s_part[1][q][cl] = sp;
+    __syncthreads();
+    if (q == 0 && k < a.head) {
+      float gw = a.w ? a.acc_w[k] : 0.f, gp = a.phi ? a.acc_p[k] : 0.f;
+      for (int i = 0; i < 16; ++i) {
+        gw += s_part[0][i][cl];
+        gp += s_part[1][i][cl];
+      }
+      fold(k, gw, gp);
+    }
+  } else {
+    for (int k = a.head + ((int)blockIdx.x - nh) * blockDim.x + threadIdx.x; k < a.d;
+         k += nrest * blockDim.x)
+      fold(k, a.w ? a.acc_w[k] : 0.f, a.phi ? a.acc_p[k] : 0.f);
   }
   if (blockIdx.x == 0 && threadIdx.x == 0 && a.phi && a.bias) {
-    const float bn = *a.bias - a.lr_a * (*a.acc_gb * inv_m);
-    *a.bias = bn;
+    const float bn = m > 0 ? *a.bias - a.lr_a * (*a.acc_gb * inv_m) : *a.bias;
+    if (m > 0) *a.bias = bn;
     if (a.bias_copy) *a.bias_copy = bn;
   }
 }
@@ -302,7 +342,7 @@ int32_t general_pass_blocks(int32_t count, bool csr, int mode) {
   const bool grad = (mode & (kSvm | kAssist)) != 0;
   const int waves = (grad ? kGradThreads : kPoolThreads) / kWave;
   const int rows_per_block = waves * (csr ? 4 : 1);
-  const int cap = grad ? 256 : 256 * 16;
+  const int cap = grad ? kGeneralGradBlocks : 256 * 16;
   int64_t want = ((int64_t)count + rows_per_block - 1) / rows_per_block;
   if (want > cap) want = cap;
   if (want < 1) want = 1;
@@ -323,12 +363,19 @@ hipError_t launch_zero_f32(float *p, size_t count, hipStream_t st) {
   return hipGetLastError();
 }
 
+int32_t general_head_columns(int32_t d, int nvec) {
+  const int direct = nvec == 2 ? kDirectTwoVec : kDirectOneVec;
+  return d < direct ? d : direct;
+}
+
 hipError_t launch_general_apply(const ApplyArgs &a, hipStream_t st) {
-  int nb = (a.d + 1023) / 1024;
-  if (nb > 1024) nb = 1024;
-  if (nb < 1) nb = 1;
-  hipLaunchKernelGGL(k_apply_general, dim3(nb + (a.flags ? compact_tiles(a.P) : 0)), dim3(256), 0, st,
-                     a);
+  const int nh = (a.head + kHeadCols - 1) / kHeadCols;
+  int nrest = (a.d - a.head + 1023) / 1024;
+  if (nrest > 1024) nrest = 1024;
+  if (nrest < 0) nrest = 0;
+  if (nh + nrest < 1) nrest = 1;
+  hipLaunchKernelGGL(k_apply_general, dim3(nh + nrest + (a.flags ? compact_tiles(a.P) : 0)), dim3(256),
+                     0, st, a, nh, nrest);
   return hipGetLastError();
 }
 

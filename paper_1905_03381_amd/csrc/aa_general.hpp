@@ -35,7 +35,20 @@ struct GenArgs {
   float *acc_p;      // [d]
   int32_t *acc_cnt;  // kept count
   float *acc_gb;     // bias gradient
+  // per-block sums of the first `head` columns: part[(block * nvec + vec) * head + column],
+  // written whole by every block of a gradient pass (no clearing needed)
+  float *part;
+  int32_t head;
 };
+
+// Columns whose gradient sums leave a block as plain stores instead of atomics, for a pass
+// that updates nvec vectors over d columns; blocks of a gradient pass at most.
+int32_t general_head_columns(int32_t d, int nvec);
+constexpr int kGeneralGradBlocks = 256;
+inline size_t general_part_floats(int32_t d) {
+  const size_t per_block = 2 * (size_t)d < 16384 ? 2 * (size_t)d : 16384;
+  return kGeneralGradBlocks * per_block;
+}
 
 struct ApplyArgs {
   int32_t d;
@@ -50,6 +63,8 @@ struct ApplyArgs {
   float *bias;
   float *phi_copy;   // optional second destination of the updated Assistant (written even if m == 0)
   float *bias_copy;
+  const float *part;  // per-block sums of the first `head` columns (see GenArgs)
+  int32_t head, nvec, nblk_pass;
   float lambda, lr, lr_a, l2_a;
   int32_t *kept_hist;
   const uint8_t *flags;
