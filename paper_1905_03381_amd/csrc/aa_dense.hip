@@ -365,8 +365,8 @@ __global__ __launch_bounds__(NW * 64)
   if (GRAD && a.t_upd && blockIdx.x == 0 && threadIdx.x == 0) *a.t_snap = *a.t_upd;
 }
 
-constexpr int kFinCols4 = 4;    // 128-bit columns reduced by one finalize block
-constexpr int kFinGroups = 64;  // partial groups per column (256 threads)
+constexpr int kFinCols4 = 8;    // 128-bit columns reduced by one finalize block
+constexpr int kFinGroups = 32;  // partial groups per column (256 threads)
 
 // Sum the block partials in a fixed order and apply the SGD updates; extra
 // blocks compact the keep flags of a pool pass, one tile each.
