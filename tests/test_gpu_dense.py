@@ -624,3 +624,39 @@ def test_profile_hooks_bracket_every_step_of_an_epoch(ws):
     del keepalive
     with pytest.raises(api.AAError):
         api.profile_hooks([None], [pairs[0][1].cuda_event])
+
+
+def test_shrinking_saves_boss_rows_at_equal_objective(ref, ws):
+    """What the method is for (Sections 3.4 and 5): on separable data more and more instances become
+    trivial (zero hinge loss), the Assistant learns to drop them, and the Boss reaches the objective
+    of plain mini-batch SGD (gamma = 1) while stepping on clearly fewer rows."""
+    n, d, P, epochs = 32768, 128, 1024, 6
+    r = rng(301)
+    X = r.standard_normal((n, d)).astype(np.float32)
+    X /= np.linalg.norm(X, axis=1, keepdims=True)
+    w_star = r.standard_normal(d)
+    y = np.where(X @ w_star >= 0, 1.0, -1.0).astype(np.float32)
+    Fh, F, yd = ref.Features.dense(X), dense_features(X), dev(y)
+    lam, lr0, lr_a = 1e-4, 8.0, 1.0
+    perms = [dev(rng(400 + e).permutation(n).astype(np.int32)) for e in range(epochs)]
+    steps = n // P
+    Tt = scalar_dev(0.0)
+
+    def run(gamma):
+        w, phi, b = torch.zeros(d, device="cuda"), torch.zeros(d, device="cuda"), scalar_dev(0.0)
+        tu = torch.zeros(1, dtype=torch.int32, device="cuda")
+        hist = torch.zeros(steps, dtype=torch.int32, device="cuda")
+        kept = []
+        for e in range(epochs):
+            cfg = api.step_config(gamma, lam, lr0, lr_a, 0.0, 42, e * steps, Tt)
+            api.train_epoch(F, yd, perms[e], n, P, w, phi, b, cfg, tu, hist, ws)
+            kept.append(int(host(hist).sum()))
+        return ref.primal_objective(Fh, y, None, n, host(w), lam), kept
+
+    obj_plain, kept_plain = run(1.0)
+    obj_aa, kept_aa = run(0.1)
+    assert kept_plain == [n] * epochs
+    assert abs(obj_aa - obj_plain) < 0.01 * obj_plain          # the same objective value
+    assert sum(kept_aa) < 0.85 * sum(kept_plain)               # on fewer Boss rows
+    assert kept_aa[-1] < 0.75 * n and kept_aa[-1] < kept_aa[0]  # the keep rate keeps falling
+    assert obj_plain < 0.4                                      # and both have trained (start: 1.0)
