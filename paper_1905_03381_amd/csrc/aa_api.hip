@@ -43,7 +43,7 @@ size_t general_acc_bytes(int32_t d) {
 Ws carve(void *ws, size_t grad_bytes, int32_t P, bool epoch_outputs = false) {
   Ws w;
   w.base = static_cast<char *>(ws);
-  w.ctl = reinterpret_cast<int32_t *>(w.base + kWsTickets);
+  w.ctl = reinterpret_cast<int32_t *>(w.base + kWsControl);
   w.blk_cnt = reinterpret_cast<int32_t *>(w.base + kWsBlkCnt);
   w.blk_gb = reinterpret_cast<float *>(w.base + kWsBlkGb);
   size_t off = kWsBody;

@@ -21,7 +21,7 @@ constexpr int kCompactTile = 2048;     // keep flags compacted by one block
 // [.., +8)            scalars
 // then a region sized by the call: gradient partials / accumulators, pool
 // scratch (flags, per-position losses), block offsets.
-constexpr size_t kWsTickets = 0;
+constexpr size_t kWsControl = 0;
 constexpr size_t kWsBlkCnt = 256;
 constexpr size_t kWsBlkGb = kWsBlkCnt + sizeof(int32_t) * kMaxBlocks;
 constexpr size_t kWsScalars = kWsBlkGb + sizeof(float) * kMaxBlocks;
