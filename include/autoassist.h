@@ -259,6 +259,17 @@ int32_t aa_train_epoch(const aa_features *F, const float *y, const int32_t *perm
                        int32_t *kept_ids_hist, float *loss_hist, void *ws, size_t ws_bytes,
                        void *stream);
 
+/* One epoch of hard-threshold shrinking steps: aa_sk_step on pool t =
+ * perm[t*P : min((t+1)*P, n_perm)] for every t, with the step size
+ * lr_t = lr0 / sqrt(t_upd) kept on the device as in aa_train_epoch (t_upd ==
+ * NULL: lr0 throughout), kept counts in kept_hist[t], and the kept ids and
+ * losses of step t in kept_ids_hist[t*P ..] / loss_hist[t*P ..] (each may be
+ * NULL).  T: device scalar.  Needs the fast dense layout when t_upd is given. */
+int32_t aa_sk_epoch(const aa_features *F, const float *y, const int32_t *perm, int64_t n_perm,
+                    int32_t P, float *w, const float *T, float lambda, float lr0, int32_t *t_upd,
+                    int32_t *kept_hist, int32_t *kept_ids_hist, float *loss_hist, void *ws,
+                    size_t ws_bytes, void *stream);
+
 /* ---- The asynchronous Boss / Assistant schedule of Section 5.3 in a deterministic
  * form, on two streams.  Pool s is perm[s*P : min((s+1)*P, n_perm)].  The
  * generator (stream_gen) makes batch s -- score, keep draw with Philox step

@@ -23,7 +23,7 @@ SYMBOLS = [
     "aa_assistant_score", "aa_shrink", "aa_score_shrink", "aa_shrink_threshold", "aa_gather",
     "aa_gather_csr", "aa_svm_sgd_step", "aa_assistant_update", "aa_boss_assistant_step",
     "aa_fused_step", "aa_sk_step", "aa_train_epoch", "aa_threshold_update", "aa_bucket_batches",
-    "aa_pipeline_workspace_bytes", "aa_train_epoch_stale",
+    "aa_pipeline_workspace_bytes", "aa_train_epoch_stale", "aa_sk_epoch",
 ]
 
 
@@ -76,6 +76,7 @@ def lib():
         "aa_fused_step": (i32, [FP, vp, vp, i32, vp, vp, vp, CP, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
         "aa_sk_step": (i32, [FP, vp, vp, i32, vp, vp, f32, f32, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
         "aa_train_epoch": (i32, [FP, vp, vp, i64, i32, vp, vp, vp, CP, vp, vp, vp, vp, vp, sz, vp]),
+        "aa_sk_epoch": (i32, [FP, vp, vp, i64, i32, vp, vp, f32, f32, vp, vp, vp, vp, vp, sz, vp]),
         "aa_threshold_update": (i32, [vp, vp, i32, f32, vp, vp, vp]),
         "aa_pipeline_workspace_bytes": (sz, [i32, i32, i32]),
         "aa_train_epoch_stale": (i32, [FP, vp, vp, i64, i32, i32, vp, vp, vp, CP, vp, vp, vp, vp, sz, vp, vp]),
@@ -254,6 +255,13 @@ def train_epoch(F, y, perm, n_perm, P, w, phi, bias, cfg, t_upd, kept_hist, ws, 
                                 _ptr(bias), C.byref(cfg), _ptr(t_upd), _ptr(kept_hist),
                                 _ptr(kept_ids_hist), _ptr(loss_hist), ws.ptr, ws.bytes, _stream()),
            "aa_train_epoch")
+
+
+def sk_epoch(F, y, perm, n_perm, P, w, T, lam, lr0, t_upd, kept_hist, ws, kept_ids_hist=None,
+             loss_hist=None):
+    _check(lib().aa_sk_epoch(F.ref(), _ptr(y), _ptr(perm), n_perm, P, _ptr(w), _ptr(T), lam, lr0,
+                             _ptr(t_upd), _ptr(kept_hist), _ptr(kept_ids_hist), _ptr(loss_hist),
+                             ws.ptr, ws.bytes, _stream()), "aa_sk_epoch")
 
 
 def train_epoch_stale(F, y, perm, n_perm, P, staleness, w, phi, bias, cfg, t_upd, kept_hist,

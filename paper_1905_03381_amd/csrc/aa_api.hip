@@ -372,10 +372,11 @@ int32_t fused_step_impl(const aa_features *F, const float *y, const int32_t *idx
                         uint64_t step, float *logit, float *prob, uint8_t *keep,
                         int32_t *kept_pos, int32_t *kept_ids, float *loss, int32_t *kept_count,
                         int32_t *t_upd, int32_t *kept_hist, EpochCtl *ep, void *ws_ptr,
-                        size_t ws_bytes, hipStream_t st) {
+                        size_t ws_bytes, hipStream_t st, bool hard = false) {
+  // hard: keep by the candidate's own loss against *cfg->T, no Assistant (phi, bias unused)
   PassSpec s{};
   s.F = F;
-  s.mode = kPool | kSvm | kAssist;
+  s.mode = hard ? (kPool | kSvm | kHard) : (kPool | kSvm | kAssist);
   s.y = y;
   s.rows = idx;
   s.count_max = ep ? ep->P_layout : P;  // sizes the gradient partials for the whole epoch
@@ -386,7 +387,7 @@ int32_t fused_step_impl(const aa_features *F, const float *y, const int32_t *idx
   s.gamma = cfg->gamma;
   s.seed = cfg->seed;
   s.step = step;
-  s.do_keep = 1;
+  s.do_keep = hard ? 0 : 1;
   s.logit = logit;
   s.prob = prob;
   s.t_upd = t_upd;
@@ -399,7 +400,7 @@ int32_t fused_step_impl(const aa_features *F, const float *y, const int32_t *idx
   float *loss_pool = ws.loss_pool;
   s.flags = keep ? keep : ws.flags;
   if (ep) {  // the batch of each step is assembled in the workspace (or the caller's history)
-    s.prob = ws.prob;
+    s.prob = hard ? nullptr : ws.prob;
     kept_pos = ws.kept_pos;
     kept_ids = ep->ids_dst ? ep->ids_dst : ws.kept_ids;
     loss = ep->loss_dst ? ep->loss_dst : ws.loss;
@@ -876,16 +877,17 @@ int32_t aa_bucket_batches(const int32_t *len_s, const int32_t *len_t, const int3
   return hip_status(launch_bucket_batches(a, as_stream(stream)));
 }
 
-int32_t aa_train_epoch(const aa_features *F, const float *y, const int32_t *perm, int64_t n_perm,
-                       int32_t P, float *w, float *phi, float *bias, const aa_step_config *cfg,
-                       int32_t *t_upd, int32_t *kept_hist, int32_t *kept_ids_hist,
-                       float *loss_hist, void *ws, size_t ws_bytes, void *stream) {
+// The epoch loop of aa_train_epoch and aa_sk_epoch (hard: no Assistant, keep by own loss).
+static int32_t epoch_impl(const aa_features *F, const float *y, const int32_t *perm, int64_t n_perm,
+                          int32_t P, float *w, float *phi, float *bias, const aa_step_config *cfg,
+                          int32_t *t_upd, int32_t *kept_hist, int32_t *kept_ids_hist,
+                          float *loss_hist, void *ws, size_t ws_bytes, void *stream, bool hard) {
   if (P <= 0 || n_perm < 0) return AA_ERR_SHAPE;
   if (n_perm == 0) return AA_OK;
   if (int32_t rc = check_features(F)) return rc;
-  if (!y || !w || !phi || !cfg || !cfg->T || !perm) return AA_ERR_NULL;
+  if (!y || !w || (!hard && !phi) || !cfg || !cfg->T || !perm) return AA_ERR_NULL;
   const int64_t steps = (n_perm + P - 1) / P;
-  const int mode = kPool | kSvm | kAssist;
+  const int mode = hard ? (kPool | kSvm | kHard) : (kPool | kSvm | kAssist);
   CompactArgs pending{};
   bool have_pending = false;
   for (int64_t t = 0; t < steps; ++t) {
@@ -909,12 +911,32 @@ int32_t aa_train_epoch(const aa_features *F, const float *y, const int32_t *perm
     const int32_t rc = fused_step_impl(F, y, perm + lo, Pt, w, phi, bias, cfg, cfg->step + t,
                                        nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
                                        nullptr, t_upd, kept_hist ? kept_hist + t : nullptr, &ep, ws,
-                                       ws_bytes, as_stream(stream));
+                                       ws_bytes, as_stream(stream), hard);
     if (rc != AA_OK) return rc;
     have_pending = ep.did_defer;
     pending = mine;
   }
   return AA_OK;
+}
+
+int32_t aa_train_epoch(const aa_features *F, const float *y, const int32_t *perm, int64_t n_perm,
+                       int32_t P, float *w, float *phi, float *bias, const aa_step_config *cfg,
+                       int32_t *t_upd, int32_t *kept_hist, int32_t *kept_ids_hist,
+                       float *loss_hist, void *ws, size_t ws_bytes, void *stream) {
+  return epoch_impl(F, y, perm, n_perm, P, w, phi, bias, cfg, t_upd, kept_hist, kept_ids_hist,
+                    loss_hist, ws, ws_bytes, stream, false);
+}
+
+int32_t aa_sk_epoch(const aa_features *F, const float *y, const int32_t *perm, int64_t n_perm,
+                    int32_t P, float *w, const float *T, float lambda, float lr0, int32_t *t_upd,
+                    int32_t *kept_hist, int32_t *kept_ids_hist, float *loss_hist, void *ws,
+                    size_t ws_bytes, void *stream) {
+  aa_step_config cfg{};
+  cfg.lambda = lambda;
+  cfg.lr = lr0;
+  cfg.T = T;
+  return epoch_impl(F, y, perm, n_perm, P, w, nullptr, nullptr, &cfg, t_upd, kept_hist, kept_ids_hist,
+                    loss_hist, ws, ws_bytes, stream, true);
 }
 
 size_t aa_pipeline_workspace_bytes(int32_t P_max, int32_t d_max, int32_t staleness) {

@@ -220,26 +220,17 @@ def sk(a, torch, api, synth):
     ws = api.Workspace(P, d)
     w = torch.zeros(d, device="cuda")
     T = torch.zeros(1, device="cuda")
-    cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
-    pos = torch.zeros(P, dtype=torch.int32, device="cuda")
-    ids = torch.zeros(P, dtype=torch.int32, device="cuda")
-    loss = torch.zeros(P, device="cuda")
-    steps = n // P
+    steps = (n + P - 1) // P
+    tu = torch.zeros(1, dtype=torch.int32, device="cuda")
     kept = torch.zeros(steps, dtype=torch.int32, device="cuda")
 
-    def epoch(record=False):
-        for t in range(steps):
-            api.sk_step(F, yd, perm[t * P:(t + 1) * P], P, w, T, 1e-4, 1.0 / np.sqrt(t + 1.0), None,
-                        None, pos, ids, loss, cnt, ws)
-            if record:
-                kept[t:t + 1].copy_(cnt)
+    def epoch():
+        api.sk_epoch(F, yd, perm, n, P, w, T, 1e-4, 256.0, tu, kept, ws)
 
-    us = _timed(torch, epoch, a.repeats, lambda: w.zero_()) / steps
-    w.zero_()
-    epoch(record=True)                       # untimed: the keep rate of the same epoch
+    us = _timed(torch, epoch, a.repeats, lambda: (w.zero_(), tu.zero_())) / steps
     return {"workload": f"hard-threshold shrinking, dense n={n} d={d}, pool {P}",
-            "candidates_per_s": P / us * 1e6, "keep_rate": float(kept.sum().item()) / (steps * P),
-            "stages": [_stage("SK step (losses, keep, compact, SVM step)", us, P * (4 * d + 4 + 4 + 1 + 4))]}
+            "candidates_per_s": n / steps / us * 1e6, "keep_rate": float(kept.sum().item()) / n,
+            "stages": [_stage("SK step (losses, keep, compact, SVM step)", us, n / steps * (4 * d + 4 + 4 + 1 + 4))]}
 
 
 def stale(a, torch, api, synth):
