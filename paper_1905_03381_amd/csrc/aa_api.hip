@@ -34,10 +34,13 @@ struct Ws {
   size_t total;
 };
 
-// General kernels: 16 scalars, the two atomic accumulators, then the per-block sums of the
-// first columns.
-size_t general_acc_bytes(int32_t d) {
-  return (16 + 2 * (size_t)d + general_part_floats(d)) * sizeof(float);
+// General kernels: a header (scalars, bin fill counts), the two dense accumulators, the
+// per-block sums of the first columns, then the record bins of the other columns.
+size_t general_bins_offset(int32_t d) {
+  return align_up((kGeneralHeader + 2 * (size_t)d + general_part_floats(d)) * sizeof(float), 256);
+}
+size_t general_acc_bytes(int32_t d, int32_t count_max) {
+  return general_bins_offset(d) + general_record_capacity(count_max) * sizeof(TailRecord);
 }
 
 Ws carve(void *ws, size_t grad_bytes, int32_t P, bool epoch_outputs = false) {
@@ -155,7 +158,7 @@ size_t grad_bytes_for(const PassSpec &s) {
   if (use_fast(s))
     return (size_t)dense_pass_blocks(s.F->d, s.count_max, s.mode) * nvec *
            dense_d_pad(s.F->d) * sizeof(float);
-  return general_acc_bytes(s.F->d);
+  return general_acc_bytes(s.F->d, s.count_max);
 }
 
 // Launch the pass (and, for the general family, the accumulator clear before it).
@@ -200,7 +203,7 @@ hipError_t run_pass(const PassSpec &s, const Ws &ws, int32_t *nblk_out, hipStrea
   const bool csr = s.F->layout == AA_CSR;
   float *acc = reinterpret_cast<float *>(ws.grad);
   if (s.mode & (kSvm | kAssist)) {
-    hipError_t e = launch_zero_f32(acc, 16 + 2 * (size_t)s.F->d, st);
+    hipError_t e = launch_zero_f32(acc, kGeneralHeader + 2 * (size_t)s.F->d, st);
     if (e != hipSuccess) return e;
   }
   GenArgs a{};
@@ -227,12 +230,16 @@ hipError_t run_pass(const PassSpec &s, const Ws &ws, int32_t *nblk_out, hipStrea
   a.flags = s.flags;
   a.loss_out = s.loss_out;
   a.loss_in = s.loss_in;
-  a.acc_cnt = reinterpret_cast<int32_t *>(acc);
-  a.acc_gb = acc + 1;
-  a.acc_w = acc + 16;
-  a.acc_p = acc + 16 + s.F->d;
-  a.part = acc + 16 + 2 * (size_t)s.F->d;
-  a.head = general_head_columns(s.F->d, ((s.mode & kSvm) ? 1 : 0) + ((s.mode & kAssist) ? 1 : 0));
+  a.blk_cnt = ws.blk_cnt;
+  a.blk_gb = ws.blk_gb;
+  const int nvec = ((s.mode & kSvm) ? 1 : 0) + ((s.mode & kAssist) ? 1 : 0);
+  a.acc_w = acc + kGeneralHeader;
+  a.acc_p = acc + kGeneralHeader + s.F->d;
+  a.part = acc + kGeneralHeader + 2 * (size_t)s.F->d;
+  a.head = general_head_columns(s.F->d, nvec);
+  a.bin_fill = reinterpret_cast<int32_t *>(acc) + 16;
+  a.bins = reinterpret_cast<TailRecord *>(ws.grad + general_bins_offset(s.F->d));
+  a.plan = general_bin_plan(s.F->d, a.head, nvec, s.count_max);
   const int32_t nblk = general_pass_blocks(s.count_max, csr, s.mode);
   *nblk_out = nblk;
   HookScope hook(st);
@@ -296,13 +303,16 @@ hipError_t run_update(const PassSpec &s, const UpdateSpec &u, const Ws &ws, int3
   const float *acc = reinterpret_cast<const float *>(ws.grad);
   ApplyArgs p{};
   p.d = s.F->d;
-  p.acc_cnt = reinterpret_cast<const int32_t *>(acc);
-  p.acc_gb = acc + 1;
-  p.acc_w = acc + 16;
-  p.acc_p = acc + 16 + s.F->d;
-  p.part = acc + 16 + 2 * (size_t)s.F->d;
+  p.blk_cnt = ws.blk_cnt;
+  p.blk_gb = ws.blk_gb;
+  p.acc_w = acc + kGeneralHeader;
+  p.acc_p = acc + kGeneralHeader + s.F->d;
+  p.part = acc + kGeneralHeader + 2 * (size_t)s.F->d;
   p.nvec = ((s.mode & kSvm) ? 1 : 0) + ((s.mode & kAssist) ? 1 : 0);
   p.head = general_head_columns(s.F->d, p.nvec);
+  p.bin_fill = reinterpret_cast<const int32_t *>(acc) + 16;
+  p.bins = reinterpret_cast<const TailRecord *>(ws.grad + general_bins_offset(s.F->d));
+  p.plan = general_bin_plan(s.F->d, p.head, p.nvec, s.count_max);
   p.nblk_pass = nblk;
   p.m_dev = pool ? nullptr : s.m_dev;
   p.m_max = s.count_max;
@@ -505,7 +515,7 @@ size_t aa_workspace_bytes(int32_t P_max, int32_t d_max) {
   // d <= 2048, the general kernels dense accumulators
   const int32_t d_fast = d_max < kFastDenseMaxD ? d_max : kFastDenseMaxD;
   size_t grad = (size_t)kMaxBlocks * 2 * dense_d_pad(d_fast) * sizeof(float);
-  if (general_acc_bytes(d_max) > grad) grad = general_acc_bytes(d_max);
+  if (general_acc_bytes(d_max, P_max) > grad) grad = general_acc_bytes(d_max, P_max);
   return carve(nullptr, grad, P_max, true).total;
 }
 

@@ -1,19 +1,19 @@
 // General row passes: CSR rows, and dense rows the register-resident kernels
 // cannot take (d > 2048, d % 4 != 0, unaligned).  A group of GL lanes walks the
 // stored entries of a row; phi and w are read through the caches (they are the
-// only reused data); gradient sums go into dense fp32 accumulators that a second
-// kernel folds into the model.  Every block first sums what it can in an LDS table
-// of its own -- the first columns have a slot each (frequency-ranked column ids,
-// the usual layout of bag-of-words data, put the hot columns there), any other
-// column claims a slot by hash, first come first served.  At the end the first
-// columns leave the block as plain stores into a per-block array that the second
-// kernel sums (nearly every block touches nearly every one of them, so atomics
-// would buy nothing), the hashed slots as one atomic each.
-// In bag-of-words data a few hot columns take most of the entries, and device-wide
-// atomics on one address run one after the other, about 13 ns each on MI355X: the
-// table turns the thousands of adds a block would send to a hot column into one.
-// Columns that find their slots taken add to HBM directly, which the chip
-// sustains at about 20 G atomics/s on scattered addresses.
+// only reused data); a second kernel folds the gradient sums into the model.
+// Device-wide fp32 atomics are what such a pass must avoid on MI355X: about 20 G/s
+// on scattered addresses, and adds to one address run one after the other, about
+// 13 ns each, while bag-of-words data puts most entries on a few hot columns.  So:
+//  * the first columns (frequency-ranked column ids, the usual layout of such data,
+//    put the hot ones there) have a slot each in an LDS table of the block and leave
+//    it as plain stores into a per-block array that the second kernel sums;
+//  * entries of any other column are collected as records in LDS and written, sorted
+//    by column bin, into per-bin arrays; the block that owns a bin in the second
+//    kernel sums its records in LDS.  One integer atomic per block, bin and flush
+//    reserves the space;
+//  * only what does not fit (records beyond the LDS buffer or a bin's capacity, or
+//    more columns than the bins can cover) is added to dense accumulators in HBM.
 #include "aa_compact.hpp"
 #include "aa_general.hpp"
 
@@ -28,12 +28,73 @@ __device__ __forceinline__ float gsum(float v) {
   return v;
 }
 
-// Per-block LDS table: kDirect* slots for columns 0..kDirect*-1, then kHashed* slots
-// claimed by hash (a column tag each); one sum per slot and updated vector.
-// 112 KB with both vectors, 128 KB with one: one block of 16 waves per compute unit.
-constexpr int kDirectTwoVec = 8192, kHashedTwoVec = 4096;
-constexpr int kDirectOneVec = 16384, kHashedOneVec = 8192;
+// Per-block LDS: kDirect* slots for columns 0..kDirect*-1 (one sum per updated vector), then a
+// buffer of kRecords* records for entries of other columns.  About 138 KB with both vectors,
+// 130 KB with one: one block of 16 waves per compute unit.
+constexpr int kDirectTwoVec = 8192, kRecordsTwoVec = 6144;
+constexpr int kDirectOneVec = 16384, kRecordsOneVec = 8192;
 constexpr int kGradThreads = 1024, kPoolThreads = 256;
+
+__device__ __forceinline__ int bin_of(int c, int head, const BinPlan &p) {
+  return ((c - head) >> 4) & (p.nb - 1);
+}
+
+// Adds one entry's terms to the dense accumulators in HBM (the path of last resort).
+template <bool SVM, bool ASSIST>
+__device__ __forceinline__ void add_global(const GenArgs &a, int c, float ta, float tb) {
+  if (SVM && ta != 0.f) unsafeAtomicAdd(a.acc_w + c, ta);
+  if (ASSIST) {
+    const float t = SVM ? tb : ta;
+    if (t != 0.f) unsafeAtomicAdd(a.acc_p + c, t);
+  }
+}
+
+// Empties the block's record buffer into the bins.  Whole block; the caller has put a barrier
+// between the last append and this call.  R records at most, R / 1024 per thread.
+template <int R, bool SVM, bool ASSIST>
+__device__ void flush_records(const GenArgs &a, int head, const int *s_rc, const float *s_ra,
+                              const float *s_rb, int *s_nrec, int *s_hist, int *s_base) {
+  constexpr int kPer = R / kGradThreads;
+  const int n = min(*s_nrec, R);
+  const int nb = a.plan.nb;
+  for (int t = threadIdx.x; t < nb; t += blockDim.x) s_hist[t] = 0;
+  __syncthreads();
+  int rank[kPer];
+#pragma unroll
+  for (int q = 0; q < kPer; ++q) {
+    const int i = threadIdx.x + q * kGradThreads;
+    rank[q] = i < n ? atomicAdd(s_hist + bin_of(s_rc[i], head, a.plan), 1) : 0;
+  }
+  __syncthreads();
+  for (int t = threadIdx.x; t < nb; t += blockDim.x) {
+    const int h = s_hist[t];
+    s_base[t] = h > 0 ? atomicAdd(a.bin_fill + t, h) : 0;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < kPer; ++q) {
+    const int i = threadIdx.x + q * kGradThreads;
+    if (i < n) {
+      const int c = s_rc[i];
+      const int bin = bin_of(c, head, a.plan);
+      const int pos = s_base[bin] + rank[q];
+      const float ta = s_ra[i], tb = (SVM && ASSIST) ? s_rb[i] : 0.f;
+      if (pos < a.plan.cap) {
+        TailRecord r;
+        r.col = c;
+        r.a = ta;
+        r.b = tb;
+        r.pad = 0;
+        a.bins[(size_t)bin * a.plan.cap + pos] = r;
+      } else {
+        add_global<SVM, ASSIST>(a, c, ta, tb);
+      }
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) *s_nrec = 0;
+  __syncthreads();
+}
 
 template <int GL, int MODE, bool CSR>
 __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
@@ -46,14 +107,20 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
   constexpr int G = kWave / GL;
   constexpr int NVEC = (SVM ? 1 : 0) + (ASSIST ? 1 : 0);
   constexpr int D = NVEC == 2 ? kDirectTwoVec : kDirectOneVec;  // slots 0..D-1: column = slot
-  constexpr int H = NVEC == 2 ? kHashedTwoVec : kHashedOneVec;  // slots D..D+H-1: by hash
-  __shared__ int s_tag[GRAD ? H : 1];
-  __shared__ float s_sum[GRAD ? NVEC * (D + H) : 1];
-  float *const s_w = s_sum, *const s_p = s_sum + (SVM ? D + H : 0);
-  const int salt = (int)((blockIdx.x * 0x9E3779B1u) >> 19) & (H - 1);
+  constexpr int R = NVEC == 2 ? kRecordsTwoVec : kRecordsOneVec;  // record buffer
+  __shared__ float s_sum[GRAD ? NVEC * D : 1];
+  __shared__ int s_rc[GRAD ? R : 1];
+  __shared__ float s_rt[GRAD ? NVEC * R : 1];
+  __shared__ int s_hist[GRAD ? kMaxBins : 1], s_base[GRAD ? kMaxBins : 1];
+  __shared__ int s_nrec;
+  __shared__ int s_cnt[16];
+  __shared__ float s_gb[16];
+  float *const s_w = s_sum, *const s_p = s_sum + (SVM ? D : 0);
+  float *const s_ra = s_rt, *const s_rb = s_rt + (NVEC == 2 ? R : 0);
+  const bool binned = GRAD && a.plan.nb > 0;
   if (GRAD) {
-    for (int k = threadIdx.x; k < H; k += blockDim.x) s_tag[k] = -1;
-    for (int k = threadIdx.x; k < NVEC * (D + H); k += blockDim.x) s_sum[k] = 0.f;
+    for (int k = threadIdx.x; k < NVEC * D; k += blockDim.x) s_sum[k] = 0.f;
+    if (threadIdx.x == 0) s_nrec = 0;
     __syncthreads();
   }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
@@ -71,8 +138,11 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
   float gb = 0.f;
   int kept = 0;
 
-  for (int base = lo; base < hi; base += kWave) {
-    const int cnt = min(kWave, hi - base);
+  // every wave of the grid makes the same number of rounds, so that a block can meet between them
+  const int rounds = (per + (rem > 0 ? 1 : 0) + kWave - 1) / kWave;
+  for (int round = 0; round < rounds; ++round) {
+    const int base = lo + round * kWave;
+    const int cnt = max(0, min(kWave, hi - base));
     const int j_l = base + lane;
     int row_l = 0;
     long long e0_l = 0;
@@ -157,58 +227,66 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
           if (sub == 0) gb += resid;
         }
         if (sub == 0 && keep) kept += 1;
-        if (cw != 0.f || resid != 0.f) {
-          for (int e = sub; e < len; e += GL) {
-            const int c = CSR ? a.col[e0 + e] : e;
-            const float xv = CSR ? (a.val ? a.val[e0 + e] : 1.f) : a.x[e0 + e];
-            int slot = -1;
-            if (c < D) {
-              slot = c;
-            } else {  // claim a slot for this column, or find the one it already holds
-              int h = (c ^ (c >> 13) ^ salt) & (H - 1);
-              int old = atomicCAS(s_tag + h, -1, c);
-              if (old == -1 || old == c) {
-                slot = D + h;
-              } else {
-                h = (h + 1) & (H - 1);
-                old = atomicCAS(s_tag + h, -1, c);
-                if (old == -1 || old == c) slot = D + h;
+        // second walk: the wave's groups step together, so that lanes with an entry outside the
+        // table can reserve their places in the record buffer with one LDS atomic per step
+        const bool contrib = cw != 0.f || resid != 0.f;
+        int steps_len = contrib ? len : 0;
+#pragma unroll
+        for (int off = GL; off < kWave; off <<= 1)
+          steps_len = max(steps_len, __shfl_xor(steps_len, off, kWave));
+        for (int eb = 0; eb < steps_len; eb += GL) {
+          const int e = eb + sub;
+          const bool active = contrib && e < len;
+          int c = 0;
+          float xv = 0.f;
+          if (active) {
+            c = CSR ? a.col[e0 + e] : e;
+            xv = CSR ? (a.val ? a.val[e0 + e] : 1.f) : a.x[e0 + e];
+          }
+          const float ta = SVM ? cw * xv : resid * xv, tb = resid * xv;
+          if (active && c < D) {
+            if (SVM && cw != 0.f) unsafeAtomicAdd(s_w + c, cw * xv);
+            if (ASSIST && resid != 0.f) unsafeAtomicAdd(s_p + c, resid * xv);
+          }
+          const bool tail = active && c >= D;
+          if (binned) {
+            const unsigned long long mask = __ballot(tail);
+            if (mask != 0ull) {
+              const int leader = __ffsll((long long)mask) - 1;
+              int first = 0;
+              if (lane == leader) first = atomicAdd(&s_nrec, __popcll(mask));
+              first = __shfl(first, leader, kWave);
+              if (tail) {
+                const int pos = first + (int)__builtin_amdgcn_mbcnt_hi(
+                                            (uint32_t)(mask >> 32),
+                                            __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+                if (pos < R) {
+                  s_rc[pos] = c;
+                  s_ra[pos] = ta;
+                  if (NVEC == 2) s_rb[pos] = tb;
+                } else {
+                  add_global<SVM, ASSIST>(a, c, ta, tb);
+                }
               }
             }
-            if (slot >= 0) {  // LDS and HBM atomics are different instructions: branch, not select
-              if (SVM && cw != 0.f) unsafeAtomicAdd(s_w + slot, cw * xv);
-              if (ASSIST && resid != 0.f) unsafeAtomicAdd(s_p + slot, resid * xv);
-            } else {
-              if (SVM && cw != 0.f) unsafeAtomicAdd(a.acc_w + c, cw * xv);
-              if (ASSIST && resid != 0.f) unsafeAtomicAdd(a.acc_p + c, resid * xv);
-            }
+          } else if (tail) {
+            add_global<SVM, ASSIST>(a, c, ta, tb);
           }
         }
       }
     }
+    if (GRAD && round + 1 < rounds) {  // a buffer more than half full is emptied between rounds
+      __syncthreads();
+      const int fill = s_nrec;
+      __syncthreads();
+      if (binned && fill > R / 2)
+        flush_records<R, SVM, ASSIST>(a, D, s_rc, s_ra, s_rb, &s_nrec, s_hist, s_base);
+    }
   }
 
   if (GRAD) {
-    __syncthreads();
-    // the first columns: this block's sums, zeros included, as plain stores
-    float *const mine = a.part + (size_t)blockIdx.x * NVEC * a.head;
-    for (int k = threadIdx.x; k < a.head; k += blockDim.x) {
-      if (SVM) mine[k] = s_w[k];
-      if (ASSIST) mine[(SVM ? a.head : 0) + k] = s_p[k];
-    }
-    for (int k = D + threadIdx.x; k < D + H; k += blockDim.x) {
-      const int c = s_tag[k - D];
-      if (c < 0) continue;
-      if (SVM) {
-        const float v = s_w[k];
-        if (v != 0.f) unsafeAtomicAdd(a.acc_w + c, v);
-      }
-      if (ASSIST) {
-        const float v = s_p[k];
-        if (v != 0.f) unsafeAtomicAdd(a.acc_p + c, v);
-      }
-    }
-    // scalars[0] = kept count (int), scalars[1] = bias gradient (float bits via atomics)
+    // kept count and bias-gradient sum of the block: wave sums, then wave order (one store per
+    // block; thousands of waves adding to one address would run one after the other)
     int kw = kept;
     float gbw = gb;
 #pragma unroll
@@ -217,9 +295,27 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
       gbw += __shfl_xor(gbw, off, kWave);
     }
     if (lane == 0) {
-      if (kw) atomicAdd(a.acc_cnt, kw);
-      if (ASSIST && gbw != 0.f) unsafeAtomicAdd(a.acc_gb, gbw);
+      s_cnt[wave] = kw;
+      s_gb[wave] = gbw;
     }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      int kb = 0;
+      float gbb = 0.f;
+      for (int i = 0; i < nw; ++i) {
+        kb += s_cnt[i];
+        gbb += s_gb[i];
+      }
+      a.blk_cnt[blockIdx.x] = kb;
+      a.blk_gb[blockIdx.x] = gbb;
+    }
+    // the first columns: this block's sums, zeros included, as plain stores
+    float *const mine = a.part + (size_t)blockIdx.x * NVEC * a.head;
+    for (int k = threadIdx.x; k < a.head; k += blockDim.x) {
+      if (SVM) mine[k] = s_w[k];
+      if (ASSIST) mine[(SVM ? a.head : 0) + k] = s_p[k];
+    }
+    if (binned) flush_records<R, SVM, ASSIST>(a, D, s_rc, s_ra, s_rb, &s_nrec, s_hist, s_base);
   }
 }
 
@@ -231,13 +327,19 @@ __global__ __launch_bounds__(256) void k_zero_f32(float *p, size_t count) {
 
 // Folds the gradient sums into the model.  Blocks [0, nh): 16 of the first `head` columns each,
 // 16 threads per column adding the per-block sums of the pass in a fixed order; blocks after
-// them: the other columns, whose sums are the atomic accumulators; then one block per
-// compaction tile.
+// them: the other columns -- one block per bin, which adds the bin's records up in LDS (plus
+// whatever overflowed into the dense accumulators), or with no bins a strided share of the
+// accumulators; then one block per compaction tile.  Every block adds up the per-block kept
+// counts of the pass for itself.
 constexpr int kHeadCols = 16;
+static_assert(kGeneralGradBlocks <= 256, "k_apply_general reads one per-block count per thread");
 
 __global__ __launch_bounds__(256) void k_apply_general(const ApplyArgs a, int nh, int nrest) {
   __shared__ int s_int[40];
   __shared__ float s_part[2][16][kHeadCols];
+  __shared__ int s_m[4];
+  __shared__ float s_g[4];
+  __shared__ float s_bin[kBinColsMax];
   if ((int)blockIdx.x >= nh + nrest) {
     CompactArgs c;
     c.flags = a.flags;
@@ -252,7 +354,24 @@ __global__ __launch_bounds__(256) void k_apply_general(const ApplyArgs a, int nh
     tile_compact(c, (int)blockIdx.x - nh - nrest, s_int);
     return;
   }
-  const int m = a.m_dev ? min(max(*a.m_dev, 0), a.m_max) : *a.acc_cnt;
+  {  // nblk_pass <= blockDim.x: one per-block count (and bias-gradient sum) per thread
+    const int t = threadIdx.x;
+    int cnt = t < a.nblk_pass ? a.blk_cnt[t] : 0;
+    float gbs = (t < a.nblk_pass && a.phi && a.bias) ? a.blk_gb[t] : 0.f;
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+      cnt += __shfl_xor(cnt, off, kWave);
+      gbs += __shfl_xor(gbs, off, kWave);
+    }
+    if ((t & 63) == 0) {
+      s_m[t >> 6] = cnt;
+      s_g[t >> 6] = gbs;
+    }
+    __syncthreads();
+  }
+  const int m_pass = s_m[0] + s_m[1] + s_m[2] + s_m[3];
+  const float gb_pass = (s_g[0] + s_g[1]) + (s_g[2] + s_g[3]);
+  const int m = a.m_dev ? min(max(*a.m_dev, 0), a.m_max) : m_pass;
   if (blockIdx.x == 0 && threadIdx.x == 0 && a.kept_hist) *a.kept_hist = m;
   const float inv_m = m > 0 ? 1.f / (float)m : 0.f;
   const float shrink = 1.f - a.lr * a.lambda, scale = a.lr * inv_m;
@@ -294,13 +413,34 @@ __global__ __launch_bounds__(256) void k_apply_general(const ApplyArgs a, int nh
       }
       fold(k, gw, gp);
     }
+  } else if (a.plan.nb > 0) {  // nrest == nb: this block owns a bin
+    const int bin = (int)blockIdx.x - nh, cols = a.plan.cols;
+    float *const s_a = s_bin, *const s_b = s_bin + cols;
+    for (int k = threadIdx.x; k < a.nvec * cols; k += blockDim.x) s_bin[k] = 0.f;
+    __syncthreads();
+    const int n = m > 0 ? min(a.bin_fill[bin], a.plan.cap) : 0;
+    const TailRecord *rec = a.bins + (size_t)bin * a.plan.cap;
+    for (int i = threadIdx.x; i < n; i += blockDim.x) {
+      const TailRecord r = rec[i];
+      const int rel = r.col - a.head;
+      const int k = (((rel >> 4) >> a.plan.nb_log2) << 4) | (rel & 15);
+      if (r.a != 0.f) unsafeAtomicAdd(s_a + k, r.a);
+      if (a.nvec == 2 && r.b != 0.f) unsafeAtomicAdd(s_b + k, r.b);
+    }
+    __syncthreads();
+    for (int k = threadIdx.x; k < cols; k += blockDim.x) {
+      const int col = a.head + (((((k >> 4) << a.plan.nb_log2) | bin) << 4) | (k & 15));
+      if (col >= a.d) continue;
+      const float va = s_a[k], vb = a.nvec == 2 ? s_b[k] : va;
+      fold(col, a.w ? a.acc_w[col] + va : 0.f, a.phi ? a.acc_p[col] + vb : 0.f);
+    }
   } else {
     for (int k = a.head + ((int)blockIdx.x - nh) * blockDim.x + threadIdx.x; k < a.d;
          k += nrest * blockDim.x)
       fold(k, a.w ? a.acc_w[k] : 0.f, a.phi ? a.acc_p[k] : 0.f);
   }
   if (blockIdx.x == 0 && threadIdx.x == 0 && a.phi && a.bias) {
-    const float bn = m > 0 ? *a.bias - a.lr_a * (*a.acc_gb * inv_m) : *a.bias;
+    const float bn = m > 0 ? *a.bias - a.lr_a * (gb_pass * inv_m) : *a.bias;
     if (m > 0) *a.bias = bn;
     if (a.bias_copy) *a.bias_copy = bn;
   }
@@ -373,6 +513,7 @@ hipError_t launch_general_apply(const ApplyArgs &a, hipStream_t st) {
   int nrest = (a.d - a.head + 1023) / 1024;
   if (nrest > 1024) nrest = 1024;
   if (nrest < 0) nrest = 0;
+  if (a.plan.nb > 0) nrest = a.plan.nb;
   if (nh + nrest < 1) nrest = 1;
   hipLaunchKernelGGL(k_apply_general, dim3(nh + nrest + (a.flags ? compact_tiles(a.P) : 0)), dim3(256),
                      0, st, a, nh, nrest);

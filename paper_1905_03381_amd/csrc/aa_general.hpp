@@ -6,6 +6,44 @@
 
 namespace aa {
 
+// One stored entry of a kept row whose column has no slot in the block's LDS table:
+// its column and its terms of the (up to two) gradient sums.
+struct __attribute__((aligned(16))) TailRecord {
+  int32_t col;
+  float a, b;  // two updated vectors: a -> w, b -> phi; one: a -> that vector
+  int32_t pad;
+};
+
+// Columns from `head` on are dealt to nb bins (a power of two, 0: no binning) in groups of 16:
+// group g = (col - head) / 16 goes to bin g % nb, where it is group g / nb; a bin spans
+// `cols` columns in all and holds up to `cap` records.
+struct BinPlan {
+  int32_t nb, nb_log2, cols, cap;
+};
+constexpr int kMaxBins = 256;
+constexpr int kBinColsMax = 8192;  // LDS floats of a bin's owner in the update kernel
+inline size_t general_record_capacity(int32_t count_max) {
+  const size_t want = 24 * (size_t)(count_max > 0 ? count_max : 0);
+  return want < 65536 ? 65536 : want;
+}
+inline BinPlan general_bin_plan(int32_t d, int32_t head, int nvec, int32_t count_max) {
+  BinPlan p{0, 0, 0, 0};
+  const int64_t groups = ((int64_t)d - head + 15) / 16;
+  if (groups <= 0 || nvec < 1) return p;
+  int nb = 1, lg = 0;
+  while (nb * 2 <= kMaxBins && nb * 2 <= groups) {
+    nb *= 2;
+    ++lg;
+  }
+  const int64_t cols = 16 * ((groups + nb - 1) / nb);
+  if (cols * nvec > kBinColsMax) return p;  // too many columns for the owners' LDS: atomics instead
+  p.nb = nb;
+  p.nb_log2 = lg;
+  p.cols = (int32_t)cols;
+  p.cap = (int32_t)(general_record_capacity(count_max) / nb);
+  return p;
+}
+
 struct GenArgs {
   // features
   const float *x;
@@ -33,18 +71,25 @@ struct GenArgs {
   // atomic accumulators (zeroed before the pass)
   float *acc_w;      // [d]
   float *acc_p;      // [d]
-  int32_t *acc_cnt;  // kept count
-  float *acc_gb;     // bias gradient
+  // per-block kept count and bias-gradient sum of a gradient pass (plain stores)
+  int32_t *blk_cnt;  // [blocks of the pass]
+  float *blk_gb;     // [blocks of the pass]
   // per-block sums of the first `head` columns: part[(block * nvec + vec) * head + column],
   // written whole by every block of a gradient pass (no clearing needed)
   float *part;
   int32_t head;
+  // entries of the other columns leave a block as records, sorted into bins by column
+  // (see BinPlan); fill[bin] counts the records offered to a bin, zeroed before the pass
+  TailRecord *bins;
+  int32_t *bin_fill;
+  BinPlan plan;
 };
 
 // Columns whose gradient sums leave a block as plain stores instead of atomics, for a pass
 // that updates nvec vectors over d columns; blocks of a gradient pass at most.
 int32_t general_head_columns(int32_t d, int nvec);
 constexpr int kGeneralGradBlocks = 256;
+constexpr int kGeneralHeader = 16 + 256;  // floats ahead of the accumulators: scalars, bin fill counts
 inline size_t general_part_floats(int32_t d) {
   const size_t per_block = 2 * (size_t)d < 16384 ? 2 * (size_t)d : 16384;
   return kGeneralGradBlocks * per_block;
@@ -54,8 +99,8 @@ struct ApplyArgs {
   int32_t d;
   const float *acc_w;
   const float *acc_p;
-  const int32_t *acc_cnt;
-  const float *acc_gb;
+  const int32_t *blk_cnt;  // per-block kept counts and bias-gradient sums of the pass
+  const float *blk_gb;
   const int32_t *m_dev;
   int32_t m_max;
   float *w;
@@ -65,6 +110,9 @@ struct ApplyArgs {
   float *bias_copy;
   const float *part;  // per-block sums of the first `head` columns (see GenArgs)
   int32_t head, nvec, nblk_pass;
+  const TailRecord *bins;  // records of the other columns (see GenArgs)
+  const int32_t *bin_fill;
+  BinPlan plan;
   float lambda, lr, lr_a, l2_a;
   int32_t *kept_hist;
   const uint8_t *flags;
