@@ -8,10 +8,14 @@
 //  * the first columns (frequency-ranked column ids, the usual layout of such data,
 //    put the hot ones there) have a slot each in an LDS table of the block and leave
 //    it as plain stores into a per-block array that the second kernel sums;
-//  * entries of any other column are collected as records in LDS and written, sorted
-//    by column bin, into per-bin arrays; the block that owns a bin in the second
-//    kernel sums its records in LDS.  One integer atomic per block, bin and flush
-//    reserves the space;
+//  * any other column may claim one of a few thousand hashed LDS slots, first come
+//    first served (a hot column outside the first ones -- a bias-like feature at the
+//    end, the head of a second vocabulary -- comes early and keeps its slot);
+//  * entries that find their slot taken are collected as records in LDS and written,
+//    sorted by column bin, into per-bin arrays, and so are the hashed slots at the
+//    end; the block that owns a bin in the second kernel sums its records in LDS.
+//    One integer atomic per block, bin and flush reserves the space.  The buffer is
+//    emptied whenever the block finds it half full after 16 rows per wave;
 //  * only what does not fit (records beyond the LDS buffer or a bin's capacity, or
 //    more columns than the bins can cover) is added to dense accumulators in HBM.
 #include "aa_compact.hpp"
@@ -28,15 +32,17 @@ __device__ __forceinline__ float gsum(float v) {
   return v;
 }
 
-// Per-block LDS: kDirect* slots for columns 0..kDirect*-1 (one sum per updated vector), then a
-// buffer of kRecords* records for entries of other columns.  About 138 KB with both vectors,
-// 130 KB with one: one block of 16 waves per compute unit.
-constexpr int kDirectTwoVec = 8192, kRecordsTwoVec = 6144;
-constexpr int kDirectOneVec = 16384, kRecordsOneVec = 8192;
+// Per-block LDS: kDirect* slots for columns 0..kDirect*-1 (one sum per updated vector),
+// kHashed* slots with a column tag each, and a buffer of kRecords records.  About 138 KB with
+// both vectors, 130 KB with one: one block of 16 waves per compute unit.
+constexpr int kDirectTwoVec = 8192, kHashedTwoVec = 2048;
+constexpr int kDirectOneVec = 16384, kHashedOneVec = 4096;
+constexpr int kRecords = 4096;
 constexpr int kGradThreads = 1024, kPoolThreads = 256;
+constexpr int kCheckRows = 16;  // rows per wave between two looks at the record buffer
 
 __device__ __forceinline__ int bin_of(int c, int head, const BinPlan &p) {
-  return ((c - head) >> 4) & (p.nb - 1);
+  return ((c - head) >> kBinGroupLog2) & (p.nb - 1);
 }
 
 // Adds one entry's terms to the dense accumulators in HBM (the path of last resort).
@@ -49,21 +55,33 @@ __device__ __forceinline__ void add_global(const GenArgs &a, int c, float ta, fl
   }
 }
 
-// Empties the block's record buffer into the bins.  Whole block; the caller has put a barrier
-// between the last append and this call.  R records at most, R / 1024 per thread.
-template <int R, bool SVM, bool ASSIST>
-__device__ void flush_records(const GenArgs &a, int head, const int *s_rc, const float *s_ra,
-                              const float *s_rb, int *s_nrec, int *s_hist, int *s_base) {
-  constexpr int kPer = R / kGradThreads;
+// Empties the block's record buffer -- and with `with_hashed` its hashed slots -- into the
+// bins.  Whole block; the caller has put a barrier between the last append and this call.
+template <int H, bool SVM, bool ASSIST>
+__device__ __forceinline__ void flush_records(const GenArgs &a, int head, const int *s_rc,
+                                              const float *s_ra, const float *s_rb, int *s_nrec,
+                                              const int *s_tag, const float *s_ha,
+                                              const float *s_hb, bool with_hashed, int *s_hist,
+                                              int *s_base) {
+  constexpr int R = kRecords;
+  constexpr int kPerR = R / kGradThreads, kPer = (R + H) / kGradThreads;
+  static_assert(R % kGradThreads == 0 && H % kGradThreads == 0, "whole turns of the block");
   const int n = min(*s_nrec, R);
   const int nb = a.plan.nb;
   for (int t = threadIdx.x; t < nb; t += blockDim.x) s_hist[t] = 0;
   __syncthreads();
-  int rank[kPer];
+  int col[kPer], rank[kPer];
 #pragma unroll
   for (int q = 0; q < kPer; ++q) {
     const int i = threadIdx.x + q * kGradThreads;
-    rank[q] = i < n ? atomicAdd(s_hist + bin_of(s_rc[i], head, a.plan), 1) : 0;
+    int c = -1;
+    if (q < kPerR) {
+      if (i < n) c = s_rc[i];
+    } else if (with_hashed) {
+      c = s_tag[i - R];
+    }
+    col[q] = c;
+    rank[q] = c >= 0 ? atomicAdd(s_hist + bin_of(c, head, a.plan), 1) : 0;
   }
   __syncthreads();
   for (int t = threadIdx.x; t < nb; t += blockDim.x) {
@@ -73,22 +91,22 @@ __device__ void flush_records(const GenArgs &a, int head, const int *s_rc, const
   __syncthreads();
 #pragma unroll
   for (int q = 0; q < kPer; ++q) {
+    const int c = col[q];
+    if (c < 0) continue;
     const int i = threadIdx.x + q * kGradThreads;
-    if (i < n) {
-      const int c = s_rc[i];
-      const int bin = bin_of(c, head, a.plan);
-      const int pos = s_base[bin] + rank[q];
-      const float ta = s_ra[i], tb = (SVM && ASSIST) ? s_rb[i] : 0.f;
-      if (pos < a.plan.cap) {
-        TailRecord r;
-        r.col = c;
-        r.a = ta;
-        r.b = tb;
-        r.pad = 0;
-        a.bins[(size_t)bin * a.plan.cap + pos] = r;
-      } else {
-        add_global<SVM, ASSIST>(a, c, ta, tb);
-      }
+    const float ta = q < kPerR ? s_ra[i] : s_ha[i - R];
+    const float tb = (SVM && ASSIST) ? (q < kPerR ? s_rb[i] : s_hb[i - R]) : 0.f;
+    const int bin = bin_of(c, head, a.plan);
+    const int pos = s_base[bin] + rank[q];
+    if (pos < a.plan.cap) {
+      TailRecord r;
+      r.col = c;
+      r.a = ta;
+      r.b = tb;
+      r.pad = 0;
+      a.bins[(size_t)bin * a.plan.cap + pos] = r;
+    } else {
+      add_global<SVM, ASSIST>(a, c, ta, tb);
     }
   }
   __syncthreads();
@@ -107,8 +125,11 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
   constexpr int G = kWave / GL;
   constexpr int NVEC = (SVM ? 1 : 0) + (ASSIST ? 1 : 0);
   constexpr int D = NVEC == 2 ? kDirectTwoVec : kDirectOneVec;  // slots 0..D-1: column = slot
-  constexpr int R = NVEC == 2 ? kRecordsTwoVec : kRecordsOneVec;  // record buffer
+  constexpr int H = NVEC == 2 ? kHashedTwoVec : kHashedOneVec;  // hashed slots
+  constexpr int R = kRecords;                                    // record buffer
   __shared__ float s_sum[GRAD ? NVEC * D : 1];
+  __shared__ int s_tag[GRAD ? H : 1];
+  __shared__ float s_hs[GRAD ? NVEC * H : 1];
   __shared__ int s_rc[GRAD ? R : 1];
   __shared__ float s_rt[GRAD ? NVEC * R : 1];
   __shared__ int s_hist[GRAD ? kMaxBins : 1], s_base[GRAD ? kMaxBins : 1];
@@ -117,9 +138,13 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
   __shared__ float s_gb[16];
   float *const s_w = s_sum, *const s_p = s_sum + (SVM ? D : 0);
   float *const s_ra = s_rt, *const s_rb = s_rt + (NVEC == 2 ? R : 0);
+  float *const s_ha = s_hs, *const s_hb = s_hs + (NVEC == 2 ? H : 0);
   const bool binned = GRAD && a.plan.nb > 0;
+  const int salt = (int)((blockIdx.x * 0x9E3779B1u) >> 19) & (H - 1);
   if (GRAD) {
     for (int k = threadIdx.x; k < NVEC * D; k += blockDim.x) s_sum[k] = 0.f;
+    for (int k = threadIdx.x; k < H; k += blockDim.x) s_tag[k] = -1;
+    for (int k = threadIdx.x; k < NVEC * H; k += blockDim.x) s_hs[k] = 0.f;
     if (threadIdx.x == 0) s_nrec = 0;
     __syncthreads();
   }
@@ -139,7 +164,8 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
   int kept = 0;
 
   // every wave of the grid makes the same number of rounds, so that a block can meet between them
-  const int rounds = (per + (rem > 0 ? 1 : 0) + kWave - 1) / kWave;
+  const int rows_max = per + (rem > 0 ? 1 : 0);
+  const int rounds = (rows_max + kWave - 1) / kWave;
   for (int round = 0; round < rounds; ++round) {
     const int base = lo + round * kWave;
     const int cnt = max(0, min(kWave, hi - base));
@@ -161,7 +187,8 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
       if (POOL && a.do_keep) u_l = keep_uniform(a.key, (uint32_t)j_l);
       if (ASSIST && !SVM) lin_l = a.loss_in[j_l];
     }
-    const int iters = (cnt + G - 1) / G;
+    // the same trip count in every wave of the block (rows past a wave's own count are idle)
+    const int iters = (max(0, min(kWave, rows_max - round * kWave)) + G - 1) / G;
     for (int it = 0; it < iters; ++it) {
       const int li = it * G + grp;
       const bool live = li < cnt;
@@ -248,7 +275,16 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
             if (SVM && cw != 0.f) unsafeAtomicAdd(s_w + c, cw * xv);
             if (ASSIST && resid != 0.f) unsafeAtomicAdd(s_p + c, resid * xv);
           }
-          const bool tail = active && c >= D;
+          bool tail = active && c >= D;
+          if (tail) {  // the column's hashed slot, if it is free or already the column's
+            const int h = (c ^ (c >> 11) ^ salt) & (H - 1);
+            const int old = atomicCAS(s_tag + h, -1, c);
+            if (old == -1 || old == c) {
+              if (SVM && cw != 0.f) unsafeAtomicAdd(s_ha + h, ta);
+              if (ASSIST && resid != 0.f) unsafeAtomicAdd((SVM ? s_hb : s_ha) + h, tb);
+              tail = false;
+            }
+          }
           if (binned) {
             const unsigned long long mask = __ballot(tail);
             if (mask != 0ull) {
@@ -273,14 +309,16 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
             add_global<SVM, ASSIST>(a, c, ta, tb);
           }
         }
+        // every kCheckRows rows per wave the block looks at its record buffer together
+        if (binned && ((it + 1) * G) % kCheckRows == 0 && (it + 1 < iters || round + 1 < rounds)) {
+          __syncthreads();
+          const int fill = s_nrec;
+          __syncthreads();
+          if (fill > R / 2)
+            flush_records<H, SVM, ASSIST>(a, D, s_rc, s_ra, s_rb, &s_nrec, s_tag, s_ha, s_hb,
+                                          false, s_hist, s_base);
+        }
       }
-    }
-    if (GRAD && round + 1 < rounds) {  // a buffer more than half full is emptied between rounds
-      __syncthreads();
-      const int fill = s_nrec;
-      __syncthreads();
-      if (binned && fill > R / 2)
-        flush_records<R, SVM, ASSIST>(a, D, s_rc, s_ra, s_rb, &s_nrec, s_hist, s_base);
     }
   }
 
@@ -315,7 +353,15 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
       if (SVM) mine[k] = s_w[k];
       if (ASSIST) mine[(SVM ? a.head : 0) + k] = s_p[k];
     }
-    if (binned) flush_records<R, SVM, ASSIST>(a, D, s_rc, s_ra, s_rb, &s_nrec, s_hist, s_base);
+    if (binned) {
+      flush_records<H, SVM, ASSIST>(a, D, s_rc, s_ra, s_rb, &s_nrec, s_tag, s_ha, s_hb, true,
+                                    s_hist, s_base);
+    } else {
+      for (int k = threadIdx.x; k < H; k += blockDim.x) {
+        const int c = s_tag[k];
+        if (c >= 0) add_global<SVM, ASSIST>(a, c, s_ha[k], (SVM && ASSIST) ? s_hb[k] : 0.f);
+      }
+    }
   }
 }
 
@@ -332,9 +378,128 @@ __global__ __launch_bounds__(256) void k_zero_f32(float *p, size_t count) {
 // accumulators; then one block per compaction tile.  Every block adds up the per-block kept
 // counts of the pass for itself.
 constexpr int kHeadCols = 16;
-static_assert(kGeneralGradBlocks <= 256, "k_apply_general reads one per-block count per thread");
+constexpr int kApplyThreads = 256;
+static_assert(kGeneralGradBlocks <= kApplyThreads, "one per-block count of the pass per thread");
 
-__global__ __launch_bounds__(256) void k_apply_general(const ApplyArgs a, int nh, int nrest) {
+// The update of one column from its gradient sums (m == 0: the model stays, its copy is still due).
+struct Fold {
+  const ApplyArgs &a;
+  int m;
+  float inv_m, shrink, scale;
+  __device__ Fold(const ApplyArgs &args, int m_)
+      : a(args), m(m_), inv_m(m_ > 0 ? 1.f / (float)m_ : 0.f),
+        shrink(1.f - args.lr * args.lambda), scale(args.lr * inv_m) {}
+  // w_old, ph: the column's current values, loaded by the caller
+  __device__ __forceinline__ void loaded(int k, float gw, float gp, float w_old, float ph) const {
+    if (m <= 0) {
+      if (a.phi && a.phi_copy) a.phi_copy[k] = ph;
+      return;
+    }
+    if (a.w) a.w[k] = __fmaf_rn(scale, gw, shrink * w_old);
+    if (a.phi) {
+      const float pn = ph - a.lr_a * __fmaf_rn(a.l2_a, ph, gp * inv_m);
+      a.phi[k] = pn;
+      if (a.phi_copy) a.phi_copy[k] = pn;
+    }
+  }
+  __device__ __forceinline__ void column(int k, float gw, float gp) const {
+    loaded(k, gw, gp, a.w ? a.w[k] : 0.f, a.phi ? a.phi[k] : 0.f);
+  }
+};
+
+// Kept count of the pass (and the sum of its bias gradients): one per-block value per thread.
+__device__ __forceinline__ int pass_totals(const ApplyArgs &a, int cnt, float gbs, int *s_m,
+                                           float *s_g, float *gb_out) {
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) {
+    cnt += __shfl_xor(cnt, off, kWave);
+    gbs += __shfl_xor(gbs, off, kWave);
+  }
+  if ((t & 63) == 0) {
+    s_m[t >> 6] = cnt;
+    s_g[t >> 6] = gbs;
+  }
+  __syncthreads();
+  *gb_out = (s_g[0] + s_g[1]) + (s_g[2] + s_g[3]);
+  const int m_pass = s_m[0] + s_m[1] + s_m[2] + s_m[3];
+  return a.m_dev ? min(max(*a.m_dev, 0), a.m_max) : m_pass;
+}
+
+__device__ __forceinline__ int bin_local(int col, const ApplyArgs &a) {
+  const int rel = col - a.head;
+  return (((rel >> kBinGroupLog2) >> a.plan.nb_log2) << kBinGroupLog2) | (rel & (kBinGroup - 1));
+}
+
+__device__ __forceinline__ int bin_column(int k, int bin, const ApplyArgs &a) {
+  return a.head +
+         (((((k >> kBinGroupLog2) << a.plan.nb_log2) | bin) << kBinGroupLog2) | (k & (kBinGroup - 1)));
+}
+
+// The block that owns a bin.  Everything it needs from memory (the first records and columns
+// per thread, in registers) is requested before anything is used: one round trip, not five.
+__device__ void apply_bin(const ApplyArgs &a, int bin, float *s_bin, int *s_m, float *s_g) {
+  constexpr int kRec = 16, kCol = 16;
+  const int tid = threadIdx.x, cols = a.plan.cols, cap = a.plan.cap;
+  const int cnt = tid < a.nblk_pass ? a.blk_cnt[tid] : 0;
+  const int fill = a.bin_fill[bin];
+  const TailRecord *rec = a.bins + (size_t)bin * cap;
+  TailRecord r[kRec];
+#pragma unroll
+  for (int u = 0; u < kRec; ++u) {
+    const int i = tid + u * kApplyThreads;
+    if (i < cap) {  // past the fill count: stale, in bounds, not used
+      r[u] = rec[i];
+    } else {
+      r[u].col = a.head;
+      r[u].a = r[u].b = 0.f;
+    }
+  }
+  int col[kCol];
+  float gw[kCol], gp[kCol], wo[kCol], po[kCol];
+#pragma unroll
+  for (int u = 0; u < kCol; ++u) {
+    const int k = tid + u * kApplyThreads;
+    int c = bin_column(k, bin, a);
+    if (k >= cols || c >= a.d) c = -1;
+    col[u] = c;
+    gw[u] = (c >= 0 && a.w) ? a.acc_w[c] : 0.f;
+    gp[u] = (c >= 0 && a.phi) ? a.acc_p[c] : 0.f;
+    wo[u] = (c >= 0 && a.w) ? a.w[c] : 0.f;
+    po[u] = (c >= 0 && a.phi) ? a.phi[c] : 0.f;
+  }
+  float *const s_a = s_bin, *const s_b = s_bin + cols;
+  for (int k = tid; k < a.nvec * cols; k += kApplyThreads) s_bin[k] = 0.f;
+  float gb_unused;
+  const int m = pass_totals(a, cnt, 0.f, s_m, s_g, &gb_unused);  // barrier: the sums are zero
+  const Fold fold(a, m);
+  const int n = min(fill, cap);
+  auto add = [&](const TailRecord &t) {
+    const int k = bin_local(t.col, a);
+    if (t.a != 0.f) unsafeAtomicAdd(s_a + k, t.a);
+    if (a.nvec == 2 && t.b != 0.f) unsafeAtomicAdd(s_b + k, t.b);
+  };
+#pragma unroll
+  for (int u = 0; u < kRec; ++u)
+    if (tid + u * kApplyThreads < n) add(r[u]);
+  for (int i = tid + kRec * kApplyThreads; i < n; i += kApplyThreads) add(rec[i]);
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < kCol; ++u) {
+    if (col[u] < 0) continue;
+    const int k = tid + u * kApplyThreads;
+    const float va = s_a[k], vb = a.nvec == 2 ? s_b[k] : va;
+    fold.loaded(col[u], gw[u] + (a.w ? va : 0.f), gp[u] + vb, wo[u], po[u]);
+  }
+  for (int k = tid + kCol * kApplyThreads; k < cols; k += kApplyThreads) {
+    const int c = bin_column(k, bin, a);
+    if (c >= a.d) continue;
+    const float va = s_a[k], vb = a.nvec == 2 ? s_b[k] : va;
+    fold.column(c, a.w ? a.acc_w[c] + va : 0.f, a.phi ? a.acc_p[c] + vb : 0.f);
+  }
+}
+
+__global__ __launch_bounds__(kApplyThreads) void k_apply_general(const ApplyArgs a, int nh, int nrest) {
   __shared__ int s_int[40];
   __shared__ float s_part[2][16][kHeadCols];
   __shared__ int s_m[4];
@@ -354,95 +519,57 @@ __global__ __launch_bounds__(256) void k_apply_general(const ApplyArgs a, int nh
     tile_compact(c, (int)blockIdx.x - nh - nrest, s_int);
     return;
   }
-  {  // nblk_pass <= blockDim.x: one per-block count (and bias-gradient sum) per thread
-    const int t = threadIdx.x;
-    int cnt = t < a.nblk_pass ? a.blk_cnt[t] : 0;
-    float gbs = (t < a.nblk_pass && a.phi && a.bias) ? a.blk_gb[t] : 0.f;
-#pragma unroll
-    for (int off = kWave / 2; off > 0; off >>= 1) {
-      cnt += __shfl_xor(cnt, off, kWave);
-      gbs += __shfl_xor(gbs, off, kWave);
-    }
-    if ((t & 63) == 0) {
-      s_m[t >> 6] = cnt;
-      s_g[t >> 6] = gbs;
-    }
-    __syncthreads();
+  if ((int)blockIdx.x >= nh && a.plan.nb > 0) {  // nrest == nb
+    apply_bin(a, (int)blockIdx.x - nh, s_bin, s_m, s_g);
+    return;
   }
-  const int m_pass = s_m[0] + s_m[1] + s_m[2] + s_m[3];
-  const float gb_pass = (s_g[0] + s_g[1]) + (s_g[2] + s_g[3]);
-  const int m = a.m_dev ? min(max(*a.m_dev, 0), a.m_max) : m_pass;
-  if (blockIdx.x == 0 && threadIdx.x == 0 && a.kept_hist) *a.kept_hist = m;
-  const float inv_m = m > 0 ? 1.f / (float)m : 0.f;
-  const float shrink = 1.f - a.lr * a.lambda, scale = a.lr * inv_m;
-  // one column: sums gw / gp -> new w, new phi (m == 0: the model stays, its copy is still due)
-  auto fold = [&](int k, float gw, float gp) {
-    if (m <= 0) {
-      if (a.phi && a.phi_copy) a.phi_copy[k] = a.phi[k];
-      return;
-    }
-    if (a.w) a.w[k] = __fmaf_rn(scale, gw, shrink * a.w[k]);
-    if (a.phi) {
-      const float ph = a.phi[k];
-      const float pn = ph - a.lr_a * __fmaf_rn(a.l2_a, ph, gp * inv_m);
-      a.phi[k] = pn;
-      if (a.phi_copy) a.phi_copy[k] = pn;
-    }
-  };
+  const int t = threadIdx.x;
+  const int cnt = t < a.nblk_pass ? a.blk_cnt[t] : 0;
+  const float gbs = (t < a.nblk_pass && a.phi && a.bias) ? a.blk_gb[t] : 0.f;
   if ((int)blockIdx.x < nh) {
-    const int cl = threadIdx.x & (kHeadCols - 1), q = threadIdx.x >> 4;
+    const int cl = t & (kHeadCols - 1), q = t >> 4;
     const int k = blockIdx.x * kHeadCols + cl;
     float sw = 0.f, sp = 0.f;
-    if (k < a.head && m > 0) {
+    if (k < a.head) {  // (all zeros when nothing was kept)
       const size_t stride = (size_t)a.nvec * a.head;
       const float *pw = a.part + k, *pp = a.part + (a.w ? a.head : 0) + k;
-#pragma unroll 4
+#pragma unroll 8
       for (int b = q; b < a.nblk_pass; b += 16) {
         if (a.w) sw += pw[b * stride];
         if (a.phi) sp += pp[b * stride];
       }
     }
+    float gw = 0.f, gp = 0.f, wo = 0.f, po = 0.f;
+    if (q == 0 && k < a.head) {
+      gw = a.w ? a.acc_w[k] : 0.f;
+      gp = a.phi ? a.acc_p[k] : 0.f;
+      wo = a.w ? a.w[k] : 0.f;
+      po = a.phi ? a.phi[k] : 0.f;
+    }
     s_part[0][q][cl] = sw;
     s_part[1][q][cl] = sp;
-    __syncthreads();
+    float gb_pass;
+    const int m = pass_totals(a, cnt, gbs, s_m, s_g, &gb_pass);  // barrier
+    const Fold fold(a, m);
+    if (blockIdx.x == 0 && t == 0 && a.kept_hist) *a.kept_hist = m;
     if (q == 0 && k < a.head) {
-      float gw = a.w ? a.acc_w[k] : 0.f, gp = a.phi ? a.acc_p[k] : 0.f;
       for (int i = 0; i < 16; ++i) {
         gw += s_part[0][i][cl];
         gp += s_part[1][i][cl];
       }
-      fold(k, gw, gp);
+      fold.loaded(k, gw, gp, wo, po);
     }
-  } else if (a.plan.nb > 0) {  // nrest == nb: this block owns a bin
-    const int bin = (int)blockIdx.x - nh, cols = a.plan.cols;
-    float *const s_a = s_bin, *const s_b = s_bin + cols;
-    for (int k = threadIdx.x; k < a.nvec * cols; k += blockDim.x) s_bin[k] = 0.f;
-    __syncthreads();
-    const int n = m > 0 ? min(a.bin_fill[bin], a.plan.cap) : 0;
-    const TailRecord *rec = a.bins + (size_t)bin * a.plan.cap;
-    for (int i = threadIdx.x; i < n; i += blockDim.x) {
-      const TailRecord r = rec[i];
-      const int rel = r.col - a.head;
-      const int k = (((rel >> 4) >> a.plan.nb_log2) << 4) | (rel & 15);
-      if (r.a != 0.f) unsafeAtomicAdd(s_a + k, r.a);
-      if (a.nvec == 2 && r.b != 0.f) unsafeAtomicAdd(s_b + k, r.b);
-    }
-    __syncthreads();
-    for (int k = threadIdx.x; k < cols; k += blockDim.x) {
-      const int col = a.head + (((((k >> 4) << a.plan.nb_log2) | bin) << 4) | (k & 15));
-      if (col >= a.d) continue;
-      const float va = s_a[k], vb = a.nvec == 2 ? s_b[k] : va;
-      fold(col, a.w ? a.acc_w[col] + va : 0.f, a.phi ? a.acc_p[col] + vb : 0.f);
+    if (blockIdx.x == 0 && t == 0 && a.phi && a.bias) {
+      const float bn = m > 0 ? *a.bias - a.lr_a * (gb_pass * fold.inv_m) : *a.bias;
+      if (m > 0) *a.bias = bn;
+      if (a.bias_copy) *a.bias_copy = bn;
     }
   } else {
-    for (int k = a.head + ((int)blockIdx.x - nh) * blockDim.x + threadIdx.x; k < a.d;
-         k += nrest * blockDim.x)
-      fold(k, a.w ? a.acc_w[k] : 0.f, a.phi ? a.acc_p[k] : 0.f);
-  }
-  if (blockIdx.x == 0 && threadIdx.x == 0 && a.phi && a.bias) {
-    const float bn = m > 0 ? *a.bias - a.lr_a * (gb_pass * inv_m) : *a.bias;
-    if (m > 0) *a.bias = bn;
-    if (a.bias_copy) *a.bias_copy = bn;
+    float gb_pass;
+    const int m = pass_totals(a, cnt, gbs, s_m, s_g, &gb_pass);
+    const Fold fold(a, m);
+    for (int k = a.head + ((int)blockIdx.x - nh) * blockDim.x + t; k < a.d; k += nrest * blockDim.x)
+      fold.column(k, a.w ? a.acc_w[k] : 0.f, a.phi ? a.acc_p[k] : 0.f);
   }
 }
 
@@ -515,7 +642,7 @@ hipError_t launch_general_apply(const ApplyArgs &a, hipStream_t st) {
   if (nrest < 0) nrest = 0;
   if (a.plan.nb > 0) nrest = a.plan.nb;
   if (nh + nrest < 1) nrest = 1;
-  hipLaunchKernelGGL(k_apply_general, dim3(nh + nrest + (a.flags ? compact_tiles(a.P) : 0)), dim3(256),
+  hipLaunchKernelGGL(k_apply_general, dim3(nh + nrest + (a.flags ? compact_tiles(a.P) : 0)), dim3(kApplyThreads),
                      0, st, a, nh, nrest);
   return hipGetLastError();
 }

@@ -14,28 +14,29 @@ struct __attribute__((aligned(16))) TailRecord {
   int32_t pad;
 };
 
-// Columns from `head` on are dealt to nb bins (a power of two, 0: no binning) in groups of 16:
-// group g = (col - head) / 16 goes to bin g % nb, where it is group g / nb; a bin spans
-// `cols` columns in all and holds up to `cap` records.
+// Columns from `head` on are dealt to nb bins (a power of two, 0: no binning) in groups of 16
+// (one 64-byte line of a model vector): group g = (col - head) / 16 goes to bin g % nb,
+// where it is group g / nb; a bin spans `cols` columns in all and holds up to `cap` records.
 struct BinPlan {
   int32_t nb, nb_log2, cols, cap;
 };
 constexpr int kMaxBins = 256;
+constexpr int kBinGroupLog2 = 4, kBinGroup = 1 << kBinGroupLog2;
 constexpr int kBinColsMax = 8192;  // LDS floats of a bin's owner in the update kernel
 inline size_t general_record_capacity(int32_t count_max) {
-  const size_t want = 24 * (size_t)(count_max > 0 ? count_max : 0);
+  const size_t want = 48 * (size_t)(count_max > 0 ? count_max : 0);
   return want < 65536 ? 65536 : want;
 }
 inline BinPlan general_bin_plan(int32_t d, int32_t head, int nvec, int32_t count_max) {
   BinPlan p{0, 0, 0, 0};
-  const int64_t groups = ((int64_t)d - head + 15) / 16;
+  const int64_t groups = ((int64_t)d - head + kBinGroup - 1) / kBinGroup;
   if (groups <= 0 || nvec < 1) return p;
   int nb = 1, lg = 0;
   while (nb * 2 <= kMaxBins && nb * 2 <= groups) {
     nb *= 2;
     ++lg;
   }
-  const int64_t cols = 16 * ((groups + nb - 1) / nb);
+  const int64_t cols = kBinGroup * ((groups + nb - 1) / nb);
   if (cols * nvec > kBinColsMax) return p;  // too many columns for the owners' LDS: atomics instead
   p.nb = nb;
   p.nb_log2 = lg;
@@ -89,7 +90,7 @@ struct GenArgs {
 // that updates nvec vectors over d columns; blocks of a gradient pass at most.
 int32_t general_head_columns(int32_t d, int nvec);
 constexpr int kGeneralGradBlocks = 256;
-constexpr int kGeneralHeader = 16 + 256;  // floats ahead of the accumulators: scalars, bin fill counts
+constexpr int kGeneralHeader = 16 + kMaxBins;  // floats ahead of the accumulators: scalars, bin fill counts
 inline size_t general_part_floats(int32_t d) {
   const size_t per_block = 2 * (size_t)d < 16384 ? 2 * (size_t)d : 16384;
   return kGeneralGradBlocks * per_block;

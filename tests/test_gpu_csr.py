@@ -297,3 +297,104 @@ def test_train_epoch_on_csr_rows(ref, ws, sparse):
     with pytest.raises(api.AAError):
         api.train_epoch(F, dev(y), dev(perm), n, P, w, phi, b, cfg,
                         torch.zeros(1, dtype=torch.int32, device="cuda"), hist, ws)
+
+
+def _uniform_csr(r, n, d, nnz_lo, nnz_hi):
+    """Rows whose columns are uniform over all of d (no hot columns), unit L2 norm."""
+    lens = r.integers(nnz_lo, nnz_hi + 1, size=n)
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(lens, out=rowptr[1:])
+    col = r.integers(0, d, size=int(rowptr[-1])).astype(np.int32)
+    val = r.standard_normal(col.size).astype(np.float32)
+    norm = np.sqrt(np.add.reduceat(val.astype(np.float64) ** 2, rowptr[:-1]))
+    val = (val / np.repeat(norm, lens)).astype(np.float32)
+    return rowptr, col, val
+
+
+def _col_abs_sum_sp(Fh, ids, d):
+    S = sp.csr_matrix((np.abs(Fh.val.astype(np.float64)), Fh.col, Fh.rowptr), shape=(Fh.n, d))
+    return np.asarray(S[np.asarray(ids)].sum(axis=0)).ravel()
+
+
+def test_csr_updates_many_rows_per_block_uniform_columns(ref):
+    """300,000 kept rows with columns uniform over d = 2^18: nearly every entry falls outside
+    the per-block table, every block makes two rounds, and its entry buffer fills more than
+    once (emptied between the rounds, the excess added to the accumulators directly)."""
+    r = rng(21)
+    n, d, m = 300_000, 1 << 18, 300_000
+    rowptr, col, val = _uniform_csr(r, n, d, 8, 16)
+    y = np.where(r.random(n) < 0.5, -1.0, 1.0).astype(np.float32)
+    w0 = (2.0 * r.standard_normal(d)).astype(np.float32)
+    phi0 = r.standard_normal(d).astype(np.float32)
+    rows = r.permutation(n)[:m].astype(np.int32)
+    Fh = ref.Features.csr(rowptr, col, val, d)
+    F = csr_features(rowptr, col, val, d)
+    ws = api.Workspace(m, d)
+    lam, lr, T, lr_a, b0 = 1e-3, 50.0, 0.8, 40.0, 0.1
+    w_ref, loss_ref = ref.svm_sgd_step(Fh, y, rows, m, w0, lam, lr)
+    S = abs_dot_scale(Fh, rows, w0)
+    dots = _dots(Fh, rows, w0) * y[rows]
+    on_kink = np.abs(dots - 1) <= RTOL * S
+    assert on_kink.sum() <= 20
+    w = dev(w0)
+    loss = torch.zeros(m, device="cuda")
+    api.svm_sgd_step(F, dev(y), dev(rows), scalar_dev(m, torch.int32), m, w, lam, lr, 0.0, loss, ws)
+    assert_close_scaled(host(loss), loss_ref, S, "loss")
+    absx = _col_abs_sum_sp(Fh, rows[dots < 1], d)
+    assert_close_scaled(host(w), w_ref, np.abs(w0.astype(np.float64)) + lr / m * absx, "w",
+                        atol=lr / m * _col_abs_sum_sp(Fh, rows[on_kink], d))
+    assert np.abs(w_ref - w0).max() > 1e-3  # the step is visible at the tolerance
+    phi_ref, b_ref = ref.assistant_update(Fh, rows, m, loss_ref, T, phi0, b0, lr_a)
+    phi, b = dev(phi0), scalar_dev(b0)
+    api.assistant_update(F, dev(rows), scalar_dev(m, torch.int32), m, dev(loss_ref), scalar_dev(T),
+                         phi, b, lr_a, 0.0, ws)
+    absx = _col_abs_sum_sp(Fh, rows, d)
+    assert_close_scaled(host(phi), phi_ref, np.abs(phi0.astype(np.float64)) + lr_a / m * absx, "phi")
+    assert np.abs(phi_ref - phi0).max() > 2e-4  # 20 times the tolerance
+    assert abs(float(host(b)[0]) - b_ref) <= RTOL * (abs(b0) + lr_a)
+
+
+def test_csr_fused_step_more_columns_than_the_bins_cover(ref):
+    """d = 1,300,000 with both vectors updated: too many columns for the column bins, so every
+    entry outside the per-block table goes to the dense accumulators."""
+    r = rng(22)
+    n, d, P = 6000, 1_300_000, 5000
+    rowptr, col, val = _uniform_csr(r, n, d, 20, 40)
+    y = np.where(r.random(n) < 0.5, -1.0, 1.0).astype(np.float32)
+    w0 = (2.0 * r.standard_normal(d)).astype(np.float32)
+    phi0 = (2.0 * r.standard_normal(d)).astype(np.float32)
+    idx = r.permutation(n)[:P].astype(np.int32)
+    Fh = ref.Features.csr(rowptr, col, val, d)
+    F = csr_features(rowptr, col, val, d)
+    ws = api.Workspace(P, d)
+    b0, gamma, step, lam, lr, T, lr_a = 0.0, 0.1, 3, 1e-3, 0.5, 0.1, 0.3
+    for seed in range(1, 20):
+        out = ref.step(Fh, y, idx, P, w0, phi0, b0, gamma, seed, step, lam, lr, T, lr_a)
+        if clear_draws(ref, out["prob"], gamma, seed, step).all():
+            break
+    else:
+        raise AssertionError("no clear seed")
+    kept = out["kept_ids"]
+    dots = _dots(Fh, kept, w0) * y[kept]
+    on_kink = np.abs(dots - 1) <= RTOL * abs_dot_scale(Fh, kept, w0)
+    assert on_kink.sum() <= 3
+    w, phi, b = dev(w0), dev(phi0), scalar_dev(b0)
+    Tt = scalar_dev(T)
+    cfg = api.step_config(gamma, lam, lr, lr_a, 0.0, seed, step, Tt)
+    prob = torch.zeros(P, device="cuda")
+    keep = torch.zeros(P, dtype=torch.uint8, device="cuda")
+    pos = torch.zeros(P, dtype=torch.int32, device="cuda")
+    ids = torch.zeros(P, dtype=torch.int32, device="cuda")
+    loss = torch.zeros(P, device="cuda")
+    cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    api.fused_step(F, dev(y), dev(idx), P, w, phi, b, cfg, None, prob, keep, pos, ids, loss, cnt, ws)
+    m = out["m"]
+    assert int(host(cnt)[0]) == m
+    assert np.array_equal(host(keep), out["keep"])
+    assert np.array_equal(host(ids)[:m], out["kept_ids"])
+    absx_a = _col_abs_sum_sp(Fh, kept[dots < 1], d)
+    assert_close_scaled(host(w), out["w"], np.abs(w0.astype(np.float64)) + lr / m * absx_a, "w",
+                        atol=lr / m * _col_abs_sum_sp(Fh, kept[on_kink], d))
+    absx = _col_abs_sum_sp(Fh, kept, d)
+    assert_close_scaled(host(phi), out["phi"], np.abs(phi0.astype(np.float64)) + lr_a / m * absx,
+                        "phi")
