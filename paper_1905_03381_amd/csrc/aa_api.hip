@@ -234,6 +234,7 @@ hipError_t run_pass(const PassSpec &s, const Ws &ws, int32_t *nblk_out, hipStrea
   a.blk_gb = ws.blk_gb;
   const int nvec = ((s.mode & kSvm) ? 1 : 0) + ((s.mode & kAssist) ? 1 : 0);
   a.acc_w = acc + kGeneralHeader;
+  a.acc_used = reinterpret_cast<int32_t *>(acc) + 2;
   a.acc_p = acc + kGeneralHeader + s.F->d;
   a.part = acc + kGeneralHeader + 2 * (size_t)s.F->d;
   a.head = general_head_columns(s.F->d, nvec);
@@ -306,6 +307,7 @@ hipError_t run_update(const PassSpec &s, const UpdateSpec &u, const Ws &ws, int3
   p.blk_cnt = ws.blk_cnt;
   p.blk_gb = ws.blk_gb;
   p.acc_w = acc + kGeneralHeader;
+  p.acc_used = reinterpret_cast<const int32_t *>(acc) + 2;
   p.acc_p = acc + kGeneralHeader + s.F->d;
   p.part = acc + kGeneralHeader + 2 * (size_t)s.F->d;
   p.nvec = ((s.mode & kSvm) ? 1 : 0) + ((s.mode & kAssist) ? 1 : 0);

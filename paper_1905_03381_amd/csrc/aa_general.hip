@@ -48,6 +48,7 @@ __device__ __forceinline__ int bin_of(int c, int head, const BinPlan &p) {
 // Adds one entry's terms to the dense accumulators in HBM (the path of last resort).
 template <bool SVM, bool ASSIST>
 __device__ __forceinline__ void add_global(const GenArgs &a, int c, float ta, float tb) {
+  *a.acc_used = 1;  // tells the update kernel to read the accumulators at all
   if (SVM && ta != 0.f) unsafeAtomicAdd(a.acc_w + c, ta);
   if (ASSIST) {
     const float t = SVM ? tb : ta;
@@ -277,8 +278,12 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
           }
           bool tail = active && c >= D;
           if (tail) {  // the column's hashed slot, if it is free or already the column's
-            const int h = (c ^ (c >> 11) ^ salt) & (H - 1);
-            const int old = atomicCAS(s_tag + h, -1, c);
+            int h = (c ^ (c >> 11) ^ salt) & (H - 1);
+            int old = atomicCAS(s_tag + h, -1, c);
+            if (old != -1 && old != c) {  // second try, elsewhere in the table
+              h = (h ^ (H / 2) ^ (c >> 5)) & (H - 1);
+              old = atomicCAS(s_tag + h, -1, c);
+            }
             if (old == -1 || old == c) {
               if (SVM && cw != 0.f) unsafeAtomicAdd(s_ha + h, ta);
               if (ASSIST && resid != 0.f) unsafeAtomicAdd((SVM ? s_hb : s_ha) + h, tb);
@@ -443,59 +448,87 @@ __device__ void apply_bin(const ApplyArgs &a, int bin, float *s_bin, int *s_m, f
   const int tid = threadIdx.x, cols = a.plan.cols, cap = a.plan.cap;
   const int cnt = tid < a.nblk_pass ? a.blk_cnt[tid] : 0;
   const int fill = a.bin_fill[bin];
+  const int acc_used = *a.acc_used;
   const TailRecord *rec = a.bins + (size_t)bin * cap;
-  TailRecord r[kRec];
+  int rc[kRec];  // records: column and the two terms (the fourth word of a record is padding)
+  float ra[kRec], rb[kRec];
+  auto load_record = [&](int u, int i) {
+    const int *words = reinterpret_cast<const int *>(rec + i);
+    rc[u] = words[0];
+    ra[u] = __int_as_float(words[1]);
+    rb[u] = __int_as_float(words[2]);
+  };
 #pragma unroll
   for (int u = 0; u < kRec; ++u) {
     const int i = tid + u * kApplyThreads;
     if (i < cap) {  // past the fill count: stale, in bounds, not used
-      r[u] = rec[i];
+      load_record(u, i);
     } else {
-      r[u].col = a.head;
-      r[u].a = r[u].b = 0.f;
+      rc[u] = a.head;
+      ra[u] = rb[u] = 0.f;
     }
   }
   int col[kCol];
-  float gw[kCol], gp[kCol], wo[kCol], po[kCol];
+  float wo[kCol], po[kCol];
 #pragma unroll
   for (int u = 0; u < kCol; ++u) {
     const int k = tid + u * kApplyThreads;
     int c = bin_column(k, bin, a);
     if (k >= cols || c >= a.d) c = -1;
     col[u] = c;
-    gw[u] = (c >= 0 && a.w) ? a.acc_w[c] : 0.f;
-    gp[u] = (c >= 0 && a.phi) ? a.acc_p[c] : 0.f;
     wo[u] = (c >= 0 && a.w) ? a.w[c] : 0.f;
     po[u] = (c >= 0 && a.phi) ? a.phi[c] : 0.f;
   }
-  float *const s_a = s_bin, *const s_b = s_bin + cols;
-  for (int k = tid; k < a.nvec * cols; k += kApplyThreads) s_bin[k] = 0.f;
+  // A bin of few columns keeps several copies of its sums, one per lane residue, so that the
+  // lanes of a wave that meet on a hot column add to different addresses (an odd stride puts
+  // the copies of a column into different LDS banks).
+  const int span = a.nvec * cols + 1;
+  int copies = 1;
+  while (copies < 16 && 2 * copies * span <= kBinColsMax) copies *= 2;
+  float *const s_mine = s_bin + (tid & (copies - 1)) * span;
+  for (int k = tid; k < copies * span; k += kApplyThreads) s_bin[k] = 0.f;
   float gb_unused;
   const int m = pass_totals(a, cnt, 0.f, s_m, s_g, &gb_unused);  // barrier: the sums are zero
   const Fold fold(a, m);
   const int n = min(fill, cap);
-  auto add = [&](const TailRecord &t) {
-    const int k = bin_local(t.col, a);
-    if (t.a != 0.f) unsafeAtomicAdd(s_a + k, t.a);
-    if (a.nvec == 2 && t.b != 0.f) unsafeAtomicAdd(s_b + k, t.b);
+  auto add = [&](int c, float ta, float tb) {
+    const int k = bin_local(c, a);
+    if (ta != 0.f) unsafeAtomicAdd(s_mine + k, ta);
+    if (a.nvec == 2 && tb != 0.f) unsafeAtomicAdd(s_mine + cols + k, tb);
   };
+  for (int base = 0; base < n; base += kRec * kApplyThreads) {
+    if (base > 0) {  // further batches: again all loads first
 #pragma unroll
-  for (int u = 0; u < kRec; ++u)
-    if (tid + u * kApplyThreads < n) add(r[u]);
-  for (int i = tid + kRec * kApplyThreads; i < n; i += kApplyThreads) add(rec[i]);
+      for (int u = 0; u < kRec; ++u) {
+        const int i = base + tid + u * kApplyThreads;
+        if (i < n) load_record(u, i);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kRec; ++u)
+      if (base + tid + u * kApplyThreads < n) add(rc[u], ra[u], rb[u]);
+  }
   __syncthreads();
+  auto sum_of = [&](int k) {  // over the copies, in order
+    float v = 0.f;
+    for (int c = 0; c < copies; ++c) v += s_bin[c * span + k];
+    return v;
+  };
+  // (the dense accumulators hold something only if an entry found no room in LDS or in a bin)
+  auto acc_w_of = [&](int c) { return (acc_used && a.w) ? a.acc_w[c] : 0.f; };
+  auto acc_p_of = [&](int c) { return (acc_used && a.phi) ? a.acc_p[c] : 0.f; };
 #pragma unroll
   for (int u = 0; u < kCol; ++u) {
     if (col[u] < 0) continue;
     const int k = tid + u * kApplyThreads;
-    const float va = s_a[k], vb = a.nvec == 2 ? s_b[k] : va;
-    fold.loaded(col[u], gw[u] + (a.w ? va : 0.f), gp[u] + vb, wo[u], po[u]);
+    const float va = sum_of(k), vb = a.nvec == 2 ? sum_of(cols + k) : va;
+    fold.loaded(col[u], acc_w_of(col[u]) + (a.w ? va : 0.f), acc_p_of(col[u]) + vb, wo[u], po[u]);
   }
   for (int k = tid + kCol * kApplyThreads; k < cols; k += kApplyThreads) {
     const int c = bin_column(k, bin, a);
     if (c >= a.d) continue;
-    const float va = s_a[k], vb = a.nvec == 2 ? s_b[k] : va;
-    fold.column(c, a.w ? a.acc_w[c] + va : 0.f, a.phi ? a.acc_p[c] + vb : 0.f);
+    const float va = sum_of(k), vb = a.nvec == 2 ? sum_of(cols + k) : va;
+    fold.column(c, acc_w_of(c) + (a.w ? va : 0.f), acc_p_of(c) + vb);
   }
 }
 
@@ -504,8 +537,11 @@ __global__ __launch_bounds__(kApplyThreads) void k_apply_general(const ApplyArgs
   __shared__ float s_part[2][16][kHeadCols];
   __shared__ int s_m[4];
   __shared__ float s_g[4];
-  __shared__ float s_bin[kBinColsMax];
-  if ((int)blockIdx.x >= nh + nrest) {
+  __shared__ float s_bin[kBinColsMax + 1];  // (+1: the odd stride of a single copy)
+  // roles by block number: the other columns first (the bin owners have the longest way to
+  // go), then the first columns, then the compaction tiles
+  const int bid = (int)blockIdx.x, hb = bid - nrest;
+  if (bid >= nh + nrest) {
     CompactArgs c;
     c.flags = a.flags;
     c.P = a.P;
@@ -516,19 +552,19 @@ __global__ __launch_bounds__(kApplyThreads) void k_apply_general(const ApplyArgs
     c.loss = a.loss;
     c.kept_count = a.kept_count;
     c.tile_off = nullptr;
-    tile_compact(c, (int)blockIdx.x - nh - nrest, s_int);
+    tile_compact(c, bid - nh - nrest, s_int);
     return;
   }
-  if ((int)blockIdx.x >= nh && a.plan.nb > 0) {  // nrest == nb
-    apply_bin(a, (int)blockIdx.x - nh, s_bin, s_m, s_g);
+  if (bid < nrest && a.plan.nb > 0) {  // nrest == nb
+    apply_bin(a, bid, s_bin, s_m, s_g);
     return;
   }
   const int t = threadIdx.x;
   const int cnt = t < a.nblk_pass ? a.blk_cnt[t] : 0;
   const float gbs = (t < a.nblk_pass && a.phi && a.bias) ? a.blk_gb[t] : 0.f;
-  if ((int)blockIdx.x < nh) {
+  if (hb >= 0) {
     const int cl = t & (kHeadCols - 1), q = t >> 4;
-    const int k = blockIdx.x * kHeadCols + cl;
+    const int k = hb * kHeadCols + cl;
     float sw = 0.f, sp = 0.f;
     if (k < a.head) {  // (all zeros when nothing was kept)
       const size_t stride = (size_t)a.nvec * a.head;
@@ -540,9 +576,7 @@ __global__ __launch_bounds__(kApplyThreads) void k_apply_general(const ApplyArgs
       }
     }
     float gw = 0.f, gp = 0.f, wo = 0.f, po = 0.f;
-    if (q == 0 && k < a.head) {
-      gw = a.w ? a.acc_w[k] : 0.f;
-      gp = a.phi ? a.acc_p[k] : 0.f;
+    if (q == 0 && k < a.head) {  // (the accumulators take entries of the other columns only)
       wo = a.w ? a.w[k] : 0.f;
       po = a.phi ? a.phi[k] : 0.f;
     }
@@ -551,7 +585,7 @@ __global__ __launch_bounds__(kApplyThreads) void k_apply_general(const ApplyArgs
     float gb_pass;
     const int m = pass_totals(a, cnt, gbs, s_m, s_g, &gb_pass);  // barrier
     const Fold fold(a, m);
-    if (blockIdx.x == 0 && t == 0 && a.kept_hist) *a.kept_hist = m;
+    if (hb == 0 && t == 0 && a.kept_hist) *a.kept_hist = m;
     if (q == 0 && k < a.head) {
       for (int i = 0; i < 16; ++i) {
         gw += s_part[0][i][cl];
@@ -559,7 +593,7 @@ __global__ __launch_bounds__(kApplyThreads) void k_apply_general(const ApplyArgs
       }
       fold.loaded(k, gw, gp, wo, po);
     }
-    if (blockIdx.x == 0 && t == 0 && a.phi && a.bias) {
+    if (hb == 0 && t == 0 && a.phi && a.bias) {
       const float bn = m > 0 ? *a.bias - a.lr_a * (gb_pass * fold.inv_m) : *a.bias;
       if (m > 0) *a.bias = bn;
       if (a.bias_copy) *a.bias_copy = bn;
@@ -568,7 +602,7 @@ __global__ __launch_bounds__(kApplyThreads) void k_apply_general(const ApplyArgs
     float gb_pass;
     const int m = pass_totals(a, cnt, gbs, s_m, s_g, &gb_pass);
     const Fold fold(a, m);
-    for (int k = a.head + ((int)blockIdx.x - nh) * blockDim.x + t; k < a.d; k += nrest * blockDim.x)
+    for (int k = a.head + bid * blockDim.x + t; k < a.d; k += nrest * blockDim.x)
       fold.column(k, a.w ? a.acc_w[k] : 0.f, a.phi ? a.acc_p[k] : 0.f);
   }
 }

@@ -69,9 +69,10 @@ struct GenArgs {
   uint8_t *flags;
   float *loss_out;
   const float *loss_in;
-  // atomic accumulators (zeroed before the pass)
+  // atomic accumulators (zeroed before the pass); *acc_used (zeroed too) is set by whoever adds
   float *acc_w;      // [d]
   float *acc_p;      // [d]
+  int32_t *acc_used;
   // per-block kept count and bias-gradient sum of a gradient pass (plain stores)
   int32_t *blk_cnt;  // [blocks of the pass]
   float *blk_gb;     // [blocks of the pass]
@@ -100,6 +101,7 @@ struct ApplyArgs {
   int32_t d;
   const float *acc_w;
   const float *acc_p;
+  const int32_t *acc_used;  // 0: the pass added nothing to the accumulators
   const int32_t *blk_cnt;  // per-block kept counts and bias-gradient sums of the pass
   const float *blk_gb;
   const int32_t *m_dev;
