@@ -32,11 +32,12 @@ __device__ __forceinline__ float gsum(float v) {
   return v;
 }
 
-// Per-block LDS: kDirect* slots for columns 0..kDirect*-1 (one sum per updated vector),
-// kHashed* slots with a column tag each, and a buffer of kRecords records.  About 138 KB with
-// both vectors, 130 KB with one: one block of 16 waves per compute unit.
-constexpr int kDirectTwoVec = 8192, kHashedTwoVec = 2048;
-constexpr int kDirectOneVec = 16384, kHashedOneVec = 4096;
+// Per-block LDS: kDirect* slots for columns 0..kDirect*-1 (one sum per updated vector) and as
+// many entries of the model vectors themselves, kHashed* slots with a column tag each, and a
+// buffer of kRecords records.  About 138 KB with both vectors, 130 KB with one: one block of
+// 16 waves per compute unit.
+constexpr int kDirectTwoVec = 4096, kHashedTwoVec = 2048;
+constexpr int kDirectOneVec = 8192, kHashedOneVec = 4096;
 constexpr int kRecords = 4096;
 constexpr int kGradThreads = 1024, kPoolThreads = 256;
 constexpr int kCheckRows = 16;  // rows per wave between two looks at the record buffer
@@ -129,6 +130,7 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
   constexpr int H = NVEC == 2 ? kHashedTwoVec : kHashedOneVec;  // hashed slots
   constexpr int R = kRecords;                                    // record buffer
   __shared__ float s_sum[GRAD ? NVEC * D : 1];
+  __shared__ float s_model[GRAD ? NVEC * D : 1];  // the first D entries of w and / or phi
   __shared__ int s_tag[GRAD ? H : 1];
   __shared__ float s_hs[GRAD ? NVEC * H : 1];
   __shared__ int s_rc[GRAD ? R : 1];
@@ -138,12 +140,17 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
   __shared__ int s_cnt[16];
   __shared__ float s_gb[16];
   float *const s_w = s_sum, *const s_p = s_sum + (SVM ? D : 0);
+  const float *const s_mw = s_model, *const s_mp = s_model + (SVM ? D : 0);
   float *const s_ra = s_rt, *const s_rb = s_rt + (NVEC == 2 ? R : 0);
   float *const s_ha = s_hs, *const s_hb = s_hs + (NVEC == 2 ? H : 0);
   const bool binned = GRAD && a.plan.nb > 0;
   const int salt = (int)((blockIdx.x * 0x9E3779B1u) >> 19) & (H - 1);
   if (GRAD) {
     for (int k = threadIdx.x; k < NVEC * D; k += blockDim.x) s_sum[k] = 0.f;
+    for (int k = threadIdx.x; k < min(D, a.d); k += blockDim.x) {
+      if (SVM) s_model[k] = a.w[k];
+      if (ASSIST) s_model[(SVM ? D : 0) + k] = a.phi[k];
+    }
     for (int k = threadIdx.x; k < H; k += blockDim.x) s_tag[k] = -1;
     for (int k = threadIdx.x; k < NVEC * H; k += blockDim.x) s_hs[k] = 0.f;
     if (threadIdx.x == 0) s_nrec = 0;
@@ -204,9 +211,9 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
       // kUnroll entries per lane at a time: their column and value loads leave together, then
       // the model gathers that depend on the columns (the chain that bounds this loop)
       constexpr int kUnroll = 8;
-      for (int e = sub; e < len; e += GL * kUnroll) {
-        int c[kUnroll];
-        float xv[kUnroll];
+      int c0[kUnroll];  // the first kUnroll entries of the lane stay in registers for the second walk
+      float x0[kUnroll];
+      auto load_entries = [&](int e, int *c, float *xv) {
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
           const int eu = e + u * GL;
@@ -214,11 +221,31 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
           c[u] = CSR ? (in ? a.col[e0 + eu] : 0) : (in ? eu : 0);
           xv[u] = in ? (CSR ? (a.val ? a.val[e0 + eu] : 1.f) : a.x[e0 + eu]) : 0.f;
         }
+      };
+      auto dot_entries = [&](const int *c, const float *xv) {
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-          if (NEED_PHI) dp = __fmaf_rn(a.phi[c[u]], xv[u], dp);
-          if (SVM) dw = __fmaf_rn(a.w[c[u]], xv[u], dw);
+          if (GRAD) {  // the first columns of the model are in LDS
+            const bool near = c[u] < D;
+            if (NEED_PHI) {
+              const float pv = ASSIST ? (near ? s_mp[c[u]] : a.phi[c[u]]) : a.phi[c[u]];
+              dp = __fmaf_rn(pv, xv[u], dp);
+            }
+            if (SVM) dw = __fmaf_rn(near ? s_mw[c[u]] : a.w[c[u]], xv[u], dw);
+          } else {
+            if (NEED_PHI) dp = __fmaf_rn(a.phi[c[u]], xv[u], dp);
+          }
         }
+      };
+      if (GRAD) {
+        load_entries(sub, c0, x0);
+        dot_entries(c0, x0);
+      }
+      for (int e = sub + (GRAD ? GL * kUnroll : 0); e < len; e += GL * kUnroll) {
+        int c[kUnroll];
+        float xv[kUnroll];
+        load_entries(e, c, xv);
+        dot_entries(c, xv);
       }
       float g = 0.f;
       bool keep = live;
@@ -262,15 +289,7 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
 #pragma unroll
         for (int off = GL; off < kWave; off <<= 1)
           steps_len = max(steps_len, __shfl_xor(steps_len, off, kWave));
-        for (int eb = 0; eb < steps_len; eb += GL) {
-          const int e = eb + sub;
-          const bool active = contrib && e < len;
-          int c = 0;
-          float xv = 0.f;
-          if (active) {
-            c = CSR ? a.col[e0 + e] : e;
-            xv = CSR ? (a.val ? a.val[e0 + e] : 1.f) : a.x[e0 + e];
-          }
+        auto scatter = [&](bool active, int c, float xv) {
           const float ta = SVM ? cw * xv : resid * xv, tb = resid * xv;
           if (active && c < D) {
             if (SVM && cw != 0.f) unsafeAtomicAdd(s_w + c, cw * xv);
@@ -278,13 +297,22 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
           }
           bool tail = active && c >= D;
           if (tail) {  // the column's hashed slot, if it is free or already the column's
+            // (a tag changes once, from -1 to its column: a plain read settles most cases)
+            auto owner_of = [&](int slot) {
+              int t = s_tag[slot];
+              if (t == -1) {
+                const int old = atomicCAS(s_tag + slot, -1, c);
+                t = old == -1 ? c : old;
+              }
+              return t;
+            };
             int h = (c ^ (c >> 11) ^ salt) & (H - 1);
-            int old = atomicCAS(s_tag + h, -1, c);
-            if (old != -1 && old != c) {  // second try, elsewhere in the table
+            int owner = owner_of(h);
+            if (owner != c) {  // second try, elsewhere in the table
               h = (h ^ (H / 2) ^ (c >> 5)) & (H - 1);
-              old = atomicCAS(s_tag + h, -1, c);
+              owner = owner_of(h);
             }
-            if (old == -1 || old == c) {
+            if (owner == c) {
               if (SVM && cw != 0.f) unsafeAtomicAdd(s_ha + h, ta);
               if (ASSIST && resid != 0.f) unsafeAtomicAdd((SVM ? s_hb : s_ha) + h, tb);
               tail = false;
@@ -313,6 +341,21 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
           } else if (tail) {
             add_global<SVM, ASSIST>(a, c, ta, tb);
           }
+                };
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {  // from registers
+          if (u * GL < steps_len) scatter(contrib && sub + u * GL < len, c0[u], x0[u]);
+        }
+        for (int eb = GL * kUnroll; eb < steps_len; eb += GL) {
+          const int e = eb + sub;
+          const bool active = contrib && e < len;
+          int c = 0;
+          float xv = 0.f;
+          if (active) {
+            c = CSR ? a.col[e0 + e] : e;
+            xv = CSR ? (a.val ? a.val[e0 + e] : 1.f) : a.x[e0 + e];
+          }
+          scatter(active, c, xv);
         }
         // every kCheckRows rows per wave the block looks at its record buffer together
         if (binned && ((it + 1) * G) % kCheckRows == 0 && (it + 1 < iters || round + 1 < rounds)) {

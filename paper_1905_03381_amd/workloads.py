@@ -87,7 +87,7 @@ def sparse(a, torch, api, synth):
                         f"{steps} pools per epoch",
             "candidates_per_s": P / us_step * 1e6,
             "stages": [_stage("fused step (score, keep, compact, SVM step, Assistant update)", us_step,
-                              row_bytes, note="bound by fp32 atomics, not by HBM"),
+                              row_bytes, note="bound by LDS atomics and model gathers, not by HBM"),
                        _stage("assistant score only", us_score, row_bytes)]}
 
 
@@ -202,7 +202,7 @@ def translation(a, torch, api, synth):
                        _stage("length-bucketed batches", us_bucket, m * (8 + 4 + 4 + 4)),
                        _stage("compacted CSR of kept pairs", us_rows, 2 * kept_nnz * entry + m * 20),
                        _stage("Assistant update over kept pairs", us_upd, kept_nnz * entry + m * 16,
-                              note="bound by fp32 atomics")]}
+                              note="bound by LDS atomics")]}
 
 
 def _dense_job(a, torch, api, synth):
