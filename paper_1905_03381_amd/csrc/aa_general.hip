@@ -34,13 +34,14 @@ __device__ __forceinline__ float gsum(float v) {
 
 // Per-block LDS: kDirect* slots for columns 0..kDirect*-1 (one sum per updated vector) and as
 // many entries of the model vectors themselves, kHashed* slots with a column tag each, and a
-// buffer of kRecords records.  About 138 KB with both vectors, 130 KB with one: one block of
-// 16 waves per compute unit.
-constexpr int kDirectTwoVec = 4096, kHashedTwoVec = 2048;
-constexpr int kDirectOneVec = 8192, kHashedOneVec = 4096;
-constexpr int kRecords = 4096;
+// buffer of kRecords* records.  About 154 KB: one block of 16 waves per compute unit.
+// The sums are doubles: on MI355X `ds_add_f32` retires about one lane every three cycles,
+// `ds_add_f64` three lanes a cycle (measured, scattered addresses), and the sums come out
+// closer to exact.
+constexpr int kDirectTwoVec = 4096, kHashedTwoVec = 1024, kRecordsTwoVec = 3072;
+constexpr int kDirectOneVec = 8192, kHashedOneVec = 2048, kRecordsOneVec = 4096;
 constexpr int kGradThreads = 1024, kPoolThreads = 256;
-constexpr int kCheckRows = 16;  // rows per wave between two looks at the record buffer
+constexpr int kCheckRows = 4;  // rows per wave between two looks at the record buffer
 
 __device__ __forceinline__ int bin_of(int c, int head, const BinPlan &p) {
   return ((c - head) >> kBinGroupLog2) & (p.nb - 1);
@@ -59,13 +60,12 @@ __device__ __forceinline__ void add_global(const GenArgs &a, int c, float ta, fl
 
 // Empties the block's record buffer -- and with `with_hashed` its hashed slots -- into the
 // bins.  Whole block; the caller has put a barrier between the last append and this call.
-template <int H, bool SVM, bool ASSIST>
+template <int R, int H, bool SVM, bool ASSIST>
 __device__ __forceinline__ void flush_records(const GenArgs &a, int head, const int *s_rc,
                                               const float *s_ra, const float *s_rb, int *s_nrec,
-                                              const int *s_tag, const float *s_ha,
-                                              const float *s_hb, bool with_hashed, int *s_hist,
+                                              const int *s_tag, const double *s_ha,
+                                              const double *s_hb, bool with_hashed, int *s_hist,
                                               int *s_base) {
-  constexpr int R = kRecords;
   constexpr int kPerR = R / kGradThreads, kPer = (R + H) / kGradThreads;
   static_assert(R % kGradThreads == 0 && H % kGradThreads == 0, "whole turns of the block");
   const int n = min(*s_nrec, R);
@@ -96,8 +96,8 @@ __device__ __forceinline__ void flush_records(const GenArgs &a, int head, const 
     const int c = col[q];
     if (c < 0) continue;
     const int i = threadIdx.x + q * kGradThreads;
-    const float ta = q < kPerR ? s_ra[i] : s_ha[i - R];
-    const float tb = (SVM && ASSIST) ? (q < kPerR ? s_rb[i] : s_hb[i - R]) : 0.f;
+    const float ta = q < kPerR ? s_ra[i] : (float)s_ha[i - R];
+    const float tb = (SVM && ASSIST) ? (q < kPerR ? s_rb[i] : (float)s_hb[i - R]) : 0.f;
     const int bin = bin_of(c, head, a.plan);
     const int pos = s_base[bin] + rank[q];
     if (pos < a.plan.cap) {
@@ -128,31 +128,31 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
   constexpr int NVEC = (SVM ? 1 : 0) + (ASSIST ? 1 : 0);
   constexpr int D = NVEC == 2 ? kDirectTwoVec : kDirectOneVec;  // slots 0..D-1: column = slot
   constexpr int H = NVEC == 2 ? kHashedTwoVec : kHashedOneVec;  // hashed slots
-  constexpr int R = kRecords;                                    // record buffer
-  __shared__ float s_sum[GRAD ? NVEC * D : 1];
+  constexpr int R = NVEC == 2 ? kRecordsTwoVec : kRecordsOneVec;  // record buffer
+  __shared__ double s_sum[GRAD ? NVEC * D : 1];
   __shared__ float s_model[GRAD ? NVEC * D : 1];  // the first D entries of w and / or phi
   __shared__ int s_tag[GRAD ? H : 1];
-  __shared__ float s_hs[GRAD ? NVEC * H : 1];
+  __shared__ double s_hs[GRAD ? NVEC * H : 1];
   __shared__ int s_rc[GRAD ? R : 1];
   __shared__ float s_rt[GRAD ? NVEC * R : 1];
   __shared__ int s_hist[GRAD ? kMaxBins : 1], s_base[GRAD ? kMaxBins : 1];
   __shared__ int s_nrec;
   __shared__ int s_cnt[16];
   __shared__ float s_gb[16];
-  float *const s_w = s_sum, *const s_p = s_sum + (SVM ? D : 0);
+  double *const s_w = s_sum, *const s_p = s_sum + (SVM ? D : 0);
   const float *const s_mw = s_model, *const s_mp = s_model + (SVM ? D : 0);
   float *const s_ra = s_rt, *const s_rb = s_rt + (NVEC == 2 ? R : 0);
-  float *const s_ha = s_hs, *const s_hb = s_hs + (NVEC == 2 ? H : 0);
+  double *const s_ha = s_hs, *const s_hb = s_hs + (NVEC == 2 ? H : 0);
   const bool binned = GRAD && a.plan.nb > 0;
   const int salt = (int)((blockIdx.x * 0x9E3779B1u) >> 19) & (H - 1);
   if (GRAD) {
-    for (int k = threadIdx.x; k < NVEC * D; k += blockDim.x) s_sum[k] = 0.f;
+    for (int k = threadIdx.x; k < NVEC * D; k += blockDim.x) s_sum[k] = 0.0;
     for (int k = threadIdx.x; k < min(D, a.d); k += blockDim.x) {
       if (SVM) s_model[k] = a.w[k];
       if (ASSIST) s_model[(SVM ? D : 0) + k] = a.phi[k];
     }
     for (int k = threadIdx.x; k < H; k += blockDim.x) s_tag[k] = -1;
-    for (int k = threadIdx.x; k < NVEC * H; k += blockDim.x) s_hs[k] = 0.f;
+    for (int k = threadIdx.x; k < NVEC * H; k += blockDim.x) s_hs[k] = 0.0;
     if (threadIdx.x == 0) s_nrec = 0;
     __syncthreads();
   }
@@ -237,11 +237,12 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
           }
         }
       };
-      if (GRAD) {
+      constexpr bool KEEP = GRAD && CSR;  // (dense rows here are long: nothing worth keeping)
+      if (KEEP) {
         load_entries(sub, c0, x0);
         dot_entries(c0, x0);
       }
-      for (int e = sub + (GRAD ? GL * kUnroll : 0); e < len; e += GL * kUnroll) {
+      for (int e = sub + (KEEP ? GL * kUnroll : 0); e < len; e += GL * kUnroll) {
         int c[kUnroll];
         float xv[kUnroll];
         load_entries(e, c, xv);
@@ -292,8 +293,8 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
         auto scatter = [&](bool active, int c, float xv) {
           const float ta = SVM ? cw * xv : resid * xv, tb = resid * xv;
           if (active && c < D) {
-            if (SVM && cw != 0.f) unsafeAtomicAdd(s_w + c, cw * xv);
-            if (ASSIST && resid != 0.f) unsafeAtomicAdd(s_p + c, resid * xv);
+            if (SVM && cw != 0.f) unsafeAtomicAdd(s_w + c, (double)(cw * xv));
+            if (ASSIST && resid != 0.f) unsafeAtomicAdd(s_p + c, (double)(resid * xv));
           }
           bool tail = active && c >= D;
           if (tail) {  // the column's hashed slot, if it is free or already the column's
@@ -313,8 +314,8 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
               owner = owner_of(h);
             }
             if (owner == c) {
-              if (SVM && cw != 0.f) unsafeAtomicAdd(s_ha + h, ta);
-              if (ASSIST && resid != 0.f) unsafeAtomicAdd((SVM ? s_hb : s_ha) + h, tb);
+              if (SVM && cw != 0.f) unsafeAtomicAdd(s_ha + h, (double)ta);
+              if (ASSIST && resid != 0.f) unsafeAtomicAdd((SVM ? s_hb : s_ha) + h, (double)tb);
               tail = false;
             }
           }
@@ -342,11 +343,13 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
             add_global<SVM, ASSIST>(a, c, ta, tb);
           }
                 };
+        if (KEEP) {
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {  // from registers
-          if (u * GL < steps_len) scatter(contrib && sub + u * GL < len, c0[u], x0[u]);
+          for (int u = 0; u < kUnroll; ++u) {  // from registers
+            if (u * GL < steps_len) scatter(contrib && sub + u * GL < len, c0[u], x0[u]);
+          }
         }
-        for (int eb = GL * kUnroll; eb < steps_len; eb += GL) {
+        for (int eb = KEEP ? GL * kUnroll : 0; eb < steps_len; eb += GL) {
           const int e = eb + sub;
           const bool active = contrib && e < len;
           int c = 0;
@@ -363,7 +366,7 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
           const int fill = s_nrec;
           __syncthreads();
           if (fill > R / 2)
-            flush_records<H, SVM, ASSIST>(a, D, s_rc, s_ra, s_rb, &s_nrec, s_tag, s_ha, s_hb,
+            flush_records<R, H, SVM, ASSIST>(a, D, s_rc, s_ra, s_rb, &s_nrec, s_tag, s_ha, s_hb,
                                           false, s_hist, s_base);
         }
       }
@@ -398,16 +401,17 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
     // the first columns: this block's sums, zeros included, as plain stores
     float *const mine = a.part + (size_t)blockIdx.x * NVEC * a.head;
     for (int k = threadIdx.x; k < a.head; k += blockDim.x) {
-      if (SVM) mine[k] = s_w[k];
-      if (ASSIST) mine[(SVM ? a.head : 0) + k] = s_p[k];
+      if (SVM) mine[k] = (float)s_w[k];
+      if (ASSIST) mine[(SVM ? a.head : 0) + k] = (float)s_p[k];
     }
     if (binned) {
-      flush_records<H, SVM, ASSIST>(a, D, s_rc, s_ra, s_rb, &s_nrec, s_tag, s_ha, s_hb, true,
+      flush_records<R, H, SVM, ASSIST>(a, D, s_rc, s_ra, s_rb, &s_nrec, s_tag, s_ha, s_hb, true,
                                     s_hist, s_base);
     } else {
       for (int k = threadIdx.x; k < H; k += blockDim.x) {
         const int c = s_tag[k];
-        if (c >= 0) add_global<SVM, ASSIST>(a, c, s_ha[k], (SVM && ASSIST) ? s_hb[k] : 0.f);
+        if (c >= 0)
+          add_global<SVM, ASSIST>(a, c, (float)s_ha[k], (SVM && ASSIST) ? (float)s_hb[k] : 0.f);
       }
     }
   }
@@ -486,7 +490,7 @@ __device__ __forceinline__ int bin_column(int k, int bin, const ApplyArgs &a) {
 
 // The block that owns a bin.  Everything it needs from memory (the first records and columns
 // per thread, in registers) is requested before anything is used: one round trip, not five.
-__device__ void apply_bin(const ApplyArgs &a, int bin, float *s_bin, int *s_m, float *s_g) {
+__device__ void apply_bin(const ApplyArgs &a, int bin, double *s_bin, int *s_m, float *s_g) {
   constexpr int kRec = 16, kCol = 16;
   const int tid = threadIdx.x, cols = a.plan.cols, cap = a.plan.cap;
   const int cnt = tid < a.nblk_pass ? a.blk_cnt[tid] : 0;
@@ -528,16 +532,16 @@ __device__ void apply_bin(const ApplyArgs &a, int bin, float *s_bin, int *s_m, f
   const int span = a.nvec * cols + 1;
   int copies = 1;
   while (copies < 16 && 2 * copies * span <= kBinColsMax) copies *= 2;
-  float *const s_mine = s_bin + (tid & (copies - 1)) * span;
-  for (int k = tid; k < copies * span; k += kApplyThreads) s_bin[k] = 0.f;
+  double *const s_mine = s_bin + (tid & (copies - 1)) * span;
+  for (int k = tid; k < copies * span; k += kApplyThreads) s_bin[k] = 0.0;
   float gb_unused;
   const int m = pass_totals(a, cnt, 0.f, s_m, s_g, &gb_unused);  // barrier: the sums are zero
   const Fold fold(a, m);
   const int n = min(fill, cap);
   auto add = [&](int c, float ta, float tb) {
     const int k = bin_local(c, a);
-    if (ta != 0.f) unsafeAtomicAdd(s_mine + k, ta);
-    if (a.nvec == 2 && tb != 0.f) unsafeAtomicAdd(s_mine + cols + k, tb);
+    if (ta != 0.f) unsafeAtomicAdd(s_mine + k, (double)ta);
+    if (a.nvec == 2 && tb != 0.f) unsafeAtomicAdd(s_mine + cols + k, (double)tb);
   };
   for (int base = 0; base < n; base += kRec * kApplyThreads) {
     if (base > 0) {  // further batches: again all loads first
@@ -553,9 +557,9 @@ __device__ void apply_bin(const ApplyArgs &a, int bin, float *s_bin, int *s_m, f
   }
   __syncthreads();
   auto sum_of = [&](int k) {  // over the copies, in order
-    float v = 0.f;
+    double v = 0.0;
     for (int c = 0; c < copies; ++c) v += s_bin[c * span + k];
-    return v;
+    return (float)v;
   };
   // (the dense accumulators hold something only if an entry found no room in LDS or in a bin)
   auto acc_w_of = [&](int c) { return (acc_used && a.w) ? a.acc_w[c] : 0.f; };
@@ -580,7 +584,7 @@ __global__ __launch_bounds__(kApplyThreads) void k_apply_general(const ApplyArgs
   __shared__ float s_part[2][16][kHeadCols];
   __shared__ int s_m[4];
   __shared__ float s_g[4];
-  __shared__ float s_bin[kBinColsMax + 1];  // (+1: the odd stride of a single copy)
+  __shared__ double s_bin[kBinColsMax + 1];  // (+1: the odd stride of a single copy)
   // roles by block number: the other columns first (the bin owners have the longest way to
   // go), then the first columns, then the compaction tiles
   const int bid = (int)blockIdx.x, hb = bid - nrest;

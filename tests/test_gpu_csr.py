@@ -316,13 +316,15 @@ def _col_abs_sum_sp(Fh, ids, d):
     return np.asarray(S[np.asarray(ids)].sum(axis=0)).ravel()
 
 
-def test_csr_updates_many_rows_per_block_uniform_columns(ref):
-    """300,000 kept rows with columns uniform over d = 2^18: nearly every entry falls outside
-    the per-block table, every block makes two rounds, and its entry buffer fills more than
-    once (emptied between the rounds, the excess added to the accumulators directly)."""
+@pytest.mark.parametrize("n,nnz_lo,nnz_hi", [(300_000, 8, 16), (3000, 500, 700)])
+def test_csr_updates_uniform_columns(ref, n, nnz_lo, nnz_hi):
+    """Columns uniform over d = 2^18: nearly every entry falls outside the per-block table.
+    300,000 short rows: every block makes two rounds and empties its entry buffer many times.
+    3000 rows of about 600 entries: the entries of four rows per wave overflow the buffer, and
+    the bins (48 records per candidate) overflow too, so the excess goes to the accumulators."""
     r = rng(21)
-    n, d, m = 300_000, 1 << 18, 300_000
-    rowptr, col, val = _uniform_csr(r, n, d, 8, 16)
+    d, m = 1 << 18, n
+    rowptr, col, val = _uniform_csr(r, n, d, nnz_lo, nnz_hi)
     y = np.where(r.random(n) < 0.5, -1.0, 1.0).astype(np.float32)
     w0 = (2.0 * r.standard_normal(d)).astype(np.float32)
     phi0 = r.standard_normal(d).astype(np.float32)
