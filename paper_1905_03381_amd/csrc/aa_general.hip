@@ -490,31 +490,36 @@ __device__ __forceinline__ int bin_column(int k, int bin, const ApplyArgs &a) {
 
 // The block that owns a bin.  Everything it needs from memory (the first records and columns
 // per thread, in registers) is requested before anything is used: one round trip, not five.
-__device__ void apply_bin(const ApplyArgs &a, int bin, double *s_bin, int *s_m, float *s_g) {
+__device__ __forceinline__ void apply_bin(const ApplyArgs &a, int bin, double *s_bin, int *s_m,
+                                          float *s_g) {
   constexpr int kRec = 16, kCol = 16;
   const int tid = threadIdx.x, cols = a.plan.cols, cap = a.plan.cap;
   const int cnt = tid < a.nblk_pass ? a.blk_cnt[tid] : 0;
   const int fill = a.bin_fill[bin];
   const int acc_used = *a.acc_used;
   const TailRecord *rec = a.bins + (size_t)bin * cap;
-  int rc[kRec];  // records: column and the two terms (the fourth word of a record is padding)
-  float ra[kRec], rb[kRec];
-  auto load_record = [&](int u, int i) {
-    const int *words = reinterpret_cast<const int *>(rec + i);
-    rc[u] = words[0];
-    ra[u] = __int_as_float(words[1]);
-    rb[u] = __int_as_float(words[2]);
-  };
+  // records: column and the two terms (the fourth word of a record is padding); two register
+  // sets, so that the loads of the next batch are in flight while this one is added up
+  int c0[kRec], c1[kRec];
+  float a0[kRec], b0[kRec], a1[kRec], b1[kRec];
+  constexpr int kBatch = kRec * kApplyThreads;
+  auto load_batch = [&](int *__restrict__ tc, float *__restrict__ ta, float *__restrict__ tb,
+                        int base, int limit) __attribute__((always_inline)) {
 #pragma unroll
-  for (int u = 0; u < kRec; ++u) {
-    const int i = tid + u * kApplyThreads;
-    if (i < cap) {  // past the fill count: stale, in bounds, not used
-      load_record(u, i);
-    } else {
-      rc[u] = a.head;
-      ra[u] = rb[u] = 0.f;
+    for (int u = 0; u < kRec; ++u) {
+      const int i = base + tid + u * kApplyThreads;
+      if (i < limit) {
+        const int *words = reinterpret_cast<const int *>(rec + i);
+        tc[u] = words[0];
+        ta[u] = __int_as_float(words[1]);
+        tb[u] = __int_as_float(words[2]);
+      } else {
+        tc[u] = a.head;
+        ta[u] = tb[u] = 0.f;
+      }
     }
-  }
+  };
+  load_batch(c0, a0, b0, 0, cap);  // past the fill count: stale, in bounds, not used
   int col[kCol];
   float wo[kCol], po[kCol];
 #pragma unroll
@@ -543,17 +548,17 @@ __device__ void apply_bin(const ApplyArgs &a, int bin, double *s_bin, int *s_m, 
     if (ta != 0.f) unsafeAtomicAdd(s_mine + k, (double)ta);
     if (a.nvec == 2 && tb != 0.f) unsafeAtomicAdd(s_mine + cols + k, (double)tb);
   };
-  for (int base = 0; base < n; base += kRec * kApplyThreads) {
-    if (base > 0) {  // further batches: again all loads first
-#pragma unroll
-      for (int u = 0; u < kRec; ++u) {
-        const int i = base + tid + u * kApplyThreads;
-        if (i < n) load_record(u, i);
-      }
-    }
+  auto add_batch = [&](const int *tc, const float *ta, const float *tb, int base)
+      __attribute__((always_inline)) {
 #pragma unroll
     for (int u = 0; u < kRec; ++u)
-      if (base + tid + u * kApplyThreads < n) add(rc[u], ra[u], rb[u]);
+      if (base + tid + u * kApplyThreads < n) add(tc[u], ta[u], tb[u]);
+  };
+  for (int base = 0; base < n; base += 2 * kBatch) {
+    if (base + kBatch < n) load_batch(c1, a1, b1, base + kBatch, n);
+    add_batch(c0, a0, b0, base);
+    if (base + 2 * kBatch < n) load_batch(c0, a0, b0, base + 2 * kBatch, n);
+    if (base + kBatch < n) add_batch(c1, a1, b1, base + kBatch);
   }
   __syncthreads();
   auto sum_of = [&](int k) {  // over the copies, in order
