@@ -120,7 +120,7 @@ __global__ __launch_bounds__(256) void k_bucket_counts(const BucketArgs a) {
   for (int r = r0 + threadIdx.x; r < min(m, r0 + kBucketTile); r += 256)
     atomicAdd(&hist[bucket_of(a.len_s[r], a.len_t[r], a.width, a.n_buckets)], 1);
   __syncthreads();
-  if (threadIdx.x < a.n_buckets) a.tile_base[blockIdx.x * a.n_buckets + threadIdx.x] = hist[threadIdx.x];
+  if ((int)threadIdx.x < a.n_buckets) a.tile_base[blockIdx.x * a.n_buckets + threadIdx.x] = hist[threadIdx.x];
 }
 
 // One block, one wave per bucket (16 waves, each taking buckets w, w + 16): per-bucket totals over
