@@ -23,9 +23,11 @@ struct BinPlan {
 constexpr int kMaxBins = 256;
 constexpr int kBinGroupLog2 = 4, kBinGroup = 1 << kBinGroupLog2;
 constexpr int kBinColsMax = 8192;  // LDS floats of a bin's owner in the update kernel
+// Records the bins hold in all: 48 per candidate (the sparse configuration needs about 26),
+// at least 65,536, at most 2^27 (2 GiB); what does not fit goes to the accumulators.
 inline size_t general_record_capacity(int32_t count_max) {
   const size_t want = 48 * (size_t)(count_max > 0 ? count_max : 0);
-  return want < 65536 ? 65536 : want;
+  return want < 65536 ? 65536 : (want > ((size_t)1 << 27) ? ((size_t)1 << 27) : want);
 }
 inline BinPlan general_bin_plan(int32_t d, int32_t head, int nvec, int32_t count_max) {
   BinPlan p{0, 0, 0, 0};
