@@ -238,7 +238,7 @@ hipError_t run_pass(const PassSpec &s, const Ws &ws, int32_t *nblk_out, hipStrea
   a.acc_p = acc + kGeneralHeader + s.F->d;
   a.part = acc + kGeneralHeader + 2 * (size_t)s.F->d;
   a.head = general_head_columns(s.F->d, nvec);
-  a.bin_fill = reinterpret_cast<int32_t *>(acc) + 16;
+  a.bin_fill = reinterpret_cast<unsigned long long *>(acc + 16);
   a.bins = reinterpret_cast<TailRecord *>(ws.grad + general_bins_offset(s.F->d));
   a.plan = general_bin_plan(s.F->d, a.head, nvec, s.count_max);
   const int32_t nblk = general_pass_blocks(s.count_max, csr, s.mode);
@@ -312,7 +312,7 @@ hipError_t run_update(const PassSpec &s, const UpdateSpec &u, const Ws &ws, int3
   p.part = acc + kGeneralHeader + 2 * (size_t)s.F->d;
   p.nvec = ((s.mode & kSvm) ? 1 : 0) + ((s.mode & kAssist) ? 1 : 0);
   p.head = general_head_columns(s.F->d, p.nvec);
-  p.bin_fill = reinterpret_cast<const int32_t *>(acc) + 16;
+  p.bin_fill = reinterpret_cast<const unsigned long long *>(acc + 16);
   p.bins = reinterpret_cast<const TailRecord *>(ws.grad + general_bins_offset(s.F->d));
   p.plan = general_bin_plan(s.F->d, p.head, p.nvec, s.count_max);
   p.nblk_pass = nblk;

@@ -88,7 +88,10 @@ __device__ __forceinline__ void flush_records(const GenArgs &a, int head, const 
   __syncthreads();
   for (int t = threadIdx.x; t < nb; t += blockDim.x) {
     const int h = s_hist[t];
-    s_base[t] = h > 0 ? atomicAdd(a.bin_fill + t, h) : 0;
+    // (64-bit fill counts: they keep counting past the capacity; the base is clamped to it)
+    s_base[t] = h > 0 ? (int)min(atomicAdd(a.bin_fill + t, (unsigned long long)h),
+                                 (unsigned long long)a.plan.cap)
+                      : 0;
   }
   __syncthreads();
 #pragma unroll
@@ -330,7 +333,7 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
                 const int pos = first + (int)__builtin_amdgcn_mbcnt_hi(
                                             (uint32_t)(mask >> 32),
                                             __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-                if (pos < R) {
+                if ((unsigned)pos < (unsigned)R) {
                   s_rc[pos] = c;
                   s_ra[pos] = ta;
                   if (NVEC == 2) s_rb[pos] = tb;
@@ -495,7 +498,7 @@ __device__ __forceinline__ void apply_bin(const ApplyArgs &a, int bin, double *s
   constexpr int kRec = 16, kCol = 16;
   const int tid = threadIdx.x, cols = a.plan.cols, cap = a.plan.cap;
   const int cnt = tid < a.nblk_pass ? a.blk_cnt[tid] : 0;
-  const int fill = a.bin_fill[bin];
+  const int fill = (int)min(a.bin_fill[bin], (unsigned long long)cap);
   const int acc_used = *a.acc_used;
   const TailRecord *rec = a.bins + (size_t)bin * cap;
   // records: column and the two terms (the fourth word of a record is padding); two register

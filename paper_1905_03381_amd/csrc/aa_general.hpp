@@ -85,7 +85,7 @@ struct GenArgs {
   // entries of the other columns leave a block as records, sorted into bins by column
   // (see BinPlan); fill[bin] counts the records offered to a bin, zeroed before the pass
   TailRecord *bins;
-  int32_t *bin_fill;
+  unsigned long long *bin_fill;
   BinPlan plan;
 };
 
@@ -93,7 +93,8 @@ struct GenArgs {
 // that updates nvec vectors over d columns; blocks of a gradient pass at most.
 int32_t general_head_columns(int32_t d, int nvec);
 constexpr int kGeneralGradBlocks = 256;
-constexpr int kGeneralHeader = 16 + kMaxBins;  // floats ahead of the accumulators: scalars, bin fill counts
+// floats ahead of the accumulators: 16 scalars, then the 64-bit fill counts of the bins
+constexpr int kGeneralHeader = 16 + 2 * kMaxBins;
 inline size_t general_part_floats(int32_t d) {
   const size_t per_block = 2 * (size_t)d < 16384 ? 2 * (size_t)d : 16384;
   return kGeneralGradBlocks * per_block;
@@ -116,7 +117,7 @@ struct ApplyArgs {
   const float *part;  // per-block sums of the first `head` columns (see GenArgs)
   int32_t head, nvec, nblk_pass;
   const TailRecord *bins;  // records of the other columns (see GenArgs)
-  const int32_t *bin_fill;
+  const unsigned long long *bin_fill;
   BinPlan plan;
   float lambda, lr, lr_a, l2_a;
   int32_t *kept_hist;
