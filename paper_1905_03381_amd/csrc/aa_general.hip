@@ -420,10 +420,13 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
   }
 }
 
+// p is 16-byte aligned: 128-bit stores, then the few floats left over.
 __global__ __launch_bounds__(256) void k_zero_f32(float *p, size_t count) {
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
-       i += (size_t)gridDim.x * blockDim.x)
-    p[i] = 0.f;
+  const size_t n4 = count / 4, tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  float4 *p4 = reinterpret_cast<float4 *>(p);
+  for (size_t i = tid; i < n4; i += stride) p4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (tid < count - 4 * n4) p[4 * n4 + tid] = 0.f;
 }
 
 // Folds the gradient sums into the model.  Blocks [0, nh): 16 of the first `head` columns each,
@@ -713,8 +716,10 @@ hipError_t launch_general_pass(const GenArgs &a, int mode, bool csr, int32_t nbl
 
 hipError_t launch_zero_f32(float *p, size_t count, hipStream_t st) {
   if (count == 0) return hipSuccess;
-  size_t blocks = (count + 1023) / 1024;
+  if ((reinterpret_cast<uintptr_t>(p) & 15) != 0) return hipErrorInvalidValue;
+  size_t blocks = (count / 4 + 255) / 256;
   if (blocks > 2048) blocks = 2048;
+  if (blocks < 1) blocks = 1;
   hipLaunchKernelGGL(k_zero_f32, dim3((unsigned)blocks), dim3(256), 0, st, p, count);
   return hipGetLastError();
 }
