@@ -1,7 +1,8 @@
 // General row passes: CSR rows, and dense rows the register-resident kernels
 // cannot take (d > 2048, d % 4 != 0, unaligned).  A group of GL lanes walks the
 // stored entries of a row; phi and w are read through the caches (they are the
-// only reused data); a second kernel folds the gradient sums into the model.
+// only reused data; a gradient pass keeps their first entries in LDS); a second
+// kernel folds the gradient sums into the model.
 // Device-wide fp32 atomics are what such a pass must avoid on MI355X: about 20 G/s
 // on scattered addresses, and adds to one address run one after the other, about
 // 13 ns each, while bag-of-words data puts most entries on a few hot columns.  So:
@@ -15,7 +16,7 @@
 //    sorted by column bin, into per-bin arrays, and so are the hashed slots at the
 //    end; the block that owns a bin in the second kernel sums its records in LDS.
 //    One integer atomic per block, bin and flush reserves the space.  The buffer is
-//    emptied whenever the block finds it half full after 16 rows per wave;
+//    emptied whenever the block finds it half full after 4 rows per wave;
 //  * only what does not fit (records beyond the LDS buffer or a bin's capacity, or
 //    more columns than the bins can cover) is added to dense accumulators in HBM.
 #include "aa_compact.hpp"
