@@ -452,9 +452,9 @@ def test_csr_updates_random_shapes(ref, block):
         loss = torch.zeros(m, device="cuda")
         api.svm_sgd_step(F, dev(y), dev(rows), scalar_dev(m, torch.int32), m, w, lam, lr, 0.0, loss, ws)
         assert_close_scaled(host(loss), loss_ref, Sdot, "loss " + tag, atol=1e-6)
-        absx = np.asarray(Sa[rows[dots < 1]].sum(axis=0)).ravel()
+        absx_w = np.asarray(Sa[rows[dots < 1]].sum(axis=0)).ravel()
         akink = np.asarray(Sa[rows[kink]].sum(axis=0)).ravel()
-        assert_close_scaled(host(w), w_ref, np.abs(w0.astype(np.float64)) + lr / m * absx, "w " + tag,
+        assert_close_scaled(host(w), w_ref, np.abs(w0.astype(np.float64)) + lr / m * absx_w, "w " + tag,
                             atol=lr / m * akink)
         phi_ref, b_ref = ref.assistant_update(Fh, rows, m, loss_ref, T, phi0, b0, lr_a)
         phi, b = dev(phi0), scalar_dev(b0)
@@ -464,3 +464,17 @@ def test_csr_updates_random_shapes(ref, block):
         assert_close_scaled(host(phi), phi_ref, np.abs(phi0.astype(np.float64)) + lr_a / m * absx,
                             "phi " + tag)
         assert abs(float(host(b)[0]) - b_ref) <= RTOL * (abs(b0) + lr_a), tag
+        # both updates in one pass over the rows (labels from the kernel's own losses: a row
+        # whose loss sits within rounding of T may take either label)
+        w, phi, b = dev(w0), dev(phi0), scalar_dev(b0)
+        Tt = scalar_dev(T)
+        cfg = api.step_config(0.0, lam, lr, lr_a, 0.0, 1, 0, Tt)
+        api.boss_assistant_step(F, dev(y), dev(rows), scalar_dev(m, torch.int32), m, w, phi, b, cfg,
+                                loss, ws)
+        assert_close_scaled(host(w), w_ref, np.abs(w0.astype(np.float64)) + lr / m * absx_w,
+                            "w (one pass) " + tag, atol=lr / m * akink)
+        on_T = np.abs(loss_ref.astype(np.float64) - T) <= RTOL * Sdot
+        a_T = np.asarray(Sa[rows[on_T]].sum(axis=0)).ravel()
+        assert_close_scaled(host(phi), phi_ref, np.abs(phi0.astype(np.float64)) + lr_a / m * absx,
+                            "phi (one pass) " + tag, atol=lr_a / m * a_T)
+        assert abs(float(host(b)[0]) - b_ref) <= RTOL * (abs(b0) + lr_a) + lr_a / m * on_T.sum(), tag
