@@ -41,6 +41,7 @@ SCORE_SHAPES = [
     (400, 200, 256, 400),       # padded rows (ld > d), masked lanes
     (300, 130, None, 250),      # d % 4 != 0 -> general kernel
     (200, 4100, None, 150),     # d > 2048 -> general kernel
+    (120, 9000, None, 100),     # general kernel, thousands of columns past its LDS table
     (64, 1024, None, 1),        # single candidate
 ]
 
@@ -212,6 +213,7 @@ SGD_SHAPES = [
     (400, 200, 256, 250),
     (300, 130, None, 111),     # general kernel (atomics)
     (200, 4100, None, 90),     # general kernel
+    (120, 9000, None, 100),    # general kernel, thousands of columns past its LDS table
     (64, 1024, None, 1),
 ]
 
