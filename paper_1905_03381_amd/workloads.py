@@ -130,13 +130,27 @@ def images(a, torch, api, synth):
             api.threshold_update(losses[i], sizes[i], B, 0.9, T, init)
             api.assistant_update(F, ids[i * B:], sizes[i], B, losses[i], T, phi, b, 0.05, 0.0, ws)
 
-    us_upd = _timed(torch, updates, a.repeats, lambda: (phi.copy_(phi0), b.zero_(), init.zero_()))
-    total = us_score + us_gather + us_upd
+    reset = lambda: (phi.copy_(phi0), b.zero_(), init.zero_())
+    us_upd = _timed(torch, updates, a.repeats, reset)
+    # the same sequence of launches replayed as one hipGraph
+    reset()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        updates()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        updates()
+    us_upd_graph = _timed(torch, graph.replay, a.repeats, reset)
+    total = us_score + us_gather + us_upd_graph
     return {"workload": f"image batch generator P={P} d={d} image {row_bytes} B, batches of {B}",
             "kept": m, "images_per_s": m / total * 1e6, "candidates_per_s": P / total * 1e6,
             "stages": [_stage("score + keep + compact", us_score, P * (4 * d + 4 + 1 + 4) + 4 * m),
                        _stage("gather kept images", us_gather, 2 * m * row_bytes + 12 * m),
                        _stage("running median + Assistant update, per batch", us_upd / nb,
+                              B * (4 * d + 4 + 4), calls=nb, note="eager launches"),
+                       _stage("the same, all batches replayed as one hipGraph", us_upd_graph / nb,
                               B * (4 * d + 4 + 4), calls=nb, note="launch-latency bound")]}
 
 
