@@ -109,7 +109,7 @@ class Job:
 
     def run(self, g0, g1, hook=None, hooks=None):
         """Enqueue global steps [g0, g1) on the current stream.  hook(g): called before a step
-        whose row-pass kernel should be bracketed by events (per-step pipelines); hooks(g, last):
+        whose row-pass kernel should give its time stamps to events (per-step pipelines); hooks(g, last):
         the same for the steps [g, last) of one epoch call of the fused pipeline."""
         api, a = self.api, self.a
         if a.pipeline == "fused":
@@ -252,9 +252,10 @@ def main():
             if g_hi > g_lo:
                 keep_by_epoch.append(float(hist[g_lo:g_hi].sum()) / job.candidates(g_lo, g_hi))
 
-    # ---- dominant kernel: the row pass, timed live with HIP events around every launch
-    # (torch events are hipEvent_t underneath: recorded once here so that they exist, then
-    # re-recorded by the library's hook on the stream the kernel is launched on)
+    # ---- dominant kernel: the row pass, timed live with HIP events: every launch hands its own
+    # start and stop time stamps to a pair of them (torch events are hipEvent_t underneath:
+    # recorded once here so that they exist, then stamped by the library's launch on the stream
+    # the kernel runs on)
     pairs, keepalive = {}, []
 
     def new_pair(g):

@@ -91,10 +91,12 @@ int32_t aa_workspace_init(void *ws, size_t ws_bytes, void *stream);
 
 /* Measurement aid: arm a one-shot hook so that the NEXT row-pass kernel launched by
  * this library (the kernel that streams the feature rows, in whichever entry
- * point launches it) is bracketed by hipEventRecord(event_before) and
- * hipEventRecord(event_after) on the call's stream.  Both are hipEvent_t handles
- * owned by the caller, passed as void*.  Two NULLs disarm.  Host state only, not
- * thread safe. */
+ * point launches it) hands its own start and stop time stamps to the two events
+ * (hipExtLaunchKernel with start and stop events, on the call's stream), so that
+ * hipEventElapsedTime(event_before, event_after) is the kernel's duration.  Both
+ * are hipEvent_t handles created with timing enabled, owned by the caller, passed
+ * as void*.  Two NULLs disarm.  Not for calls under stream capture.  Host state
+ * only, not thread safe. */
 int32_t aa_profile_hook(void *event_before, void *event_after);
 
 /* The same for the next `count` row-pass launches, pair i around the i-th of

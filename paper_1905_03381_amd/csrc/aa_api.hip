@@ -100,24 +100,20 @@ bool vec_ok(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; 
 
 hipStream_t as_stream(void *s) { return static_cast<hipStream_t>(s); }
 
-// Timing hook: the next row-pass launches are bracketed by caller events, one pair each
-// (the caller's arrays must outlive the launches they arm).
+// Timing hook: the next row-pass launches hand their own start and stop time stamps to caller
+// events, one pair each (the caller's arrays must outlive the launches they arm).
 void *const *g_hook_before = nullptr, *const *g_hook_after = nullptr;
 void *g_hook_single[2] = {nullptr, nullptr};
 int32_t g_hook_left = 0;
 
-struct HookScope {
-  hipStream_t st;
-  hipEvent_t after;
-  explicit HookScope(hipStream_t s) : st(s), after(nullptr) {
+struct Hook {
+  hipEvent_t started = nullptr, stopped = nullptr;
+  Hook() {
     if (g_hook_left > 0) {
       --g_hook_left;
-      after = static_cast<hipEvent_t>(*g_hook_after++);
-      (void)hipEventRecord(static_cast<hipEvent_t>(*g_hook_before++), st);
+      started = static_cast<hipEvent_t>(*g_hook_before++);
+      stopped = static_cast<hipEvent_t>(*g_hook_after++);
     }
-  }
-  ~HookScope() {
-    if (after) (void)hipEventRecord(after, st);
   }
 };
 
@@ -197,8 +193,8 @@ hipError_t run_pass(const PassSpec &s, const Ws &ws, int32_t *nblk_out, hipStrea
                          (reinterpret_cast<uintptr_t>(a.prev.flags) & 15) != 0))
       return hipErrorInvalidValue;  // the caller plans carried compactions within capacity
     *nblk_out = nblk;
-    HookScope hook(st);
-    return launch_dense_pass(a, s.mode, s.F->d, nblk, st);
+    const Hook hook;
+    return launch_dense_pass(a, s.mode, s.F->d, nblk, st, hook.started, hook.stopped);
   }
   const bool csr = s.F->layout == AA_CSR;
   float *acc = reinterpret_cast<float *>(ws.grad);
@@ -243,8 +239,8 @@ hipError_t run_pass(const PassSpec &s, const Ws &ws, int32_t *nblk_out, hipStrea
   a.plan = general_bin_plan(s.F->d, a.head, nvec, s.count_max);
   const int32_t nblk = general_pass_blocks(s.count_max, csr, s.mode);
   *nblk_out = nblk;
-  HookScope hook(st);
-  return launch_general_pass(a, s.mode, csr, nblk, st);
+  const Hook hook;
+  return launch_general_pass(a, s.mode, csr, nblk, st, hook.started, hook.stopped);
 }
 
 struct UpdateSpec {

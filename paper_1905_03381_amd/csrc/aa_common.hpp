@@ -2,6 +2,7 @@
 // reductions and scans, workspace layout.  CDNA4 only (wave64).
 #pragma once
 
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -28,6 +29,17 @@ constexpr size_t kWsScalars = kWsBlkGb + sizeof(float) * kMaxBlocks;
 constexpr size_t kWsBody = kWsScalars + 256;
 
 __host__ __device__ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// A kernel launch whose own start and stop time stamps go to a pair of caller events when
+// both are given (a measurement aid: not for use under stream capture).
+template <typename Kernel, typename Args>
+inline void launch_stamped(Kernel kernel, dim3 grid, dim3 block, hipStream_t stream,
+                           hipEvent_t started, hipEvent_t stopped, const Args &args) {
+  if (started && stopped)
+    hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, started, stopped, 0, args);
+  else
+    hipLaunchKernelGGL(kernel, grid, block, 0, stream, args);
+}
 
 // ---- Philox4x32-10 (Salmon et al., SC'11) ---------------------------------
 // Counter (j, 0, step_lo, step_hi), key (seed_lo, seed_hi); returns word 0.

@@ -536,25 +536,24 @@ int waves_per_block(const Shape &s, int mode) {
 }
 
 template <int LPR, int VPL, int NW, int RIF>
-hipError_t launch_grad(const PassArgs &a, int mode, int nblk, hipStream_t st) {
+hipError_t launch_grad(const PassArgs &a, int mode, int nblk, hipStream_t st, hipEvent_t e0,
+                       hipEvent_t e1) {
   const dim3 grid(nblk), block(NW * 64);
   switch (mode) {
     case kSvm:
-      hipLaunchKernelGGL((k_rows_pass<LPR, VPL, kSvm, NW, RIF>), grid, block, 0, st, a);
+      launch_stamped((k_rows_pass<LPR, VPL, kSvm, NW, RIF>), grid, block, st, e0, e1, a);
       break;
     case kAssist:
-      hipLaunchKernelGGL((k_rows_pass<LPR, VPL, kAssist, NW, RIF>), grid, block, 0, st, a);
+      launch_stamped((k_rows_pass<LPR, VPL, kAssist, NW, RIF>), grid, block, st, e0, e1, a);
       break;
     case kSvm | kAssist:
-      hipLaunchKernelGGL((k_rows_pass<LPR, VPL, kSvm | kAssist, NW, RIF>), grid, block, 0, st, a);
+      launch_stamped((k_rows_pass<LPR, VPL, kSvm | kAssist, NW, RIF>), grid, block, st, e0, e1, a);
       break;
     case kPool | kSvm | kAssist:
-      hipLaunchKernelGGL((k_rows_pass<LPR, VPL, kPool | kSvm | kAssist, NW, RIF>), grid, block, 0,
-                         st, a);
+      launch_stamped((k_rows_pass<LPR, VPL, kPool | kSvm | kAssist, NW, RIF>), grid, block, st, e0, e1, a);
       break;
     case kPool | kSvm | kHard:
-      hipLaunchKernelGGL((k_rows_pass<LPR, VPL, kPool | kSvm | kHard, NW, RIF>), grid, block, 0,
-                         st, a);
+      launch_stamped((k_rows_pass<LPR, VPL, kPool | kSvm | kHard, NW, RIF>), grid, block, st, e0, e1, a);
       break;
     default:
       return hipErrorInvalidValue;
@@ -563,8 +562,8 @@ hipError_t launch_grad(const PassArgs &a, int mode, int nblk, hipStream_t st) {
 }
 
 template <int LPR, int VPL, int RIF>
-hipError_t launch_pool(const PassArgs &a, int nblk, hipStream_t st) {
-  hipLaunchKernelGGL((k_rows_pass<LPR, VPL, kPool, 4, RIF>), dim3(nblk), dim3(256), 0, st, a);
+hipError_t launch_pool(const PassArgs &a, int nblk, hipStream_t st, hipEvent_t e0, hipEvent_t e1) {
+  launch_stamped((k_rows_pass<LPR, VPL, kPool, 4, RIF>), dim3(nblk), dim3(256), st, e0, e1, a);
   return hipGetLastError();
 }
 
@@ -595,25 +594,25 @@ int32_t dense_pass_blocks(int32_t d, int32_t count, int mode) {
 }
 
 hipError_t launch_dense_pass(const PassArgs &a, int mode, int32_t d, int32_t nblk,
-                             hipStream_t st) {
+                             hipStream_t st, hipEvent_t e0, hipEvent_t e1) {
   const Shape s = pick_shape(d);
   if (mode == kPool) {
-    if (s.lpr == 16) return launch_pool<16, 1, 4>(a, nblk, st);
-    if (s.lpr == 32) return launch_pool<32, 1, 4>(a, nblk, st);
+    if (s.lpr == 16) return launch_pool<16, 1, 4>(a, nblk, st, e0, e1);
+    if (s.lpr == 32) return launch_pool<32, 1, 4>(a, nblk, st, e0, e1);
     switch (s.vpl) {
-      case 1: return launch_pool<64, 1, 4>(a, nblk, st);
-      case 2: return launch_pool<64, 2, 4>(a, nblk, st);
-      case 4: return launch_pool<64, 4, 2>(a, nblk, st);
-      default: return launch_pool<64, 8, 2>(a, nblk, st);
+      case 1: return launch_pool<64, 1, 4>(a, nblk, st, e0, e1);
+      case 2: return launch_pool<64, 2, 4>(a, nblk, st, e0, e1);
+      case 4: return launch_pool<64, 4, 2>(a, nblk, st, e0, e1);
+      default: return launch_pool<64, 8, 2>(a, nblk, st, e0, e1);
     }
   }
-  if (s.lpr == 16) return launch_grad<16, 1, 8, 8>(a, mode, nblk, st);
-  if (s.lpr == 32) return launch_grad<32, 1, 8, 8>(a, mode, nblk, st);
+  if (s.lpr == 16) return launch_grad<16, 1, 8, 8>(a, mode, nblk, st, e0, e1);
+  if (s.lpr == 32) return launch_grad<32, 1, 8, 8>(a, mode, nblk, st, e0, e1);
   switch (s.vpl) {
-    case 1: return launch_grad<64, 1, 8, 8>(a, mode, nblk, st);
-    case 2: return launch_grad<64, 2, 8, 8>(a, mode, nblk, st);
-    case 4: return launch_grad<64, 4, AA_NW_D1024, AA_RIF_D1024>(a, mode, nblk, st);
-    default: return launch_grad<64, 8, 8, 2>(a, mode, nblk, st);
+    case 1: return launch_grad<64, 1, 8, 8>(a, mode, nblk, st, e0, e1);
+    case 2: return launch_grad<64, 2, 8, 8>(a, mode, nblk, st, e0, e1);
+    case 4: return launch_grad<64, 4, AA_NW_D1024, AA_RIF_D1024>(a, mode, nblk, st, e0, e1);
+    default: return launch_grad<64, 8, 8, 2>(a, mode, nblk, st, e0, e1);
   }
 }
 

@@ -84,8 +84,10 @@ int32_t dense_d_pad(int32_t d);
 // Number of blocks the pass will use for `count` rows of dimension d.
 int32_t dense_pass_blocks(int32_t d, int32_t count, int mode);
 
+// started / stopped: optional events that receive the kernel's own time stamps (both or none)
 hipError_t launch_dense_pass(const PassArgs &a, int mode, int32_t d, int32_t nblk,
-                             hipStream_t stream);
+                             hipStream_t stream, hipEvent_t started = nullptr,
+                             hipEvent_t stopped = nullptr);
 hipError_t launch_dense_finalize(const FinalizeArgs &a, hipStream_t stream);
 
 }  // namespace aa

@@ -667,26 +667,27 @@ __global__ __launch_bounds__(kApplyThreads) void k_apply_general(const ApplyArgs
 }
 
 template <int GL, bool CSR>
-hipError_t launch_gl(const GenArgs &a, int mode, int nblk, hipStream_t st) {
+hipError_t launch_gl(const GenArgs &a, int mode, int nblk, hipStream_t st, hipEvent_t e0,
+                     hipEvent_t e1) {
   const dim3 grid(nblk), block(mode == kPool ? kPoolThreads : kGradThreads);
   switch (mode) {
     case kPool:
-      hipLaunchKernelGGL((k_rows_general<GL, kPool, CSR>), grid, block, 0, st, a);
+      launch_stamped((k_rows_general<GL, kPool, CSR>), grid, block, st, e0, e1, a);
       break;
     case kSvm:
-      hipLaunchKernelGGL((k_rows_general<GL, kSvm, CSR>), grid, block, 0, st, a);
+      launch_stamped((k_rows_general<GL, kSvm, CSR>), grid, block, st, e0, e1, a);
       break;
     case kAssist:
-      hipLaunchKernelGGL((k_rows_general<GL, kAssist, CSR>), grid, block, 0, st, a);
+      launch_stamped((k_rows_general<GL, kAssist, CSR>), grid, block, st, e0, e1, a);
       break;
     case kSvm | kAssist:
-      hipLaunchKernelGGL((k_rows_general<GL, kSvm | kAssist, CSR>), grid, block, 0, st, a);
+      launch_stamped((k_rows_general<GL, kSvm | kAssist, CSR>), grid, block, st, e0, e1, a);
       break;
     case kPool | kSvm | kAssist:
-      hipLaunchKernelGGL((k_rows_general<GL, kPool | kSvm | kAssist, CSR>), grid, block, 0, st, a);
+      launch_stamped((k_rows_general<GL, kPool | kSvm | kAssist, CSR>), grid, block, st, e0, e1, a);
       break;
     case kPool | kSvm | kHard:
-      hipLaunchKernelGGL((k_rows_general<GL, kPool | kSvm | kHard, CSR>), grid, block, 0, st, a);
+      launch_stamped((k_rows_general<GL, kPool | kSvm | kHard, CSR>), grid, block, st, e0, e1, a);
       break;
     default:
       return hipErrorInvalidValue;
@@ -710,9 +711,9 @@ int32_t general_pass_blocks(int32_t count, bool csr, int mode) {
 }
 
 hipError_t launch_general_pass(const GenArgs &a, int mode, bool csr, int32_t nblk,
-                               hipStream_t st) {
-  if (csr) return launch_gl<16, true>(a, mode, nblk, st);
-  return launch_gl<64, false>(a, mode, nblk, st);
+                               hipStream_t st, hipEvent_t e0, hipEvent_t e1) {
+  if (csr) return launch_gl<16, true>(a, mode, nblk, st, e0, e1);
+  return launch_gl<64, false>(a, mode, nblk, st, e0, e1);
 }
 
 hipError_t launch_zero_f32(float *p, size_t count, hipStream_t st) {

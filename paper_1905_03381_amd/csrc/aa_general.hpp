@@ -133,7 +133,8 @@ struct ApplyArgs {
 
 int32_t general_pass_blocks(int32_t count, bool csr, int mode);
 hipError_t launch_general_pass(const GenArgs &a, int mode, bool csr, int32_t nblk,
-                               hipStream_t stream);
+                               hipStream_t stream, hipEvent_t started = nullptr,
+                               hipEvent_t stopped = nullptr);
 hipError_t launch_zero_f32(float *p, size_t count, hipStream_t stream);
 hipError_t launch_general_apply(const ApplyArgs &a, hipStream_t stream);
 
