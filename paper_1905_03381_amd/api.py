@@ -172,7 +172,8 @@ def profile_hook(event_before, event_after):
 
 
 def profile_hooks(events_before, events_after):
-    """Lists of raw hipEvent_t handles: pair i receives the start and stop time stamps of the i-th row-pass launch from now on.
+    """Lists of raw hipEvent_t handles: pair i receives the start and stop time stamps of the i-th
+    row-pass launch from now on.
     Returns the two ctypes arrays, which the caller keeps alive until those launches are issued."""
     n = len(events_before)
     assert n == len(events_after)
