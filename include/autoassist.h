@@ -82,7 +82,7 @@ const char *aa_status_string(int32_t status);
 
 /* Bytes of scratch needed by any call with pool size <= P_max and feature
  * dimension <= d_max: a few MB for the dense layouts; for CSR rows (and dense
- * rows with d > 2048) about 8 d + 768 P_max bytes (gradient accumulators and
+ * rows with d > 2048) about 16 d + 768 P_max bytes (gradient accumulators and
  * the bins that sort sparse gradient terms by column, at most 2 GiB of those). */
 size_t aa_workspace_bytes(int32_t P_max, int32_t d_max);
 

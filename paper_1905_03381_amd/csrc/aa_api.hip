@@ -35,9 +35,16 @@ struct Ws {
 };
 
 // General kernels: a header (scalars, bin fill counts), the two dense accumulators, the
-// per-block sums of the first columns, then the record bins of the other columns.
+// model vectors as (w, phi) pairs, the per-block sums of the first columns, then the record
+// bins of the other columns.
+size_t general_pairs_offset(int32_t d) {  // (w, phi) pairs of the columns, indexed by column
+  return align_up((kGeneralHeader + 2 * (size_t)d) * sizeof(float), 256);
+}
+size_t general_part_offset(int32_t d) {
+  return general_pairs_offset(d) + align_up(2 * (size_t)d * sizeof(float), 256);
+}
 size_t general_bins_offset(int32_t d) {
-  return align_up((kGeneralHeader + 2 * (size_t)d + general_part_floats(d)) * sizeof(float), 256);
+  return general_part_offset(d) + align_up(general_part_floats(d) * sizeof(float), 256);
 }
 size_t general_acc_bytes(int32_t d, int32_t count_max) {
   return general_bins_offset(d) + general_record_capacity(count_max) * sizeof(TailRecord);
@@ -199,7 +206,13 @@ hipError_t run_pass(const PassSpec &s, const Ws &ws, int32_t *nblk_out, hipStrea
   const bool csr = s.F->layout == AA_CSR;
   float *acc = reinterpret_cast<float *>(ws.grad);
   if (s.mode & (kSvm | kAssist)) {
-    hipError_t e = launch_zero_f32(acc, kGeneralHeader + 2 * (size_t)s.F->d, st);
+    const size_t clear = kGeneralHeader + 2 * (size_t)s.F->d;
+    const bool both = (s.mode & kSvm) && (s.mode & kAssist);
+    const int32_t head = general_head_columns(s.F->d, 2);
+    float2 *pairs = reinterpret_cast<float2 *>(ws.grad + general_pairs_offset(s.F->d));
+    hipError_t e = (both && s.F->d > head)
+                       ? launch_prepare_general(acc, clear, s.w, s.phi, pairs, head, s.F->d, st)
+                       : launch_zero_f32(acc, clear, st);
     if (e != hipSuccess) return e;
   }
   GenArgs a{};
@@ -232,8 +245,11 @@ hipError_t run_pass(const PassSpec &s, const Ws &ws, int32_t *nblk_out, hipStrea
   a.acc_w = acc + kGeneralHeader;
   a.acc_used = reinterpret_cast<int32_t *>(acc) + 2;
   a.acc_p = acc + kGeneralHeader + s.F->d;
-  a.part = acc + kGeneralHeader + 2 * (size_t)s.F->d;
+  a.part = reinterpret_cast<float *>(ws.grad + general_part_offset(s.F->d));
   a.head = general_head_columns(s.F->d, nvec);
+  a.wp = (nvec == 2 && s.F->d > a.head)
+             ? reinterpret_cast<const float2 *>(ws.grad + general_pairs_offset(s.F->d))
+             : nullptr;
   a.bin_fill = reinterpret_cast<unsigned long long *>(acc + 16);
   a.bins = reinterpret_cast<TailRecord *>(ws.grad + general_bins_offset(s.F->d));
   a.plan = general_bin_plan(s.F->d, a.head, nvec, s.count_max);
@@ -305,7 +321,7 @@ hipError_t run_update(const PassSpec &s, const UpdateSpec &u, const Ws &ws, int3
   p.acc_w = acc + kGeneralHeader;
   p.acc_used = reinterpret_cast<const int32_t *>(acc) + 2;
   p.acc_p = acc + kGeneralHeader + s.F->d;
-  p.part = acc + kGeneralHeader + 2 * (size_t)s.F->d;
+  p.part = reinterpret_cast<const float *>(ws.grad + general_part_offset(s.F->d));
   p.nvec = ((s.mode & kSvm) ? 1 : 0) + ((s.mode & kAssist) ? 1 : 0);
   p.head = general_head_columns(s.F->d, p.nvec);
   p.bin_fill = reinterpret_cast<const unsigned long long *>(acc + 16);

@@ -231,11 +231,18 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
         for (int u = 0; u < kUnroll; ++u) {
           if (GRAD) {  // the first columns of the model are in LDS
             const bool near = c[u] < D;
-            if (NEED_PHI) {
-              const float pv = ASSIST ? (near ? s_mp[c[u]] : a.phi[c[u]]) : a.phi[c[u]];
-              dp = __fmaf_rn(pv, xv[u], dp);
+            if (SVM && ASSIST) {  // past the table: both values of the column with one gather
+              float2 far = make_float2(0.f, 0.f);
+              if (!near) far = a.wp[c[u]];
+              dw = __fmaf_rn(near ? s_mw[c[u]] : far.x, xv[u], dw);
+              dp = __fmaf_rn(near ? s_mp[c[u]] : far.y, xv[u], dp);
+            } else {
+              if (NEED_PHI) {
+                const float pv = ASSIST ? (near ? s_mp[c[u]] : a.phi[c[u]]) : a.phi[c[u]];
+                dp = __fmaf_rn(pv, xv[u], dp);
+              }
+              if (SVM) dw = __fmaf_rn(near ? s_mw[c[u]] : a.w[c[u]], xv[u], dw);
             }
-            if (SVM) dw = __fmaf_rn(near ? s_mw[c[u]] : a.w[c[u]], xv[u], dw);
           } else {
             if (NEED_PHI) dp = __fmaf_rn(a.phi[c[u]], xv[u], dp);
           }
@@ -428,6 +435,19 @@ __global__ __launch_bounds__(256) void k_zero_f32(float *p, size_t count) {
   float4 *p4 = reinterpret_cast<float4 *>(p);
   for (size_t i = tid; i < n4; i += stride) p4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
   if (tid < count - 4 * n4) p[4 * n4 + tid] = 0.f;
+}
+
+// What a pass that updates both vectors needs beforehand, in one launch: the accumulators and
+// the header cleared, and the two model vectors side by side for the columns past the LDS table.
+__global__ __launch_bounds__(256) void k_prepare_general(float *p, size_t count, const float *w,
+                                                         const float *phi, float2 *wp, int head,
+                                                         int d) {
+  const size_t n4 = count / 4, tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  float4 *p4 = reinterpret_cast<float4 *>(p);
+  for (size_t i = tid; i < n4; i += stride) p4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (tid < count - 4 * n4) p[4 * n4 + tid] = 0.f;
+  for (size_t c = head + tid; c < (size_t)d; c += stride) wp[c] = make_float2(w[c], phi[c]);
 }
 
 // Folds the gradient sums into the model.  Blocks [0, nh): 16 of the first `head` columns each,
@@ -714,6 +734,19 @@ hipError_t launch_general_pass(const GenArgs &a, int mode, bool csr, int32_t nbl
                                hipStream_t st, hipEvent_t e0, hipEvent_t e1) {
   if (csr) return launch_gl<16, true>(a, mode, nblk, st, e0, e1);
   return launch_gl<64, false>(a, mode, nblk, st, e0, e1);
+}
+
+hipError_t launch_prepare_general(float *p, size_t count, const float *w, const float *phi,
+                                  float2 *wp, int32_t head, int32_t d, hipStream_t st) {
+  if ((reinterpret_cast<uintptr_t>(p) & 15) != 0 || (reinterpret_cast<uintptr_t>(wp) & 7) != 0)
+    return hipErrorInvalidValue;
+  const size_t work = count / 4 > (size_t)d ? count / 4 : (size_t)d;
+  size_t blocks = (work + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(k_prepare_general, dim3((unsigned)blocks), dim3(256), 0, st, p, count, w, phi,
+                     wp, head, d);
+  return hipGetLastError();
 }
 
 hipError_t launch_zero_f32(float *p, size_t count, hipStream_t st) {

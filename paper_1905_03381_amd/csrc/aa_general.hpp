@@ -71,6 +71,10 @@ struct GenArgs {
   uint8_t *flags;
   float *loss_out;
   const float *loss_in;
+  // (w[c], phi[c]) side by side for the columns past `head`, indexed by column: one gather
+  // brings both values of a column that is not in LDS (written before the pass; NULL unless
+  // the pass updates both vectors)
+  const float2 *wp;
   // atomic accumulators (zeroed before the pass); *acc_used (zeroed too) is set by whoever adds
   float *acc_w;      // [d]
   float *acc_p;      // [d]
@@ -136,6 +140,9 @@ hipError_t launch_general_pass(const GenArgs &a, int mode, bool csr, int32_t nbl
                                hipStream_t stream, hipEvent_t started = nullptr,
                                hipEvent_t stopped = nullptr);
 hipError_t launch_zero_f32(float *p, size_t count, hipStream_t stream);
+// Zeroes p[0, count) and writes wp[c] = (w[c], phi[c]) for head <= c < d (one launch).
+hipError_t launch_prepare_general(float *p, size_t count, const float *w, const float *phi,
+                                  float2 *wp, int32_t head, int32_t d, hipStream_t stream);
 hipError_t launch_general_apply(const ApplyArgs &a, hipStream_t stream);
 
 }  // namespace aa
