@@ -136,22 +136,29 @@ int32_t aa_ref_shrink_threshold(const float *crit, int32_t P, float T, uint8_t *
   return 0;
 }
 
+/* Keep decision of the sequential generator (Algorithm 1) for one candidate, in double.
+ * The unit interval of the draw c is split at gamma: the mass below gamma is the smoothing
+ * term and keeps any candidate; the mass above it, stretched back onto [0,1), is a uniform
+ * independent of that event and is compared with the Assistant's score g.  Together:
+ * P(keep) = gamma + (1 - gamma) g.  gamma == 1 always takes the first case, so the
+ * stretch never divides by zero. */
+static int sequential_keep(double c, double gamma, double g) {
+  if (c < gamma) return 1;
+  const double stretched = (c - gamma) / (1.0 - gamma);
+  return stretched < g;
+}
+
 int32_t aa_ref_sample_batch(const float *prob, int32_t P, float gamma, uint64_t seed,
                             uint64_t step, int32_t batch_size, int32_t *B, int32_t *B_size,
                             int32_t *consumed) {
   if (P < 0 || batch_size < 0) return -2;
   if (!B_size || !consumed) return -1;
   if (P > 0 && batch_size > 0 && (!prob || !B)) return -1;
+  /* candidates are visited in pool order until the batch is full or the pool runs out */
   int32_t size = 0, j = 0;
-  while (size < batch_size && j < P) {
-    double c = (double)aa_ref_uniform(seed, step, (uint32_t)j);
-    if (c < (double)gamma) {
-      B[size++] = j;
-    } else {
-      double c_hat = (c - (double)gamma) / (1.0 - (double)gamma);
-      if (c_hat < (double)prob[j]) B[size++] = j;
-    }
-    ++j;
+  for (; j < P && size < batch_size; ++j) {
+    const double c = (double)aa_ref_uniform(seed, step, (uint32_t)j);
+    if (sequential_keep(c, (double)gamma, (double)prob[j])) B[size++] = j;
   }
   *B_size = size;
   *consumed = j;

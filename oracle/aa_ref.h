@@ -70,10 +70,12 @@ int32_t aa_ref_shrink(const float *prob, int32_t P, float gamma, uint64_t seed, 
 int32_t aa_ref_shrink_threshold(const float *crit, int32_t P, float T, uint8_t *keep,
                                 int32_t *kept_pos, int32_t *kept_count);
 
-/* Algorithm 1 taken literally over a candidate sequence of length P: walk the
- * candidates in order, draw c, keep if c < gamma, else keep if
- * (c-gamma)/(1-gamma) < g; stop once batch_size are kept.  Double arithmetic.
- * B receives pool positions; *consumed the number of candidates looked at. */
+/* The sequential batch generator of Algorithm 1 over a candidate sequence of
+ * length P: candidates are visited in order and the batch is full after
+ * batch_size keeps.  A candidate is kept when its draw c falls into the smoothing
+ * mass [0, gamma), or when the rest of the draw, stretched from [gamma, 1) onto
+ * [0, 1), falls below the Assistant's score g.  Double arithmetic.  B receives
+ * pool positions; *consumed the number of candidates looked at. */
 int32_t aa_ref_sample_batch(const float *prob, int32_t P, float gamma, uint64_t seed,
                             uint64_t step, int32_t batch_size, int32_t *B, int32_t *B_size,
                             int32_t *consumed);

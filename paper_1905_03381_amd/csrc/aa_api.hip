@@ -23,8 +23,8 @@ struct Ws {
   char *grad;         // gradient partials / accumulators
   uint8_t *flags;     // [P]
   float *loss_pool;   // [P]
-  int32_t *tile_off;  // [P/2048 + 2]
-  int32_t *bucket_tiles;  // [(P/2048 + 2) * kMaxBuckets]
+  int32_t *tile_off;  // [ceil(P/2048) + 2]
+  int32_t *bucket_tiles;  // [bucket_table_ints(P)]
   float *prob;        // [P]   per-step outputs of the epoch driver
   int32_t *kept_pos;  // [P]
   int32_t *kept_ids;  // [P]
@@ -64,9 +64,10 @@ Ws carve(void *ws, size_t grad_bytes, int32_t P, bool epoch_outputs = false) {
   w.loss_pool = reinterpret_cast<float *>(w.base + off);
   off += align_up(sizeof(float) * (size_t)(P > 0 ? P : 0), 256);
   w.tile_off = reinterpret_cast<int32_t *>(w.base + off);
-  off += align_up(sizeof(int32_t) * ((size_t)(P > 0 ? P : 0) / kCompactTile + 2), 256);
+  const size_t tiles = ((size_t)(P > 0 ? P : 0) + kCompactTile - 1) / kCompactTile;
+  off += align_up(sizeof(int32_t) * (tiles + 2), 256);
   w.bucket_tiles = reinterpret_cast<int32_t *>(w.base + off);
-  off += align_up(sizeof(int32_t) * ((size_t)(P > 0 ? P : 0) / kCompactTile + 2) * kMaxBuckets, 256);
+  off += align_up(sizeof(int32_t) * bucket_table_ints(P), 256);
   const size_t per = align_up(sizeof(float) * (size_t)(P > 0 ? P : 0), 256);
   w.prob = reinterpret_cast<float *>(w.base + off);
   w.kept_pos = reinterpret_cast<int32_t *>(w.base + off + per);
@@ -885,6 +886,9 @@ int32_t aa_bucket_batches(const int32_t *len_s, const int32_t *len_t, const int3
   if (m_max > 0 && (!len_s || !len_t || !order || !batch_of)) return AA_ERR_NULL;
   Ws ws = carve(ws_ptr, 0, m_max);
   if (int32_t rc = check_ws(ws_ptr, ws_bytes, ws.total)) return rc;
+  // what the three kernels index: one row of n_buckets counts per tile, then two tail rows
+  const size_t tiles = ((size_t)m_max + kBucketTile - 1) / kBucketTile;
+  if ((tiles + 2) * (size_t)n_buckets > bucket_table_ints(m_max)) return AA_ERR_WORKSPACE;
   BucketArgs a{};
   a.len_s = len_s;
   a.len_t = len_t;

@@ -109,8 +109,6 @@ __device__ __forceinline__ int bucket_of(int ls, int lt, int width, int nb) {
   return min(b, nb - 1);
 }
 
-constexpr int kBucketTile = 2048;
-
 __global__ __launch_bounds__(256) void k_bucket_counts(const BucketArgs a) {
   __shared__ int hist[kMaxBuckets];
   const int m = min(max(*a.m_dev, 0), a.m_max);

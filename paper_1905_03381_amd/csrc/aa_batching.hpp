@@ -8,6 +8,15 @@ namespace aa {
 
 constexpr int kMaxBuckets = 32;
 constexpr int kMedianMax = 16384;  // losses sorted in LDS by one block
+constexpr int kBucketTile = 2048;  // kept pairs ranked by one block of the bucket partition
+
+// int32 entries of the bucket table for up to m_max pairs: one row of kMaxBuckets counts per
+// tile, then the bucket starts and the batch bases (the kernels index rows with the call's
+// n_buckets <= kMaxBuckets, so this covers every bucket count).
+inline size_t bucket_table_ints(int64_t m_max) {
+  const size_t tiles = (size_t)((m_max > 0 ? m_max : 0) + kBucketTile - 1) / kBucketTile;
+  return (tiles + 2) * kMaxBuckets;
+}
 
 struct ThresholdArgs {
   const float *loss;

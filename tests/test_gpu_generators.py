@@ -73,6 +73,53 @@ def test_bucket_batches_exact(ref, m):
     assert np.all(host(order)[m:] == -1)
 
 
+@pytest.mark.parametrize("m_max", [1000, 100_003])
+def test_bucket_batches_32_buckets_in_the_smallest_accepted_workspace(ref, m_max):
+    """The largest bucket count with a pair count that is no multiple of the tile: the call's
+    own size check must cover everything its kernels index.  The workspace handed over is the
+    smallest one the call accepts (found by bisection on the status code), followed in the same
+    allocation by a guard region that has to stay untouched."""
+    import ctypes as C
+    r = rng(m_max)
+    m = m_max
+    ls = np.clip(r.poisson(60, m), 1, 300).astype(np.int32)
+    lt = np.clip(r.poisson(60, m), 1, 300).astype(np.int32)
+    order_ref, start_ref, batch_ref, nb_ref = ref.bucket_batches(ls, lt, 8, 32, 4096)
+    order = torch.full((m,), -1, dtype=torch.int32, device="cuda")
+    batch_of = torch.full((m,), -1, dtype=torch.int32, device="cuda")
+    start = torch.full((33,), -1, dtype=torch.int32, device="cuda")
+    nb = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    ls_d, lt_d, m_d = dev(ls), dev(lt), scalar_dev(m, torch.int32)
+    hi = api.workspace_bytes(m_max, 128)
+    guard = 1 << 16
+    buf = torch.full((hi + guard + 256,), 0xA5, dtype=torch.uint8, device="cuda")
+    base = buf.data_ptr() + (-buf.data_ptr()) % 256
+    L, st = api.lib(), torch.cuda.current_stream().cuda_stream
+
+    def call(nbytes):
+        return L.aa_bucket_batches(ls_d.data_ptr(), lt_d.data_ptr(), m_d.data_ptr(), m_max, 8, 32,
+                                   4096, order.data_ptr(), start.data_ptr(), batch_of.data_ptr(),
+                                   nb.data_ptr(), base, nbytes, st)
+
+    lo = 0                               # refused at lo, accepted at hi
+    assert call(lo) == -4 and call(hi) == 0
+    while hi - lo > 1:
+        mid = (lo + hi) // 2
+        if call(mid) == 0:
+            hi = mid
+        else:
+            lo = mid
+    torch.cuda.synchronize()
+    buf.fill_(0xA5)
+    assert call(hi) == 0
+    assert int(host(nb)[0]) == nb_ref
+    assert np.array_equal(host(start), start_ref)
+    assert np.array_equal(host(order), order_ref) and np.array_equal(host(batch_of), batch_ref)
+    off = base - buf.data_ptr()
+    tail = host(buf)[off + hi: off + hi + guard]
+    assert np.all(tail == 0xA5), "the call wrote past the workspace size it accepted"
+
+
 def test_image_batch_generator_full_shape(ref):
     P, d, row_bytes, B = 65536, 512, 3 * 224 * 224, 256
     feats = synth.assistant_features(P, d)

@@ -564,6 +564,69 @@ def test_threshold_update_is_numpy_median_with_momentum(ref):
     assert T2 == 1.25 and init2
 
 
+def test_threshold_momentum_rule_by_its_closed_form(ref):
+    """The momentum half of the running threshold, pinned by what the recursion
+    T <- momentum T + (1 - momentum) med implies rather than by repeating it:
+      * momentum = 0 returns the batch median itself, momentum = 1 never moves (both exact);
+      * a threshold that already equals the median of every batch stays there;
+      * for batches that all have the median `med`, T_t = med + momentum^t (T_0 - med): the
+        distance to the median shrinks by the factor `momentum` (0.9, not 0.1) per batch.
+    Swapping the two weights, dropping one of them or updating towards anything but the
+    median breaks at least one of these."""
+    r = rng(23)
+
+    def batch_with_median(med, m):
+        """m losses (odd m) whose median is exactly med, in random order."""
+        half = m // 2
+        lo = med - r.gamma(2.0, 0.5, half) - 1e-3
+        hi = med + r.gamma(2.0, 0.5, half) + 1e-3
+        x = np.concatenate([lo, [med], hi]).astype(np.float32)
+        r.shuffle(x)
+        assert np.float32(np.median(x.astype(np.float64))) == np.float32(med)
+        return x
+
+    # momentum 0 and 1
+    loss = r.gamma(2.0, 0.5, 301).astype(np.float32)
+    med = np.float32(np.median(loss.astype(np.float64)))
+    T, init = ref.threshold_update(loss, 0.0, 5.0, True)
+    assert init and np.float32(T) == med
+    T, init = ref.threshold_update(loss, 1.0, 5.0, True)
+    assert init and np.float32(T) == np.float32(5.0)
+    # the first batch sets T whatever the momentum
+    T, init = ref.threshold_update(loss, 1.0, 5.0, False)
+    assert init and np.float32(T) == med
+
+    # fixed point: T equal to the median of each batch does not move (one rounding per term:
+    # 0.9 T + 0.1 T may differ from T by an ulp or two, never by more, and never drifts)
+    med = np.float32(1.375)
+    T = float(med)
+    for t in range(200):
+        T, _ = ref.threshold_update(batch_with_median(float(med), 101), 0.9, T, True)
+        assert abs(T - float(med)) <= 4 * np.spacing(med)
+
+    # geometric approach to a constant median from above and from below, several momenta
+    for momentum in (0.9, 0.5, 0.25):
+        for T0 in (4.0, 0.125):
+            T = T0
+            mom32 = float(np.float32(momentum))
+            one_minus32 = float(np.float32(1.0) - np.float32(momentum))
+            for t in range(1, 60):
+                T, init = ref.threshold_update(batch_with_median(float(med), 51), momentum, T, True)
+                # closed form with the fp32-rounded weights (their sum is 1 only up to an ulp)
+                want = float(med) + (T0 - float(med)) * mom32 ** t
+                # each step rounds three times at magnitude <= max(T0, med): <= 1.5 ulp; the
+                # errors are damped by `momentum` per step, so they sum to < 1.5 ulp / (1 - momentum)
+                bound = 2.0 * float(np.spacing(np.float32(max(T0, float(med))))) / (1.0 - mom32) \
+                    + abs(mom32 + one_minus32 - 1.0) * t * max(T0, float(med))
+                assert abs(T - want) <= bound, (momentum, T0, t, T, want, bound)
+            # and the direction is towards the median: with the weights swapped the first step
+            # alone would land at med + (1 - momentum)(T0 - med)
+            T1, _ = ref.threshold_update(batch_with_median(float(med), 51), momentum, T0, True)
+            if momentum != 0.5:
+                swapped = float(med) + (1.0 - mom32) * (T0 - float(med))
+                assert abs(T1 - swapped) > 0.05 * abs(T0 - float(med))
+
+
 # ---------------------------------------------------------------------------
 # Hard-threshold shrinking (SK) and the iteration of Theorem 1
 
