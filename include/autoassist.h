@@ -230,6 +230,28 @@ int32_t aa_fused_step(const aa_features *F, const float *y, const int32_t *idx, 
                       int32_t *kept_ids, float *loss, int32_t *kept_count, void *ws,
                       size_t ws_bytes, void *stream);
 
+/* ---- aa_fused_step for callers that cannot allocate device memory or carry a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, outputs and errors as aa_fused_step minus
+ * `ws` / `ws_bytes`: the scratch (block partials of the gradient sums, per-block
+ * kept counts, keep flags and per-position losses when the caller passes none)
+ * lives in a static device array of AA_STATIC_SCRATCH_BYTES inside the library,
+ * one copy per GPU, held until the process ends.  The call allocates nothing and
+ * frees nothing.  A step that needs more scratch than the array holds
+ * (aa_workspace_bytes-sized needs of large CSR problems, say) is refused with
+ * AA_ERR_WORKSPACE and launches nothing; the register-resident dense layouts fit
+ * for any d <= 2048 and P <= 131072.  The first call on a device looks up that
+ * device's copy of the array (make it outside stream capture).  All calls on one
+ * GPU share the array: two calls that may overlap in time on one GPU (different
+ * streams) race; calls on one stream are ordered and safe.  Nothing in the array
+ * has to survive between calls. */
+#define AA_STATIC_SCRATCH_BYTES (8u << 20)
+size_t aa_static_scratch_bytes(void);
+int32_t aa_fused_step_static(const aa_features *F, const float *y, const int32_t *idx, int32_t P,
+                             float *w, float *phi, float *bias, const aa_step_config *cfg,
+                             float *logit, float *prob, uint8_t *keep, int32_t *kept_pos,
+                             int32_t *kept_ids, float *loss, int32_t *kept_count, void *stream);
+
 /* ---- Hard-threshold shrinking (SK of Section 3.4; the update of eq.
  * "shrinking_grad" with the objective value as the criterion), one step on the
  * pool idx[0..P-1] with every feature row read once: crit_j = max(0, 1 - y w.x)

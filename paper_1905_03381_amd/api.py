@@ -24,6 +24,7 @@ SYMBOLS = [
     "aa_gather_csr", "aa_svm_sgd_step", "aa_assistant_update", "aa_boss_assistant_step",
     "aa_fused_step", "aa_sk_step", "aa_train_epoch", "aa_threshold_update", "aa_bucket_batches",
     "aa_pipeline_workspace_bytes", "aa_train_epoch_stale", "aa_sk_epoch",
+    "aa_static_scratch_bytes", "aa_fused_step_static",
 ]
 
 
@@ -74,6 +75,8 @@ def lib():
         "aa_assistant_update": (i32, [FP, vp, vp, i32, vp, vp, vp, vp, f32, f32, vp, sz, vp]),
         "aa_boss_assistant_step": (i32, [FP, vp, vp, vp, i32, vp, vp, vp, CP, vp, vp, sz, vp]),
         "aa_fused_step": (i32, [FP, vp, vp, i32, vp, vp, vp, CP, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
+        "aa_static_scratch_bytes": (sz, []),
+        "aa_fused_step_static": (i32, [FP, vp, vp, i32, vp, vp, vp, CP, vp, vp, vp, vp, vp, vp, vp, vp]),
         "aa_sk_step": (i32, [FP, vp, vp, i32, vp, vp, f32, f32, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
         "aa_train_epoch": (i32, [FP, vp, vp, i64, i32, vp, vp, vp, CP, vp, vp, vp, vp, vp, sz, vp]),
         "aa_sk_epoch": (i32, [FP, vp, vp, i64, i32, vp, vp, f32, f32, vp, vp, vp, vp, vp, sz, vp]),
@@ -242,6 +245,18 @@ def fused_step(F, y, idx, P, w, phi, bias, cfg, logit, prob, keep, kept_pos, kep
                                C.byref(cfg), _ptr(logit), _ptr(prob), _ptr(keep), _ptr(kept_pos),
                                _ptr(kept_ids), _ptr(loss), _ptr(kept_count), ws.ptr, ws.bytes,
                                _stream()), "aa_fused_step")
+
+
+def static_scratch_bytes():
+    return int(lib().aa_static_scratch_bytes())
+
+
+def fused_step_static(F, y, idx, P, w, phi, bias, cfg, logit, prob, keep, kept_pos, kept_ids, loss,
+                      kept_count):
+    _check(lib().aa_fused_step_static(F.ref(), _ptr(y), _ptr(idx), P, _ptr(w), _ptr(phi),
+                                      _ptr(bias), C.byref(cfg), _ptr(logit), _ptr(prob), _ptr(keep),
+                                      _ptr(kept_pos), _ptr(kept_ids), _ptr(loss), _ptr(kept_count),
+                                      _stream()), "aa_fused_step_static")
 
 
 def sk_step(F, y, idx, P, w, T, lam, lr, loss_pool, keep, kept_pos, kept_ids, loss, kept_count, ws):

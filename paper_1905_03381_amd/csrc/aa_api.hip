@@ -9,7 +9,18 @@
 #include "aa_batching.hpp"
 #include "aa_select.hpp"
 
+#include <mutex>
+
 using namespace aa;
+
+// Scratch of aa_fused_step_static: one copy per GPU the library runs on, held until the
+// process ends.  In host code the name below is only a stand-in for the device array; its
+// device address is looked up once per device (static_scratch()) and only that address is
+// handed to kernels.  The compiler gives the device-side symbol external linkage because
+// host code refers to it; that is what lets the runtime find it by name (an attribute that
+// pins the symbol, such as `used`, keeps it local and the lookup then aborts the process).
+constexpr size_t kStaticScratchBytes = AA_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -505,6 +516,25 @@ __global__ void k_copy_model(const float *phi, const float *bias, int32_t d, flo
 
 constexpr int kMaxStaleness = 15;
 
+// Device address of this GPU's copy of `scratch`, resolved on the first call per device.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+int32_t static_scratch(void **out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return AA_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return AA_ERR_HIP;
+    if ((reinterpret_cast<uintptr_t>(p) & 255) != 0) return AA_ERR_ALIGN;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return AA_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -822,6 +852,31 @@ int32_t aa_fused_step(const aa_features *F, const float *y, const int32_t *idx, 
   return fused_step_impl(F, y, idx, P, w, phi, bias, cfg, cfg->step, logit, prob, keep, kept_pos,
                          kept_ids, loss, kept_count, nullptr, nullptr, nullptr, ws, ws_bytes,
                          as_stream(stream));
+}
+
+size_t aa_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int32_t aa_fused_step_static(const aa_features *F, const float *y, const int32_t *idx, int32_t P,
+                             float *w, float *phi, float *bias, const aa_step_config *cfg,
+                             float *logit, float *prob, uint8_t *keep, int32_t *kept_pos,
+                             int32_t *kept_ids, float *loss, int32_t *kept_count, void *stream) {
+  if (P < 0) return AA_ERR_SHAPE;
+  if (!kept_count) return AA_ERR_NULL;
+  if (P == 0) {
+    CompactArgs c{};
+    c.kept_count = kept_count;
+    return hip_status(launch_compact(c, nullptr, as_stream(stream)));
+  }
+  if (int32_t rc = check_features(F)) return rc;
+  if (!y || !w || !phi || !cfg || !cfg->T) return AA_ERR_NULL;
+  void *ws = nullptr;
+  if (int32_t rc = static_scratch(&ws)) return rc;
+  // Every word of the scratch this step reads it has written before in the same call (block
+  // partials, per-block counts, flags, per-position losses), so nothing needs clearing; a
+  // step that needs more than the array holds is refused with AA_ERR_WORKSPACE.
+  return fused_step_impl(F, y, idx, P, w, phi, bias, cfg, cfg->step, logit, prob, keep, kept_pos,
+                         kept_ids, loss, kept_count, nullptr, nullptr, nullptr, ws,
+                         kStaticScratchBytes, as_stream(stream));
 }
 
 int32_t aa_sk_step(const aa_features *F, const float *y, const int32_t *idx, int32_t P, float *w,
