@@ -136,6 +136,11 @@ struct Hook {
   }
 };
 
+#ifdef AA_PHASE_TRACE
+// Measurement builds only: where the next whole-step passes write their per-wave phase stamps.
+unsigned long long *g_phase_trace = nullptr;
+#endif
+
 // Common description of one row pass, lowered to either kernel family.
 struct PassSpec {
   const aa_features *F;
@@ -207,6 +212,9 @@ hipError_t run_pass(const PassSpec &s, const Ws &ws, int32_t *nblk_out, hipStrea
     a.t_upd = s.t_upd;
     a.t_snap = ws.ctl + kCtlUpdateSnapshot;
     a.prev = s.prev;
+#ifdef AA_PHASE_TRACE
+    a.trace = g_phase_trace;
+#endif
     const int32_t nblk = dense_pass_blocks(s.F->d, s.count_max, s.mode);
     if (a.prev.flags && (a.prev.P > dense_carry_capacity(nblk) ||
                          (reinterpret_cast<uintptr_t>(a.prev.flags) & 15) != 0))
@@ -853,6 +861,16 @@ int32_t aa_fused_step(const aa_features *F, const float *y, const int32_t *idx, 
                          kept_ids, loss, kept_count, nullptr, nullptr, nullptr, ws, ws_bytes,
                          as_stream(stream));
 }
+
+#ifdef AA_PHASE_TRACE
+// Measurement builds only (not part of the product ABI): the whole-step dense passes launched
+// from now on write kTraceStamps 64-bit time stamps (10 ns ticks) per wave into `buf`
+// (device memory, blocks x waves x kTraceStamps entries); NULL stops it.
+int32_t aa_phase_trace_buffer(void *buf) {
+  g_phase_trace = static_cast<unsigned long long *>(buf);
+  return AA_OK;
+}
+#endif
 
 size_t aa_static_scratch_bytes(void) { return kStaticScratchBytes; }
 

@@ -43,7 +43,12 @@ struct PassArgs {
   // while its own rows are in flight.  Needs ceil(prev.P / 64) <= blocks of this launch and
   // 16-byte aligned prev.flags; prev.tile_off is not used.
   CompactArgs prev;
+  // Measurement builds only (AA_PHASE_TRACE): per-wave phase time stamps of k_step_pass,
+  // trace[(block * waves + wave) * kTraceStamps + k] in 10 ns ticks; NULL = none.
+  unsigned long long *trace;
 };
+
+constexpr int kTraceStamps = 8;
 
 // Largest pool whose compaction a pass of `nblk` blocks can carry.
 inline int64_t dense_carry_capacity(int32_t nblk) { return (int64_t)nblk * kWave; }
