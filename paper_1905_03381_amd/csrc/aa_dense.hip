@@ -20,7 +20,7 @@
 #define AA_RIF_D1024 1   // rows in flight per wave there
 #endif
 #ifndef AA_STEP_NW_D1024
-#define AA_STEP_NW_D1024 16  // whole-step pass at d = 1024: waves per block
+#define AA_STEP_NW_D1024 8   // whole-step pass at d = 1024: waves per block (one block per CU)
 #endif
 #ifndef AA_STEP_RIF_D1024
 #define AA_STEP_RIF_D1024 2  // and rows requested at once per wave
@@ -831,7 +831,7 @@ bool step_pass_ok(const Shape &s, int32_t d, int mode) {
 }
 
 // Waves per block: passes with gradient sums use one fat block per CU (few block
-// partials); the 1024-wide layout runs 16 waves of 128 registers, the others 8.
+// partials); the general 1024-wide pass runs 16 waves of 128 registers, everything else 8.
 int waves_per_block(const Shape &s, int32_t d, int mode) {
   const bool grad = (mode & (kSvm | kAssist)) != 0;
   if (!grad) return 4;
