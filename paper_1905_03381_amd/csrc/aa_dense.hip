@@ -713,26 +713,41 @@ __global__ __launch_bounds__(256) void k_finalize(const FinalizeArgs a) {
   const int col4 = ((int)blockIdx.x % per_vec) * kFinCols4 + c4;
   const int k0 = col4 * 4;
 
-  int cnt_part = 0;
-  if (!a.m_dev)
-    for (int i = tid; i < a.nblk; i += blockDim.x) cnt_part += a.blk_cnt[i];
-  const int m_given = a.m_dev ? *a.m_dev : 0;
-  const int t_old = a.t_upd ? *a.t_snap : 0;
-  float gb_part = 0.f;
-  if (bias_block)
-    for (int i = tid; i < a.nblk; i += blockDim.x) gb_part += a.blk_gb[i];
-  float old[4] = {0.f, 0.f, 0.f, 0.f};
-  if (pg == 0) {
+  // Every first load is requested before any is used and none sits under a condition (absent
+  // inputs read a stand-in address, indices are clamped, what was read for nothing is
+  // dropped): the block pays one memory round trip for counts, scalars, model slice and
+  // its first eight partials per thread.
+  const int nb = a.nblk;
+  const int32_t *ints = a.blk_cnt;                       // always present: the stand-in address
+  const int ci = min(tid, nb - 1);
+  int cnt_part = a.blk_cnt[ci];
+  float gb_part = a.blk_gb[ci];
+  const int m_given = *(a.m_dev ? a.m_dev : ints);
+  int t_old = *(a.t_upd ? a.t_snap : ints);
+  float b_new = *(bias_block ? a.bias : a.blk_gb);       // the bias before this update
+  float old[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      if (k0 + i < a.d) old[i] = model[k0 + i];
-  }
+  for (int i = 0; i < 4; ++i) old[i] = model[min(k0 + i, a.d - 1)];
   const f4 zero = {0.f, 0.f, 0.f, 0.f};
   f4 acc = zero;
   const f4 *p = reinterpret_cast<const f4 *>(a.partial) + (size_t)vec * row4 + col4;
   const size_t stride = (size_t)a.nvec * row4;
-#pragma unroll 8
-  for (int blk = pg; blk < a.nblk; blk += kFinGroups) acc += p[(size_t)blk * stride];
+  for (int base = pg; base < nb; base += 8 * kFinGroups) {
+    f4 v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = p[(size_t)min(base + j * kFinGroups, nb - 1) * stride];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (base + j * kFinGroups < nb) acc += v[j];       // block order within the group
+  }
+  if (a.m_dev || tid >= nb) cnt_part = 0;
+  if (!bias_block || tid >= nb) gb_part = 0.f;
+  if (!a.t_upd) t_old = 0;
+  if (pg != 0) old[0] = old[1] = old[2] = old[3] = 0.f;
+  for (int i = tid + blockDim.x; i < nb; i += blockDim.x) {  // more than 256 partials
+    if (!a.m_dev) cnt_part += a.blk_cnt[i];
+    if (bias_block) gb_part += a.blk_gb[i];
+  }
 
   // fold the groups of this wave (lanes that share a column), then the four waves
 #pragma unroll
@@ -758,9 +773,7 @@ __global__ __launch_bounds__(256) void k_finalize(const FinalizeArgs a) {
   if (a.t_upd && m > 0) lr = a.lr / sqrtf((float)t_new);
 
   float now[4] = {old[0], old[1], old[2], old[3]};
-  float b_new = 0.f;
   const bool bias_thread = bias_block && tid == 0;
-  if (bias_thread) b_new = *a.bias;
   if (m > 0) {
     const float inv_m = 1.f / (float)m;
     if (pg == 0) {
