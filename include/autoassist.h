@@ -24,6 +24,10 @@
  *    with aa_workspace_init().  A workspace must not be used by two calls that
  *    may overlap in time (different streams).  Keep flags are bytes 0 or 1.
  *  - Row ids are int32, CSR row pointers int64, column ids int32, values fp32.
+ *    PRECONDITION: every row id handed over (idx, perm, rows, kept_pos) lies in
+ *    [0, n) of the data it indexes and every CSR column id in [0, d).  Ids are
+ *    not checked on the device: an id outside the range reads (or, for column
+ *    ids of a gradient pass, writes) outside the caller's buffers.
  *  - P == 0 and *m == 0 are valid and leave the model state untouched.
  */
 #ifndef AUTOASSIST_H
@@ -201,7 +205,8 @@ int32_t aa_boss_assistant_step(const aa_features *F, const float *y, const int32
  * (m = min(*m_dev, m_max) <= 16384; mean of the two middle values for even m);
  * the first call (*initialised == 0) sets *T = med and *initialised = 1, later
  * calls *T = momentum * *T + (1 - momentum) * med, every operation rounded to
- * fp32.  m == 0 changes nothing.  T and initialised are device scalars. */
+ * fp32.  m == 0 changes nothing.  A batch that holds a NaN loss sets *T to NaN
+ * (and *initialised to 1).  T and initialised are device scalars. */
 int32_t aa_threshold_update(const float *loss, const int32_t *m_dev, int32_t m_max, float momentum,
                             float *T, int32_t *initialised, void *stream);
 

@@ -473,6 +473,13 @@ int32_t aa_ref_threshold_update(const float *loss, int32_t m, float momentum, fl
   if (!T || !initialised) return -1;
   if (m == 0) return 0;
   if (!loss) return -1;
+  for (int32_t i = 0; i < m; ++i) {
+    if (loss[i] != loss[i]) { /* a NaN loss has no rank: the threshold becomes NaN, visibly */
+      *T = NAN;
+      *initialised = 1;
+      return 0;
+    }
+  }
   float *sorted = (float *)malloc((size_t)m * sizeof(float));
   if (!sorted) return -2;
   memcpy(sorted, loss, (size_t)m * sizeof(float));

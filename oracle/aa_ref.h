@@ -158,7 +158,8 @@ int32_t aa_ref_sk_sgd(const aa_ref_features *F, const float *y, double *w, doubl
  * values for even m, in float); the first call sets *T = med, later calls
  * *T = momentum * *T + (1 - momentum) * med, each product and the sum rounded
  * to float.  m == 0 changes nothing.  This estimator is this build's reading
- * (the paper gives no estimator); it is pinned against numpy's median. */
+ * (the paper gives no estimator); it is pinned against numpy's median.  A batch that holds a NaN loss sets *T to NaN
+ * (and *initialised to 1). */
 int32_t aa_ref_threshold_update(const float *loss, int32_t m, float momentum, float *T,
                                 int32_t *initialised);
 

@@ -29,6 +29,19 @@ __global__ __launch_bounds__(1024) void k_threshold_update(const ThresholdArgs a
   const int init_old = *a.initialised;
   const int m = min(max(*a.m_dev, 0), a.m_max);
   if (m == 0) return;
+  // a NaN loss has no rank: the threshold becomes NaN, visibly (the whole block agrees)
+  int has_nan = 0;
+  for (int i = threadIdx.x; i < m; i += blockDim.x) {
+    const float v = i == i0 ? x0 : a.loss[i];
+    has_nan |= v != v;
+  }
+  if (__syncthreads_or(has_nan)) {
+    if (threadIdx.x == 0) {
+      *a.T = __builtin_nanf("");
+      *a.initialised = 1;
+    }
+    return;
+  }
   float lo_mid, hi_mid;  // sorted[(m-1)/2] and sorted[m/2]
   if (m <= kRankSelectMax) {
     const int i = i0;

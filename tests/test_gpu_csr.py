@@ -203,6 +203,17 @@ def test_gather_csr(ref, ws, sparse):
     fits = int(np.searchsorted(want_ptr, small, side="right") - 1)
     assert np.array_equal(host(out_col2)[:want_ptr[fits]], want_col[:want_ptr[fits]])
     assert np.all(host(out_col2)[want_ptr[fits]:] == -1)
+    # one entry short: only the last kept row stays out, nothing is written past the capacity
+    # (the buffers hold one guard entry behind it)
+    out_col3 = torch.full((cap,), -1, dtype=torch.int32, device="cuda")
+    out_val3 = torch.full((cap,), -1.0, device="cuda")
+    api.gather_csr(F, dev(idx), pos_d, scalar_dev(2100, torch.int32), P, out_ptr, out_col3, out_val3,
+                   cap - 1, ws)
+    assert np.array_equal(host(out_ptr)[:2101], want_ptr)
+    last = want_ptr[2099]
+    assert np.array_equal(host(out_col3)[:last], want_col[:last])
+    assert np.array_equal(host(out_val3)[:last], want_val[:last])
+    assert np.all(host(out_col3)[last:] == -1) and np.all(host(out_val3)[last:] == -1.0)
 
 
 def test_sparse_config_full_size_first_pools(ref):

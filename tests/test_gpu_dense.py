@@ -64,8 +64,8 @@ def test_assistant_score(ref, n, d, ld, P, use_idx):
     assert_logit_prob(host(logit), host(prob), ref_logit, ref_prob, S, bias=0.2)
     # bias NULL and logit NULL
     api.assistant_score(F, dev(idx), P, dev(phi), None, None, prob)
-    _, ref_prob0 = ref.assistant_score(Fh, idx, P, phi)
-    assert np.allclose(host(prob), ref_prob0, rtol=1e-4, atol=1e-6)
+    _ref_logit0, ref_prob0 = ref.assistant_score(Fh, idx, P, phi)
+    assert_logit_prob(_ref_logit0, host(prob), _ref_logit0, ref_prob0, S)
 
 
 @pytest.mark.parametrize("P", [0, 1, 63, 64, 65, 255, 256, 257, 1000, 16384, 100_001])
@@ -355,6 +355,66 @@ def test_fused_step_matches_oracle_step(ref, ws, n, d, ld, P, gamma):
         assert np.array_equal(out["w"], w_van)
 
 
+def _offset_by_4_bytes(a):
+    """The same values in device memory that starts 4 bytes past a 16-byte boundary."""
+    a = np.ascontiguousarray(a)
+    buf = torch.zeros(a.size + 4, dtype=torch.float32, device="cuda")
+    assert buf.data_ptr() % 16 == 0
+    view = buf[1:1 + a.size].view(a.shape)
+    view.copy_(torch.from_numpy(a))
+    assert view.data_ptr() % 16 == 4
+    return view
+
+
+@pytest.mark.parametrize("which", ["x", "w", "phi"])
+def test_pointers_aligned_to_4_bytes_only(ref, ws, which):
+    """x, w or phi 4-byte aligned but not 16-byte aligned: the calls take the general kernels
+    (no 128-bit loads) and still match the oracle: score, Boss step, whole step."""
+    n, d, P = 500, 1024, 333
+    X, y = make_dense(n, d, 111, unit=True)
+    r = rng(112)
+    w0 = (1.2 * r.standard_normal(d)).astype(np.float32)
+    phi0 = (2.0 * r.standard_normal(d)).astype(np.float32)
+    idx = r.permutation(n)[:P].astype(np.int32)
+    Fh = ref.Features.dense(X)
+    Xd = _offset_by_4_bytes(X) if which == "x" else dev(X)
+    F = api.Features.dense(Xd)
+    place = lambda a, name: _offset_by_4_bytes(a) if which == name else dev(a)
+    # score
+    ref_logit, ref_prob = ref.assistant_score(Fh, idx, P, phi0, bias=0.1)
+    logit, prob = torch.zeros(P, device="cuda"), torch.zeros(P, device="cuda")
+    api.assistant_score(F, dev(idx), P, place(phi0, "phi"), scalar_dev(0.1), logit, prob)
+    assert_logit_prob(host(logit), host(prob), ref_logit, ref_prob, abs_dot_scale(Fh, idx, phi0), bias=0.1)
+    # Boss step on listed rows
+    lam, lr = 1e-3, 0.5
+    w_ref, loss_ref = ref.svm_sgd_step(Fh, y, idx, P, w0, lam, lr)
+    w = place(w0, "w")
+    loss = torch.zeros(P, device="cuda")
+    api.svm_sgd_step(F, dev(y), dev(idx), scalar_dev(P, torch.int32), P, w, lam, lr, 0.0, loss, ws)
+    S = abs_dot_scale(Fh, idx, w0)
+    assert_close_scaled(host(loss), loss_ref, S, "loss")
+    marg = y[idx] * (X[idx].astype(np.float64) @ w0.astype(np.float64))
+    assert np.all(np.abs(1 - marg) > RTOL * S), "a margin sits on the hinge kink: change the seed"
+    assert_close_scaled(host(w), w_ref, _w_scale(Fh, idx, y, w0, lr, lam, P, marg < 1), "w")
+    # whole step
+    gamma, step, T, lr_a, b0 = 0.1, 3, 0.2, 0.3, 0.1
+    for seed in range(5, 25):
+        out = ref.step(Fh, y, idx, P, w0, phi0, b0, gamma, seed, step, lam, lr, T, lr_a)
+        if clear_draws(ref, out["prob"], gamma, seed, step).all():
+            break
+    w, phi, b = place(w0, "w"), place(phi0, "phi"), scalar_dev(b0)
+    cfg = api.step_config(gamma, lam, lr, lr_a, 0.0, seed, step, scalar_dev(T))
+    keep = torch.zeros(P, dtype=torch.uint8, device="cuda")
+    pos = torch.zeros(P, dtype=torch.int32, device="cuda")
+    ids = torch.zeros(P, dtype=torch.int32, device="cuda")
+    cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    api.fused_step(F, dev(y), dev(idx), P, w, phi, b, cfg, None, None, keep, pos, ids, None, cnt, ws)
+    m = out["m"]
+    assert int(host(cnt)[0]) == m and np.array_equal(host(keep), out["keep"])
+    assert np.array_equal(host(pos)[:m], out["kept_pos"]) and np.array_equal(host(ids)[:m], out["kept_ids"])
+    _check_state(out, w, phi, b, Fh, out["kept_ids"], y, w0, phi0, b0, lr, lam, lr_a, T)
+
+
 def test_boss_assistant_step_equals_the_two_staged_calls(ref, ws):
     n, d, m = 500, 1024, 301
     X, y = make_dense(n, d, 71, unit=True)
@@ -489,44 +549,24 @@ def test_tiny_config_epoch_every_step(ref, ws, pipeline):
 
 
 def test_train_epoch_matches_oracle_driver(ref, ws):
-    """aa_train_epoch (device-side lr/sqrt(t) schedule, no host sync) against the oracle loop."""
+    """aa_train_epoch (device-side lr/sqrt(t) schedule, compaction carried from pass to pass, no
+    host sync) on the tiny configuration: every one of the 40 steps against the oracle step taken
+    from the GPU's previous state, at the single-step tolerances; then the whole epoch in one
+    call, bit-identical to the step-wise run."""
+    from stepwise import check_epoch
     X, y, _ = synth.tiny_svm()
     n, d = X.shape
-    P, lam, gamma, lr_a, T, seed, lr0 = 256, 1e-4, 0.1, 0.1, 0.0, 42, 0.01
     perm = synth.epoch_permutation(n, seed=7, epoch=0)
-    Fh = ref.Features.dense(X)
-    w_r, phi_r, b_r = np.zeros(d, np.float32), np.zeros(d, np.float32), 0.0
-    ms, t_upd, batches = [], 0, []
-    for t, idx in enumerate(synth.pools(perm, P)):
-        lr = np.float32(np.float32(lr0) / np.sqrt(np.float32(t_upd + 1)))
-        out = ref.step(Fh, y, idx, idx.shape[0], w_r, phi_r, b_r, gamma, seed + 0, 100 + t, lam, lr,
-                       T, lr_a)
-        assert clear_draws(ref, out["prob"], gamma, seed, 100 + t).all()
-        w_r, phi_r, b_r = out["w"], out["phi"], out["bias"]
-        ms.append(out["m"])
-        batches.append((out["kept_ids"], out["loss"]))
-        t_upd += 1 if out["m"] > 0 else 0
-    F = dense_features(X)
-    w, phi, b = dev(np.zeros(d, np.float32)), dev(np.zeros(d, np.float32)), scalar_dev(0.0)
-    Tt = scalar_dev(T)
-    cfg = api.step_config(gamma, lam, lr0, lr_a, 0.0, seed, 100, Tt)
-    tu = torch.zeros(1, dtype=torch.int32, device="cuda")
-    hist = torch.full((len(ms),), -1, dtype=torch.int32, device="cuda")
-    ids_hist = torch.full((len(ms), P), -1, dtype=torch.int32, device="cuda")
-    loss_hist = torch.full((len(ms), P), -3.0, device="cuda")
-    api.train_epoch(F, dev(y), dev(perm), n, P, w, phi, b, cfg, tu, hist, ws, ids_hist, loss_hist)
-    assert np.array_equal(host(hist), np.array(ms))
-    assert int(host(tu)[0]) == t_upd
-    # every step's batch: compaction carried by the next step's pass, except where the next
-    # pool is too short to carry it (the 16-row last pool) and for the last step itself
-    for t, (ids_ref, loss_ref) in enumerate(batches):
-        assert np.array_equal(host(ids_hist)[t, :ms[t]], ids_ref), f"batch {t}"
-        assert np.all(host(ids_hist)[t, ms[t]:] == -1)
-        assert np.allclose(host(loss_hist)[t, :ms[t]], loss_ref, rtol=1e-4, atol=1e-6)
-        assert np.all(host(loss_hist)[t, ms[t]:] == -3.0)
-    assert np.allclose(host(w), w_r, rtol=1e-4, atol=1e-6)
-    assert np.allclose(host(phi), phi_r, rtol=1e-4, atol=1e-6)
-    assert abs(float(host(b)[0]) - b_r) < 1e-5
+    Fh, F = ref.Features.dense(X), dense_features(X)
+    zeros = np.zeros(d, np.float32)
+    counts, state = check_epoch(ref, Fh, F, y, perm, n, 256, zeros, zeros, 0.0, gamma=0.1, seed=42,
+                                step0=100, lam=1e-4, lr0=0.01, lr_a=0.1, T=0.0, ws=ws)
+    assert len(counts) == 40 and counts[-1] <= 16 and state[3] == sum(1 for m in counts if m > 0)
+    # a second epoch from a trained state with a large step size (margins crowd the hinge kink)
+    counts2, _ = check_epoch(ref, Fh, F, y, synth.epoch_permutation(n, seed=7, epoch=1), n, 256,
+                             state[0], state[1], float(state[2][0]), gamma=0.1, seed=42, step0=140,
+                             lam=1e-4, lr0=8.0, lr_a=0.1, T=0.0, ws=ws, t_upd0=state[3])
+    assert 0 < min(counts2[:-1]) and max(counts2) < 256
 
 
 def test_argument_errors(ws):

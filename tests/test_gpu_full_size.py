@@ -10,13 +10,13 @@ import torch
 
 from paper_1905_03381_amd import api, synth
 
-from gpu_util import (abs_dot_scale, assert_close_scaled, assert_logit_prob, clear_draws, dev, host,
-                      scalar_dev)
+from gpu_util import (RTOL, abs_dot_scale, assert_close_scaled, assert_logit_prob, clear_draws, dev,
+                      host, scalar_dev)
 
 pytestmark = pytest.mark.gpu
 
 N, D, P = 1_000_000, 1024, 16384
-GAMMA, LAM, LR0, LR_A, SEED = 0.1, 1e-4, 1.0, 0.1, 42
+GAMMA, LAM, LR0, LR_A, SEED = 0.1, 1e-4, 256.0, 0.1, 42   # the bench's step size
 
 
 @pytest.fixture(scope="module")
@@ -27,6 +27,7 @@ def workload():
 
 
 def test_first_pools_and_last_short_pool(ref, workload):
+    from stepwise import check_epoch
     X, y, Xd, yd = workload
     perm = synth.epoch_permutation(N, seed=7, epoch=0)
     Fh = ref.Features.dense(X)
@@ -34,36 +35,15 @@ def test_first_pools_and_last_short_pool(ref, workload):
     ws = api.Workspace(P, D)
     Tt = scalar_dev(0.0)
     steps = 3
-    # oracle trajectory over the first pools
-    w_r, phi_r, b_r = np.zeros(D, np.float32), np.zeros(D, np.float32), 0.0
-    ms, batches = [], []
-    for t in range(steps):
-        idx = perm[t * P:(t + 1) * P]
-        lr = np.float32(np.float32(LR0) / np.sqrt(np.float32(t + 1)))
-        out = ref.step(Fh, y, idx, P, w_r, phi_r, b_r, GAMMA, SEED, t, LAM, lr, 0.0, LR_A)
-        assert clear_draws(ref, out["prob"], GAMMA, SEED, t).all()
-        assert out["m"] > 0
-        w_r, phi_r, b_r = out["w"], out["phi"], out["bias"]
-        ms.append(out["m"])
-        batches.append((out["kept_ids"], out["loss"]))
-    w, phi, b = torch.zeros(D, device="cuda"), torch.zeros(D, device="cuda"), scalar_dev(0.0)
-    tu = torch.zeros(1, dtype=torch.int32, device="cuda")
-    hist = torch.zeros(steps, dtype=torch.int32, device="cuda")
-    cfg = api.step_config(GAMMA, LAM, LR0, LR_A, 0.0, SEED, 0, Tt)
-    ids_hist = torch.full((steps, P), -1, dtype=torch.int32, device="cuda")
-    loss_hist = torch.full((steps, P), -3.0, device="cuda")
-    api.train_epoch(F, yd, dev(perm), steps * P, P, w, phi, b, cfg, tu, hist, ws, ids_hist, loss_hist)
-    assert np.array_equal(host(hist), np.array(ms))      # kept counts: exact
-    # the batch of every step (the first two compacted by the pass of the step after them,
-    # at exactly the 64 positions per block that pass can carry): ids exact, losses close
-    for t, (ids_ref, loss_ref) in enumerate(batches):
-        assert np.array_equal(host(ids_hist)[t, :ms[t]], ids_ref), f"batch {t}"
-        assert np.all(host(ids_hist)[t, ms[t]:] == -1)
-        assert np.allclose(host(loss_hist)[t, :ms[t]], loss_ref, rtol=1e-4, atol=1e-5)
-        assert np.all(host(loss_hist)[t, ms[t]:] == -3.0)
-    assert np.allclose(host(w), w_r, rtol=1e-4, atol=1e-7)
-    assert np.allclose(host(phi), phi_r, rtol=1e-4, atol=1e-7)
-    assert abs(float(host(b)[0]) - b_r) < 1e-5
+    # the first pools of the epoch at the bench's step size: every step against the oracle step
+    # from the GPU's previous state (single-step tolerances), then the three steps in one call
+    # (the first two compacted by the pass of the step after them, at exactly the 64 positions
+    # per block that pass can carry) bit-identical to the step-wise run
+    zeros = np.zeros(D, np.float32)
+    counts, state = check_epoch(ref, Fh, F, y, perm, steps * P, P, zeros, zeros, 0.0, gamma=GAMMA,
+                                seed=SEED, step0=0, lam=LAM, lr0=LR0, lr_a=LR_A, T=0.0, ws=ws)
+    assert all(0 < m < P for m in counts)
+    w, phi, b = dev(state[0]), dev(state[1]), dev(state[2])
 
     # one more full step from that state with every output compared element by element,
     # then the last pool of the epoch (576 rows)
@@ -72,7 +52,7 @@ def test_first_pools_and_last_short_pool(ref, workload):
         w0, phi0, b0 = host(w).copy(), host(phi).copy(), float(host(b)[0])
         lr = float(np.float32(LR0 / math.sqrt(t + 1)))
         out = ref.step(Fh, y, idx, size, w0, phi0, b0, GAMMA, SEED, t, LAM, lr, 0.0, LR_A)
-        assert clear_draws(ref, out["prob"], GAMMA, SEED, t).all()
+        clear = clear_draws(ref, out["prob"], GAMMA, SEED, t)
         cfg = api.step_config(GAMMA, LAM, lr, LR_A, 0.0, SEED, t, Tt)
         logit = torch.zeros(size, device="cuda")
         prob = torch.zeros(size, device="cuda")
@@ -83,17 +63,55 @@ def test_first_pools_and_last_short_pool(ref, workload):
         cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
         api.fused_step(F, yd, dev(idx), size, w, phi, b, cfg, logit, prob, keep, pos, ids, loss,
                        cnt, ws)
-        m = out["m"]
-        assert int(host(cnt)[0]) == m
         assert_logit_prob(host(logit), host(prob), out["logit"], out["prob"],
                           abs_dot_scale(Fh, idx, phi0), bias=b0)
-        assert np.array_equal(host(keep), out["keep"])
-        assert np.array_equal(host(pos)[:m], out["kept_pos"])
-        assert np.array_equal(host(ids)[:m], out["kept_ids"])
-        assert_close_scaled(host(loss)[:m], out["loss"], abs_dot_scale(Fh, out["kept_ids"], w0),
-                            "loss")
-        assert np.allclose(host(w), out["w"], rtol=1e-5, atol=1e-6)
-        assert np.allclose(host(phi), out["phi"], rtol=1e-5, atol=1e-6)
+        assert np.array_equal(host(keep)[clear], out["keep"][clear])
+        kept = np.flatnonzero(host(keep))
+        m = kept.size
+        assert int(host(cnt)[0]) == m
+        assert np.array_equal(host(pos)[:m], kept)                 # compaction of the GPU's own mask
+        assert np.array_equal(host(ids)[:m], idx[kept])
+        if clear.all():
+            assert m == out["m"] and np.array_equal(kept, out["kept_pos"])
+        # Boss step and Assistant update of the oracle on the rows the GPU kept
+        ids_g = idx[kept].astype(np.int32)
+        w_ref, loss_ref = ref.svm_sgd_step(Fh, y, ids_g, m, w0, LAM, lr)
+        phi_ref, b_ref = ref.assistant_update(Fh, ids_g, m, loss_ref, 0.0, phi0, b0, LR_A)
+        S = abs_dot_scale(Fh, ids_g, w0)
+        assert_close_scaled(host(loss)[:m], loss_ref, S, "loss")
+        Xk = np.abs(X[ids_g].astype(np.float64))
+        marg = y[ids_g].astype(np.float64) * (X[ids_g].astype(np.float64) @ w0.astype(np.float64))
+        near = np.abs(1.0 - marg) <= RTOL * (S + 1.0)
+        w_scale = abs(1 - lr * LAM) * np.abs(w0.astype(np.float64)) + lr / m * Xk[marg < 1].sum(axis=0)
+        assert_close_scaled(host(w), w_ref, w_scale, "w", atol=lr / m * Xk[near].sum(axis=0))
+        phi_scale = np.abs(phi0.astype(np.float64)) + LR_A / m * Xk.sum(axis=0)
+        assert_close_scaled(host(phi), phi_ref, phi_scale, "phi", atol=LR_A / m * Xk[near].sum(axis=0))
+        assert abs(float(host(b)[0]) - b_ref) <= RTOL * (abs(b0) + LR_A) + LR_A / m * int(near.sum())
+
+
+def test_dense_slice_five_epochs_every_step(ref):
+    """A 65,536-row slice of the dense configuration (d = 1024, pools of 16,384) trained for five
+    epochs at the bench's step size through aa_train_epoch: every one of the 20 steps is
+    compared with the oracle step taken from the GPU's previous state, and each epoch run in one
+    call is bit-identical to its step-wise run.  State, update counter and Philox step carry
+    over from epoch to epoch as in the bench."""
+    from stepwise import check_epoch
+    n = 65_536
+    X, y, _ = synth.dense_svm(n=n, d=D, threads=16)
+    Fh = ref.Features.dense(X)
+    F = api.Features.dense(torch.from_numpy(X).cuda())
+    ws = api.Workspace(P, D)
+    w, phi, b, t_upd = np.zeros(D, np.float32), np.zeros(D, np.float32), 0.0, 0
+    rates = []
+    for e in range(5):
+        perm = synth.epoch_permutation(n, seed=7, epoch=e)
+        counts, state = check_epoch(ref, Fh, F, y, perm, n, P, w, phi, b, gamma=GAMMA, seed=SEED,
+                                    step0=4 * e, lam=LAM, lr0=LR0, lr_a=LR_A, T=0.0, ws=ws,
+                                    t_upd0=t_upd)
+        w, phi, b, t_upd = state[0], state[1], float(state[2][0]), state[3]
+        rates.append(sum(counts) / n)
+    assert t_upd == 20
+    assert all(0.2 < r < 0.95 for r in rates)    # rows are dropped in every epoch, never all
 
 
 def test_gather_full_pool_rows_bit_exact(ref, workload):

@@ -562,6 +562,11 @@ def test_threshold_update_is_numpy_median_with_momentum(ref):
         assert init and np.float32(T) == want
     T2, init2 = ref.threshold_update(np.zeros(0, np.float32), 0.9, 1.25, True)
     assert T2 == 1.25 and init2
+    # a NaN loss has no rank: the threshold becomes NaN instead of an arbitrary value
+    bad = r.gamma(2.0, 0.5, 300).astype(np.float32)
+    bad[17] = np.nan
+    T3, init3 = ref.threshold_update(bad, 0.9, 1.25, False)
+    assert np.isnan(T3) and init3
 
 
 def test_threshold_momentum_rule_by_its_closed_form(ref):
