@@ -49,7 +49,7 @@ struct Ws {
 // model vectors as (w, phi) pairs, the per-block sums of the first columns, then the record
 // bins of the other columns.
 size_t general_pairs_offset(int32_t d) {  // (w, phi) pairs of the columns, indexed by column
-  return align_up((kGeneralHeader + 2 * (size_t)d) * sizeof(float), 256);
+  return align_up(general_clear_floats(d) * sizeof(float), 256);
 }
 size_t general_part_offset(int32_t d) {
   return general_pairs_offset(d) + align_up(2 * (size_t)d * sizeof(float), 256);
@@ -226,7 +226,7 @@ hipError_t run_pass(const PassSpec &s, const Ws &ws, int32_t *nblk_out, hipStrea
   const bool csr = s.F->layout == AA_CSR;
   float *acc = reinterpret_cast<float *>(ws.grad);
   if (s.mode & (kSvm | kAssist)) {
-    const size_t clear = kGeneralHeader + 2 * (size_t)s.F->d;
+    const size_t clear = general_clear_floats(s.F->d);
     const bool both = (s.mode & kSvm) && (s.mode & kAssist);
     const int32_t head = general_head_columns(s.F->d, 2);
     float2 *pairs = reinterpret_cast<float2 *>(ws.grad + general_pairs_offset(s.F->d));
@@ -262,9 +262,9 @@ hipError_t run_pass(const PassSpec &s, const Ws &ws, int32_t *nblk_out, hipStrea
   a.blk_cnt = ws.blk_cnt;
   a.blk_gb = ws.blk_gb;
   const int nvec = ((s.mode & kSvm) ? 1 : 0) + ((s.mode & kAssist) ? 1 : 0);
-  a.acc_w = acc + kGeneralHeader;
+  a.acc_w = reinterpret_cast<double *>(acc + kGeneralHeader);
   a.acc_used = reinterpret_cast<int32_t *>(acc) + 2;
-  a.acc_p = acc + kGeneralHeader + s.F->d;
+  a.acc_p = a.acc_w + s.F->d;
   a.part = reinterpret_cast<float *>(ws.grad + general_part_offset(s.F->d));
   a.head = general_head_columns(s.F->d, nvec);
   a.wp = (nvec == 2 && s.F->d > a.head)
@@ -338,9 +338,9 @@ hipError_t run_update(const PassSpec &s, const UpdateSpec &u, const Ws &ws, int3
   p.d = s.F->d;
   p.blk_cnt = ws.blk_cnt;
   p.blk_gb = ws.blk_gb;
-  p.acc_w = acc + kGeneralHeader;
+  p.acc_w = reinterpret_cast<const double *>(acc + kGeneralHeader);
   p.acc_used = reinterpret_cast<const int32_t *>(acc) + 2;
-  p.acc_p = acc + kGeneralHeader + s.F->d;
+  p.acc_p = p.acc_w + s.F->d;
   p.part = reinterpret_cast<const float *>(ws.grad + general_part_offset(s.F->d));
   p.nvec = ((s.mode & kSvm) ? 1 : 0) + ((s.mode & kAssist) ? 1 : 0);
   p.head = general_head_columns(s.F->d, p.nvec);

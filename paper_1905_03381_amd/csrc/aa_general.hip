@@ -48,42 +48,72 @@ __device__ __forceinline__ int bin_of(int c, int head, const BinPlan &p) {
   return ((c - head) >> kBinGroupLog2) & (p.nb - 1);
 }
 
-// Adds one entry's terms to the dense accumulators in HBM (the path of last resort).
+// Adds one entry's terms to the dense accumulators in HBM (the path of last resort).  They
+// are doubles like every other sum of entries: which entries end up here depends on timing,
+// so their sum must not round before it meets the rest of the column's total.
 template <bool SVM, bool ASSIST>
-__device__ __forceinline__ void add_global(const GenArgs &a, int c, float ta, float tb) {
+__device__ __forceinline__ void add_global(const GenArgs &a, int c, double ta, double tb) {
   *a.acc_used = 1;  // tells the update kernel to read the accumulators at all
-  if (SVM && ta != 0.f) unsafeAtomicAdd(a.acc_w + c, ta);
+  if (SVM && ta != 0.0) unsafeAtomicAdd(a.acc_w + c, ta);
   if (ASSIST) {
-    const float t = SVM ? tb : ta;
-    if (t != 0.f) unsafeAtomicAdd(a.acc_p + c, t);
+    const double t = SVM ? tb : ta;
+    if (t != 0.0) unsafeAtomicAdd(a.acc_p + c, t);
   }
 }
 
-// Empties the block's record buffer -- and with `with_hashed` its hashed slots -- into the
-// bins.  Whole block; the caller has put a barrier between the last append and this call.
-template <int R, int H, bool SVM, bool ASSIST>
+// The k-th of the three floats whose sum is the double `s` exactly (24 + 24 + 5 bits).
+__device__ __forceinline__ float float_part(double s, int k) {
+  const float hi = (float)s;
+  if (k == 0) return hi;
+  const double r1 = s - (double)hi;
+  const float mid = (float)r1;
+  return k == 1 ? mid : (float)(r1 - (double)mid);
+}
+
+// Empties the block's record buffer -- and with HASHED its hashed slots -- into the bins.
+// Whole block; the caller has put a barrier between the last append and this call.
+// Which columns win a hashed slot depends on the order in which the waves arrive, so a slot's
+// sum must leave the block without rounding: it goes out as up to three records whose float
+// terms add up to the double exactly (the second and third are zero, and skipped, unless the
+// sum needs more than 24 bits).  The bin owner adds every record of a column in doubles, so a
+// column's total does not depend on how its entries were split between slots and records.
+template <int R, int H, bool SVM, bool ASSIST, bool HASHED>
 __device__ __forceinline__ void flush_records(const GenArgs &a, int head, const int *s_rc,
                                               const float *s_ra, const float *s_rb, int *s_nrec,
                                               const int *s_tag, const double *s_ha,
-                                              const double *s_hb, bool with_hashed, int *s_hist,
-                                              int *s_base) {
-  constexpr int kPerR = R / kGradThreads, kPer = (R + H) / kGradThreads;
+                                              const double *s_hb, int *s_hist, int *s_base) {
+  constexpr int kPerR = R / kGradThreads, kPerH = HASHED ? 3 * H / kGradThreads : 0;
+  constexpr int kPer = kPerR + kPerH;
   static_assert(R % kGradThreads == 0 && H % kGradThreads == 0, "whole turns of the block");
   const int n = min(*s_nrec, R);
   const int nb = a.plan.nb;
   for (int t = threadIdx.x; t < nb; t += blockDim.x) s_hist[t] = 0;
   __syncthreads();
   int col[kPer], rank[kPer];
+  float va[kPer], vb[kPer];
 #pragma unroll
   for (int q = 0; q < kPer; ++q) {
     const int i = threadIdx.x + q * kGradThreads;
     int c = -1;
+    float ta = 0.f, tb = 0.f;
     if (q < kPerR) {
-      if (i < n) c = s_rc[i];
-    } else if (with_hashed) {
-      c = s_tag[i - R];
+      if (i < n) {
+        c = s_rc[i];
+        ta = s_ra[i];
+        if (SVM && ASSIST) tb = s_rb[i];
+      }
+    } else {
+      const int slot = (i - R) & (H - 1), part = (i - R) / H;
+      c = s_tag[slot];
+      if (c >= 0) {
+        ta = float_part(s_ha[slot], part);
+        if (SVM && ASSIST) tb = float_part(s_hb[slot], part);
+        if (ta == 0.f && tb == 0.f) c = -1;
+      }
     }
     col[q] = c;
+    va[q] = ta;
+    vb[q] = tb;
     rank[q] = c >= 0 ? atomicAdd(s_hist + bin_of(c, head, a.plan), 1) : 0;
   }
   __syncthreads();
@@ -99,20 +129,17 @@ __device__ __forceinline__ void flush_records(const GenArgs &a, int head, const 
   for (int q = 0; q < kPer; ++q) {
     const int c = col[q];
     if (c < 0) continue;
-    const int i = threadIdx.x + q * kGradThreads;
-    const float ta = q < kPerR ? s_ra[i] : (float)s_ha[i - R];
-    const float tb = (SVM && ASSIST) ? (q < kPerR ? s_rb[i] : (float)s_hb[i - R]) : 0.f;
     const int bin = bin_of(c, head, a.plan);
     const int pos = s_base[bin] + rank[q];
     if (pos < a.plan.cap) {
       TailRecord r;
       r.col = c;
-      r.a = ta;
-      r.b = tb;
+      r.a = va[q];
+      r.b = vb[q];
       r.pad = 0;
       a.bins[(size_t)bin * a.plan.cap + pos] = r;
     } else {
-      add_global<SVM, ASSIST>(a, c, ta, tb);
+      add_global<SVM, ASSIST>(a, c, va[q], vb[q]);
     }
   }
   __syncthreads();
@@ -377,8 +404,8 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
           const int fill = s_nrec;
           __syncthreads();
           if (fill > R / 2)
-            flush_records<R, H, SVM, ASSIST>(a, D, s_rc, s_ra, s_rb, &s_nrec, s_tag, s_ha, s_hb,
-                                          false, s_hist, s_base);
+            flush_records<R, H, SVM, ASSIST, false>(a, D, s_rc, s_ra, s_rb, &s_nrec, s_tag, s_ha,
+                                                    s_hb, s_hist, s_base);
         }
       }
     }
@@ -416,13 +443,13 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
       if (ASSIST) mine[(SVM ? a.head : 0) + k] = (float)s_p[k];
     }
     if (binned) {
-      flush_records<R, H, SVM, ASSIST>(a, D, s_rc, s_ra, s_rb, &s_nrec, s_tag, s_ha, s_hb, true,
-                                    s_hist, s_base);
+      flush_records<R, H, SVM, ASSIST, true>(a, D, s_rc, s_ra, s_rb, &s_nrec, s_tag, s_ha, s_hb,
+                                             s_hist, s_base);
     } else {
       for (int k = threadIdx.x; k < H; k += blockDim.x) {
         const int c = s_tag[k];
         if (c >= 0)
-          add_global<SVM, ASSIST>(a, c, (float)s_ha[k], (SVM && ASSIST) ? (float)s_hb[k] : 0.f);
+          add_global<SVM, ASSIST>(a, c, s_ha[k], (SVM && ASSIST) ? s_hb[k] : 0.0);
       }
     }
   }
@@ -591,23 +618,25 @@ __device__ __forceinline__ void apply_bin(const ApplyArgs &a, int bin, double *s
   auto sum_of = [&](int k) {  // over the copies, in order
     double v = 0.0;
     for (int c = 0; c < copies; ++c) v += s_bin[c * span + k];
-    return (float)v;
+    return v;
   };
-  // (the dense accumulators hold something only if an entry found no room in LDS or in a bin)
-  auto acc_w_of = [&](int c) { return (acc_used && a.w) ? a.acc_w[c] : 0.f; };
-  auto acc_p_of = [&](int c) { return (acc_used && a.phi) ? a.acc_p[c] : 0.f; };
+  // (the dense accumulators hold something only if an entry found no room in LDS or in a bin);
+  // a column's total is rounded to fp32 once, after everything has been added in doubles
+  auto acc_w_of = [&](int c) { return (acc_used && a.w) ? a.acc_w[c] : 0.0; };
+  auto acc_p_of = [&](int c) { return (acc_used && a.phi) ? a.acc_p[c] : 0.0; };
 #pragma unroll
   for (int u = 0; u < kCol; ++u) {
     if (col[u] < 0) continue;
     const int k = tid + u * kApplyThreads;
-    const float va = sum_of(k), vb = a.nvec == 2 ? sum_of(cols + k) : va;
-    fold.loaded(col[u], acc_w_of(col[u]) + (a.w ? va : 0.f), acc_p_of(col[u]) + vb, wo[u], po[u]);
+    const double va = sum_of(k), vb = a.nvec == 2 ? sum_of(cols + k) : va;
+    fold.loaded(col[u], (float)(acc_w_of(col[u]) + (a.w ? va : 0.0)), (float)(acc_p_of(col[u]) + vb),
+                wo[u], po[u]);
   }
   for (int k = tid + kCol * kApplyThreads; k < cols; k += kApplyThreads) {
     const int c = bin_column(k, bin, a);
     if (c >= a.d) continue;
-    const float va = sum_of(k), vb = a.nvec == 2 ? sum_of(cols + k) : va;
-    fold.column(c, acc_w_of(c) + (a.w ? va : 0.f), acc_p_of(c) + vb);
+    const double va = sum_of(k), vb = a.nvec == 2 ? sum_of(cols + k) : va;
+    fold.column(c, (float)(acc_w_of(c) + (a.w ? va : 0.0)), (float)(acc_p_of(c) + vb));
   }
 }
 
@@ -682,7 +711,7 @@ __global__ __launch_bounds__(kApplyThreads) void k_apply_general(const ApplyArgs
     const int m = pass_totals(a, cnt, gbs, s_m, s_g, &gb_pass);
     const Fold fold(a, m);
     for (int k = a.head + bid * blockDim.x + t; k < a.d; k += nrest * blockDim.x)
-      fold.column(k, a.w ? a.acc_w[k] : 0.f, a.phi ? a.acc_p[k] : 0.f);
+      fold.column(k, a.w ? (float)a.acc_w[k] : 0.f, a.phi ? (float)a.acc_p[k] : 0.f);
   }
 }
 

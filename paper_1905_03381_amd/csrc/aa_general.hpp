@@ -76,8 +76,8 @@ struct GenArgs {
   // the pass updates both vectors)
   const float2 *wp;
   // atomic accumulators (zeroed before the pass); *acc_used (zeroed too) is set by whoever adds
-  float *acc_w;      // [d]
-  float *acc_p;      // [d]
+  double *acc_w;     // [d]
+  double *acc_p;     // [d]
   int32_t *acc_used;
   // per-block kept count and bias-gradient sum of a gradient pass (plain stores)
   int32_t *blk_cnt;  // [blocks of the pass]
@@ -98,7 +98,10 @@ struct GenArgs {
 int32_t general_head_columns(int32_t d, int nvec);
 constexpr int kGeneralGradBlocks = 256;
 // floats ahead of the accumulators: 16 scalars, then the 64-bit fill counts of the bins
+// (an even count: the accumulators behind it are doubles)
 constexpr int kGeneralHeader = 16 + 2 * kMaxBins;
+// floats the header and the two accumulators of d doubles take
+inline size_t general_clear_floats(int32_t d) { return kGeneralHeader + 4 * (size_t)d; }
 inline size_t general_part_floats(int32_t d) {
   const size_t per_block = 2 * (size_t)d < 16384 ? 2 * (size_t)d : 16384;
   return kGeneralGradBlocks * per_block;
@@ -106,8 +109,8 @@ inline size_t general_part_floats(int32_t d) {
 
 struct ApplyArgs {
   int32_t d;
-  const float *acc_w;
-  const float *acc_p;
+  const double *acc_w;
+  const double *acc_p;
   const int32_t *acc_used;  // 0: the pass added nothing to the accumulators
   const int32_t *blk_cnt;  // per-block kept counts and bias-gradient sums of the pass
   const float *blk_gb;

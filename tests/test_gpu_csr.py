@@ -172,6 +172,41 @@ def test_csr_fused_step(ref, ws, sparse):
                         "phi")
 
 
+def _bits(t):
+    return host(t).view(np.uint32).copy()
+
+
+def test_csr_fused_steps_repeat_bit_for_bit(ws, sparse):
+    """Five chained whole steps on the sparse shape, run four times from the same state: model,
+    bias and losses come out with the same bits every time.  (Entries of a column reach its
+    total by three routes -- the block's table, a hashed slot, a record -- and which route an
+    entry takes depends on timing; every route adds in doubles and rounds once.)"""
+    rowptr, col, val, y, d = sparse
+    n, P, steps = rowptr.size - 1, 6000, 5
+    r = rng(31)
+    w0 = r.standard_normal(d).astype(np.float32)
+    phi0 = r.standard_normal(d).astype(np.float32)
+    perm = dev(r.permutation(n)[:steps * P].astype(np.int32))
+    F = csr_features(rowptr, col, val, d)
+    yd, Tt = dev(y), scalar_dev(0.3)
+    cfg = api.step_config(0.1, 1e-3, 0.5, 0.3, 0.0, 5, 0, Tt)
+
+    def run():
+        w, phi, b = dev(w0), dev(phi0), scalar_dev(0.1)
+        hist = torch.zeros(steps, dtype=torch.int32, device="cuda")
+        loss = torch.full((steps, P), -3.0, device="cuda")
+        api.train_epoch(F, yd, perm, steps * P, P, w, phi, b, cfg, None, hist, ws, None, loss)
+        return _bits(w), _bits(phi), _bits(b), _bits(loss), host(hist).tolist()
+
+    first = run()
+    assert min(first[4]) > 500 and not np.array_equal(first[0], w0.view(np.uint32))
+    for _ in range(3):
+        again = run()
+        assert again[4] == first[4]
+        for name, x0, x1 in zip(("w", "phi", "bias", "losses"), first, again):
+            assert np.array_equal(x0, x1), f"{name} differs between two runs of the same steps"
+
+
 def test_gather_csr(ref, ws, sparse):
     rowptr, col, val, y, d = sparse
     n = rowptr.size - 1
@@ -232,7 +267,7 @@ def test_sparse_config_full_size_first_pools(ref):
     for t in range(2):
         idx = perm[t * P:(t + 1) * P]
         lr = float(np.float32(1.0 / np.sqrt(t + 1)))
-        w_prev, phi_prev = w_r, phi_r
+        w_prev, phi_prev, b_prev = w_r, phi_r, b_r
         # the scores do not depend on the Philox key: take the first key under which no draw of
         # this pool falls into the rounding band of its keep probability
         for seed in range(42, 74):
@@ -265,6 +300,13 @@ def test_sparse_config_full_size_first_pools(ref):
         absx = _col_abs_sum(Fh, kept, d)
         assert_close_scaled(host(phi), phi_r, np.abs(phi_prev.astype(np.float64)) + lr_a / m * absx,
                             f"phi step {t}")
+        # the same step twice more from the same state: the same bits
+        got = (host(w).copy(), host(phi).copy(), host(b).copy())
+        for _ in range(2):
+            w, phi, b = dev(w_prev), dev(phi_prev), scalar_dev(b_prev)
+            api.fused_step(F, yd, dev(idx), P, w, phi, b, cfg, None, prob, keep, pos, ids, loss, cnt, ws)
+            assert np.array_equal(host(w), got[0]) and np.array_equal(host(phi), got[1])
+            assert np.array_equal(host(b), got[2])
         # the GPU state goes on from the oracle's bits so that step 2 is compared on equal inputs
         w, phi, b = dev(w_r), dev(phi_r), scalar_dev(b_r)
 
@@ -304,6 +346,14 @@ def test_train_epoch_on_csr_rows(ref, ws, sparse):
     assert np.allclose(host(w), w_r, rtol=5e-4, atol=5e-6)
     assert np.allclose(host(phi), phi_r, rtol=5e-4, atol=5e-6)
     assert abs(float(host(b)[0]) - b_r) < 1e-5
+    # the gradient sums do not depend on the order in which waves and blocks arrive: the same
+    # epoch again gives the same bits
+    first = (host(w).copy(), host(phi).copy(), host(b).copy())
+    for _ in range(3):
+        w, phi, b = dev(np.zeros(d, np.float32)), dev(np.zeros(d, np.float32)), scalar_dev(0.0)
+        api.train_epoch(F, dev(y), dev(perm), n, P, w, phi, b, cfg, None, hist, ws, ids, None)
+        assert np.array_equal(host(w), first[0]) and np.array_equal(host(phi), first[1])
+        assert np.array_equal(host(b), first[2])
     # the device-side step-size schedule needs the register-resident dense kernels
     with pytest.raises(api.AAError):
         api.train_epoch(F, dev(y), dev(perm), n, P, w, phi, b, cfg,
@@ -357,6 +407,11 @@ def test_csr_updates_uniform_columns(ref, n, nnz_lo, nnz_hi):
     assert_close_scaled(host(w), w_ref, np.abs(w0.astype(np.float64)) + lr / m * absx, "w",
                         atol=lr / m * _col_abs_sum_sp(Fh, rows[on_kink], d))
     assert np.abs(w_ref - w0).max() > 1e-3  # the step is visible at the tolerance
+    w_bits = host(w).copy()
+    for _ in range(2):   # (accumulators included: the same bits on every run)
+        w = dev(w0)
+        api.svm_sgd_step(F, dev(y), dev(rows), scalar_dev(m, torch.int32), m, w, lam, lr, 0.0, loss, ws)
+        assert np.array_equal(host(w), w_bits)
     phi_ref, b_ref = ref.assistant_update(Fh, rows, m, loss_ref, T, phi0, b0, lr_a)
     phi, b = dev(phi0), scalar_dev(b0)
     api.assistant_update(F, dev(rows), scalar_dev(m, torch.int32), m, dev(loss_ref), scalar_dev(T),

@@ -465,10 +465,13 @@ def test_fused_step_empty_pool_and_nothing_kept(ref, ws):
     assert int(host(cnt)[0]) == 0 and np.array_equal(host(w), w0)
 
 
-def test_fused_step_is_deterministic(ws):
-    n, d, P = 3000, 1024, 2500
+@pytest.mark.parametrize("n,d,P", [(3000, 1024, 2500),    # register-resident rows
+                                   (900, 130, 800),       # general kernel, all columns in its table
+                                   (700, 6000, 600)])     # general kernel: table, bins, accumulators
+def test_fused_step_is_deterministic(n, d, P):
     X, y = make_dense(n, d, 91, unit=True)
     F = dense_features(X)
+    ws = api.Workspace(P, d)
     idx = dev(rng(92).permutation(n)[:P].astype(np.int32))
     w0 = rng(93).standard_normal(d).astype(np.float32)
     Tt = scalar_dev(0.0)
