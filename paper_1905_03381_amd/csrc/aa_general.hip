@@ -466,6 +466,196 @@ __global__ __launch_bounds__(256) void k_zero_f32(float *p, size_t count) {
 
 // What a pass that updates both vectors needs beforehand, in one launch: the accumulators and
 // the header cleared, and the two model vectors side by side for the columns past the LDS table.
+// Scoring pass over CSR rows with the first kScoreTableCols entries of phi in LDS: one block of
+// 16 waves per compute unit loads them once and then walks its rows; only columns past the
+// table are gathered through the caches.  Pays when phi is too large for the vector L1 (a few
+// thousand floats) and the rows are many: the gathers of k_rows_general then miss the L1 and
+// pull a line from L2 for four bytes each.  Same outputs and the same order of additions per
+// row as k_rows_general<16, kPool, true>, so the two give the same bits.
+#ifndef AA_SCORE_TABLE_COLS
+#define AA_SCORE_TABLE_COLS 39936
+#endif
+constexpr int kScoreTableCols = AA_SCORE_TABLE_COLS;  // 156 KB of the 160 KB
+constexpr int kScoreTableThreads = 1024;
+// Taken for pools of at least kScoreTableMinRows rows when phi is too large for the vector L1
+// to serve (more than kScoreTableMinCols columns) and the table holds at least half of it:
+// measured on 1,000,000 token-list rows over 64,002 columns 236 -> 161 us per launch; on
+// 65,536 rows of about 100 entries over 2^20 Zipf-distributed columns, where a quarter of the
+// entries lie past the table, k_rows_general stays ahead (34 us against 48).
+#ifndef AA_SCORE_TABLE_MIN_COLS
+#define AA_SCORE_TABLE_MIN_COLS 16384
+#endif
+constexpr int kScoreTableMinCols = AA_SCORE_TABLE_MIN_COLS, kScoreTableMinRows = 16384;
+constexpr int kScoreTableMaxCols = 2 * kScoreTableCols;
+
+// No load of the main loop sits behind a branch (a lane with nothing to read asks for an
+// offset outside its buffer resource, which costs no memory access and reads as zero), so the
+// waits the compiler places count the loads in flight exactly and never drain them: the
+// entries of the row groups one and two steps ahead and the cold-column gathers of the next
+// group stay outstanding while the current group is added up, and the row extents arrive a
+// round (64 rows) ahead, the row ids two rounds.  Rows longer than one chunk (128 entries) are
+// rare in data this kernel is for; they are skipped in the loop and walked afterwards.
+template <bool VAL>
+__global__ __launch_bounds__(kScoreTableThreads) void k_score_table(const GenArgs a) {
+  constexpr int GL = 16, G = kWave / GL, kUnroll = 8, kChunk = GL * kUnroll;
+  constexpr int kIters = kWave / G;  // row groups per round
+  __shared__ float s_phi[kScoreTableCols];
+  const int D = min(kScoreTableCols, a.d);
+  for (int k = threadIdx.x; k < D; k += kScoreTableThreads) s_phi[k] = a.phi[k];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = kScoreTableThreads >> 6;
+  const int grp = lane / GL, sub = lane % GL;
+  const int total = a.count_max;
+  const int nwaves = gridDim.x * nw, gwave = blockIdx.x * nw + wave;
+  const int per = total / nwaves, rem = total % nwaves;
+  const int lo = gwave * per + min(gwave, rem);
+  const int hi = lo + per + (gwave < rem ? 1 : 0);
+  const float b = a.bias ? *a.bias : 0.f;
+  // an address that is always readable, for lanes with nothing to load
+  const int *const nowhere = reinterpret_cast<const int *>(a.rowptr);
+  __syncthreads();
+
+  // Entries and cold columns are read through buffer resources: a lane with nothing to read
+  // gives an offset past the resource's range, for which the hardware returns zero without a
+  // memory access -- no stand-in addresses, no masks where the values are used (a missing entry
+  // is column 0 with value 0, as in k_rows_general).  Offsets are 32 bits: rows whose entries
+  // lie beyond kSpan bytes of the arrays take the walk after the loop.
+  constexpr int kNone = (int)0x80000000;         // out of every resource's range
+  constexpr long long kSpan = 0x7fffffffll / 4;  // entries within reach of a 32-bit byte offset
+  const __amdgpu_buffer_rsrc_t r_col = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<int32_t *>(a.col), 0, kNone, 0x00020000);
+  const __amdgpu_buffer_rsrc_t r_val = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<float *>(VAL ? a.val : a.phi), 0, kNone, 0x00020000);
+  const __amdgpu_buffer_rsrc_t r_phi = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<float *>(a.phi), 0, a.d * 4, 0x00020000);
+  struct Slot {  // one chunk per lane group
+    int c[kUnroll];
+    float x[kUnroll];
+    float far[kUnroll];
+  };
+  // entries [e, e + kChunk) of the row that starts at entry e0 and has len entries
+  auto request = [&](int e0, int len, int e, Slot &t) __attribute__((always_inline)) {
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int eu = e + sub + u * GL;
+      const int off = eu < len ? (e0 + eu) * 4 : kNone;
+      t.c[u] = __builtin_amdgcn_raw_buffer_load_b32(r_col, off, 0, 0);
+      if (VAL)
+        t.x[u] = __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(r_val, off, 0, 0));
+      else
+        t.x[u] = eu < len ? 1.f : 0.f;
+    }
+  };
+  auto gather = [&](Slot &t) __attribute__((always_inline)) {  // columns past the table
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u)
+      t.far[u] = __int_as_float(
+          __builtin_amdgcn_raw_buffer_load_b32(r_phi, t.c[u] >= D ? t.c[u] * 4 : kNone, 0, 0));
+  };
+  auto dot = [&](const Slot &t, float dp) __attribute__((always_inline)) {
+    float near[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) near[u] = s_phi[min(t.c[u], D - 1)];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u)
+      dp = __fmaf_rn(t.c[u] >= D ? t.far[u] : near[u], t.x[u], dp);
+    return dp;
+  };
+  auto emit = [&](int j, float dp, float u) __attribute__((always_inline)) {
+    const float s = dp + b;
+    const float g = sigmoidf_(s);
+    if (a.logit) a.logit[j] = s;
+    if (a.prob) a.prob[j] = g;
+    if (a.flags)
+      a.flags[j] = (!a.do_keep || keep_decision(u, g, a.gamma, a.one_minus_gamma)) ? 1 : 0;
+  };
+
+  // raw loads of the row id of pool position j and of the extent of a row
+  auto row_id = [&](int j) __attribute__((always_inline)) {
+    return *((j < hi && a.rows) ? a.rows + j : nowhere);
+  };
+  struct Extent {
+    int64_t lo, hi;
+  };
+  auto extent = [&](int j, int raw_id) __attribute__((always_inline)) {
+    const int row = j < hi ? (a.rows ? raw_id : j) : 0;
+    Extent e;
+    e.lo = a.rowptr[row];
+    e.hi = a.rowptr[row + 1];
+    return e;
+  };
+  Extent cur = extent(lo + lane, row_id(lo + lane));
+  Extent next = extent(lo + kWave + lane, row_id(lo + kWave + lane));
+  int id_after = row_id(lo + 2 * kWave + lane);
+  bool any_longer = false;
+
+  constexpr int kAhead = 3;  // row groups in flight; slot (it % kAhead) holds group it of a round
+  static_assert(kIters % kAhead == 1, "the rotation below ends on slot 0");
+  Slot t[kAhead];
+  for (int base = lo; base < hi; base += kWave) {
+    const float u_l = a.do_keep ? keep_uniform(a.key, (uint32_t)(base + lane)) : 2.f;
+    int len_cur = base + lane < hi ? (int)(cur.hi - cur.lo) : 0;
+    if (cur.hi > kSpan) len_cur = kChunk + 1;  // (out of reach: a row for the walk after the loop)
+    any_longer = any_longer || len_cur > kChunk;
+    auto request_group = [&](int it, Slot &s) __attribute__((always_inline)) {
+      const int li = min(it * G + grp, kWave - 1);
+      const int e0 = __shfl((int)cur.lo, li, kWave);
+      const int len = __shfl(len_cur, li, kWave);
+      request(e0, (it < kIters && len <= kChunk) ? len : 0, 0, s);
+    };
+    auto finish_group = [&](int it, float dp) __attribute__((always_inline)) {
+      const int li = it * G + grp;
+      const int len = __shfl(len_cur, li, kWave);
+      const float u = __shfl(u_l, li, kWave);
+      dp = gsum<GL>(dp);
+      if (sub == 0 && base + li < hi && len <= kChunk) emit(base + li, dp, u);
+    };
+    // the extents of the next round and the row ids of the one after go out ahead of this
+    // round's entries: the only loads of a round that wait for nothing
+    const Extent coming = extent(base + 2 * kWave + lane, id_after);
+    id_after = row_id(base + 3 * kWave + lane);
+#pragma unroll
+    for (int p = 0; p < kAhead; ++p) request_group(p, t[p]);
+    gather(t[0]);
+#pragma unroll 1
+    for (int it0 = 0; it0 + 1 < kIters; it0 += kAhead) {
+#pragma unroll
+      for (int p = 0; p < kAhead; ++p) {
+        gather(t[(p + 1) % kAhead]);  // group it + 1: its entries were requested two steps ago
+        const float dp = dot(t[p], 0.f);
+        request_group(it0 + p + kAhead, t[p]);
+        finish_group(it0 + p, dp);
+      }
+    }
+    finish_group(kIters - 1, dot(t[0], 0.f));
+    cur = next;
+    next = coming;
+  }
+  if (__ballot(any_longer) == 0ull) return;
+  // rows of more than one chunk, one after the other in the wave's first lane group
+  for (int base = lo; base < hi; base += kWave) {
+    const int j_l = base + lane;
+    const Extent e_l = extent(j_l, row_id(j_l));
+    const int len_l = j_l < hi ? (int)(e_l.hi - e_l.lo) : 0;
+    const float u_l = a.do_keep ? keep_uniform(a.key, (uint32_t)j_l) : 2.f;
+    unsigned long long longer = __ballot(len_l > kChunk || (j_l < hi && e_l.hi > kSpan));
+    while (longer != 0ull) {
+      const int li = __ffsll((long long)longer) - 1;
+      longer &= longer - 1;
+      const long long e0 = __shfl((long long)e_l.lo, li, kWave);
+      const int len = grp == 0 ? __shfl(len_l, li, kWave) : 0;
+      const float u = __shfl(u_l, li, kWave);
+      float dp = 0.f;
+      for (int e = sub; e < len; e += GL) {  // (the order of a lane's additions is the loop's)
+        const int c = a.col[e0 + e];
+        const float xv = VAL ? a.val[e0 + e] : 1.f;
+        dp = __fmaf_rn(c < D ? s_phi[c] : a.phi[c], xv, dp);
+      }
+      dp = gsum<GL>(dp);
+      if (lane == 0) emit(base + li, dp, u);
+    }
+  }
+}
+
 __global__ __launch_bounds__(256) void k_prepare_general(float *p, size_t count, const float *w,
                                                          const float *phi, float2 *wp, int head,
                                                          int d) {
@@ -761,6 +951,14 @@ int32_t general_pass_blocks(int32_t count, bool csr, int mode) {
 
 hipError_t launch_general_pass(const GenArgs &a, int mode, bool csr, int32_t nblk,
                                hipStream_t st, hipEvent_t e0, hipEvent_t e1) {
+  if (csr && mode == kPool && a.d > kScoreTableMinCols && a.d <= kScoreTableMaxCols &&
+      a.count_max >= kScoreTableMinRows) {
+    if (a.val)
+      launch_stamped(k_score_table<true>, dim3(kGeneralGradBlocks), dim3(kScoreTableThreads), st, e0, e1, a);
+    else
+      launch_stamped(k_score_table<false>, dim3(kGeneralGradBlocks), dim3(kScoreTableThreads), st, e0, e1, a);
+    return hipGetLastError();
+  }
   if (csr) return launch_gl<16, true>(a, mode, nblk, st, e0, e1);
   return launch_gl<64, false>(a, mode, nblk, st, e0, e1);
 }

@@ -56,6 +56,55 @@ def test_csr_score_and_fused_keep(ref, ws, sparse):
     assert m == int(k.sum()) and np.array_equal(host(pos)[:m], np.flatnonzero(k))
 
 
+@pytest.mark.parametrize("ones", [False, True])
+@pytest.mark.parametrize("indexed", [True, False])
+def test_csr_score_large_pool_equals_small_pools(ref, ws, ones, indexed):
+    """Pools of 16,384 rows and more over 16,385 to 79,872 columns are scored by the kernel that
+    keeps the head of phi in LDS, smaller ones by the general kernel: both add a row's terms in
+    the same order, so one pool of 25,001 rows and the same rows in pools of 9000 give the same
+    bits -- and the oracle's values.  Rows of 0 to 260 entries: half of them exceed the 128
+    entries of the first kernel's main loop and take its separate walk; a fifth of the
+    columns lie past its table."""
+    n, d, P = 30_000, 50_000, 25_001
+    r = rng(41)
+    lens = r.integers(0, 261, size=n)
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(lens, out=rowptr[1:])
+    col = r.integers(0, d, size=int(rowptr[-1])).astype(np.int32)
+    val = (r.standard_normal(col.size) / 10.0).astype(np.float32)
+    phi = r.standard_normal(d).astype(np.float32)
+    idx = r.permutation(n)[:P].astype(np.int32) if indexed else None
+    Fh = ref.Features.csr(rowptr, col, None if ones else val, d)
+    F = csr_features(rowptr, col, None if ones else val, d)
+    lens = lens[idx if indexed else slice(0, P)]
+    assert (lens > 128).mean() > 0.3 and (lens <= 128).mean() > 0.3 and (lens == 0).sum() > 10
+    bias, gamma, seed, step = scalar_dev(-0.4), 0.2, 11, 6
+    logit, prob = torch.zeros(P, device="cuda"), torch.zeros(P, device="cuda")
+    api.assistant_score(F, None if idx is None else dev(idx), P, dev(phi), bias, logit, prob)
+    ids = idx if indexed else np.arange(P, dtype=np.int32)
+    ref_logit, ref_prob = ref.assistant_score(Fh, ids, P, phi, bias=-0.4)
+    assert_logit_prob(host(logit), host(prob), ref_logit, ref_prob, abs_dot_scale(Fh, ids, phi), bias=-0.4)
+    logit2, prob2 = torch.zeros(P, device="cuda"), torch.zeros(P, device="cuda")
+    for lo in range(0, P, 9000):
+        m = min(9000, P - lo)
+        api.assistant_score(F, dev(ids[lo:lo + m]), m, dev(phi), bias, logit2[lo:], prob2[lo:])
+    assert np.array_equal(host(logit), host(logit2)) and np.array_equal(host(prob), host(prob2))
+    # keep flags of the fused score + keep + compact call: same draws, same probabilities
+    keep = torch.zeros(P, dtype=torch.uint8, device="cuda")
+    pos = torch.full((P,), -1, dtype=torch.int32, device="cuda")
+    cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    prob3 = torch.zeros(P, device="cuda")
+    api.score_shrink(F, None if idx is None else dev(idx), P, dev(phi), bias, gamma, seed, step, None,
+                     prob3, keep, pos, cnt, ws)
+    assert np.array_equal(host(prob3), host(prob))
+    keep_ref, _ = ref.shrink(ref_prob, gamma, seed, step)
+    clear = clear_draws(ref, ref_prob, gamma, seed, step)
+    k = host(keep)
+    assert np.array_equal(k[clear], keep_ref[clear])
+    m = int(host(cnt)[0])
+    assert m == int(k.sum()) and np.array_equal(host(pos)[:m], np.flatnonzero(k))
+
+
 def test_csr_all_ones_values(ref, ws):
     """Token lists: val == NULL means every entry is 1; repeated tokens add."""
     rowptr, col, val, len_s, len_t, d = synth.sentence_pairs(n=5000, vocab=2000)
