@@ -136,6 +136,18 @@ int main() {
   time_graph("consecutive 64 MiB, 2048 blocks x 4 waves", [&](int r) {
     hipLaunchKernelGGL(k_read_stream, dim3(2048), dim3(256), 0, st,
                        reinterpret_cast<const f4 *>(x + (size_t)r * P * kD), (size_t)P * kD / 4, out); }, NPOOL, pool_bytes);
+  // re-reads: does a pool that was read one, two or four launches ago come back faster (from the
+  // 256 MB memory-side cache) than one read for the first time?
+  time_graph("random rows, 8 waves x 2, the same pool every launch", [&](int) {
+    hipLaunchKernelGGL(k_read_rows<2>, dim3(256), dim3(512), 0, st, x, dperm, P, out); }, NPOOL, pool_bytes);
+  time_graph("random rows, 8 waves x 2, two pools in turn (128 MiB)", [&](int r) {
+    hipLaunchKernelGGL(k_read_rows<2>, dim3(256), dim3(512), 0, st, x, dperm + (size_t)(r % 2) * P, P, out); }, NPOOL, pool_bytes);
+  time_graph("random rows, 8 waves x 2, three pools in turn (192 MiB)", [&](int r) {
+    hipLaunchKernelGGL(k_read_rows<2>, dim3(256), dim3(512), 0, st, x, dperm + (size_t)(r % 3) * P, P, out); }, NPOOL, pool_bytes);
+  time_graph("random rows, 8 waves x 2, four pools in turn (256 MiB)", [&](int r) {
+    hipLaunchKernelGGL(k_read_rows<2>, dim3(256), dim3(512), 0, st, x, dperm + (size_t)(r % 4) * P, P, out); }, NPOOL, pool_bytes);
+  time_graph("random rows, 8 waves x 2, six pools in turn (384 MiB)", [&](int r) {
+    hipLaunchKernelGGL(k_read_rows<2>, dim3(256), dim3(512), 0, st, x, dperm + (size_t)(r % 6) * P, P, out); }, NPOOL, pool_bytes);
   time_graph("4 pools (256 MiB) of random rows in one launch, 8 waves x 2", [&](int r) {
     hipLaunchKernelGGL(k_read_rows<2>, dim3(256), dim3(512), 0, st, x, dperm + (size_t)(r % 15) * 4 * P, 4 * P, out); }, NPOOL, 4 * pool_bytes);
   time_graph("16 pools (1 GiB) of random rows in one launch, 8 waves x 2", [&](int r) {

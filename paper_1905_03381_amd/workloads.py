@@ -216,7 +216,7 @@ def translation(a, torch, api, synth):
                        _stage("length-bucketed batches", us_bucket, m * (8 + 4 + 4 + 4)),
                        _stage("compacted CSR of kept pairs", us_rows, 2 * kept_nnz * entry + m * 20),
                        _stage("Assistant update over kept pairs", us_upd, kept_nnz * entry + m * 16,
-                              note="bound by LDS atomics")]}
+                              note="latency-bound: no unit is busy more than 40 % of the time")]}
 
 
 def _dense_job(a, torch, api, synth):
