@@ -87,7 +87,7 @@ def sparse(a, torch, api, synth):
                         f"{steps} pools per epoch",
             "candidates_per_s": P / us_step * 1e6,
             "stages": [_stage("fused step (score, keep, compact, SVM step, Assistant update)", us_step,
-                              row_bytes, note="bound by the model gathers and LDS atomics, not by HBM"),
+                              row_bytes, note="bound by the latency of the cold-column gathers, not by HBM"),
                        _stage("assistant score only", us_score, row_bytes)]}
 
 
