@@ -211,12 +211,54 @@ __global__ __launch_bounds__(kCsrTile) void k_csr_rowptr_tiles(const GatherCsrAr
 
 // A wave takes 64 kept rows at a time: every lane fetches the extent of one row (position, id,
 // row pointers, output offset: one dependent chain for all 64), then groups of 16 lanes copy the
-// rows four at a time, four entries per lane in flight.
+// rows four at a time.  A lane moves four consecutive entries with one 128-bit load and one
+// 128-bit store per array (dword-aligned: rows start anywhere), so a row of up to 64 entries
+// is one instruction per array and direction; its last one to three entries go singly.  The
+// loads of the next four rows leave before the stores of these four.
+typedef int i4v __attribute__((ext_vector_type(4), aligned(4)));
+typedef float f4v __attribute__((ext_vector_type(4), aligned(4)));
+
 __global__ __launch_bounds__(256) void k_csr_copy(const GatherCsrArgs a) {
   const int m = min(max(*a.kept_count, 0), a.max_rows);
   const int lane = threadIdx.x & 63, grp = lane >> 4, sub = lane & 15;
   const int wave = (blockIdx.x * 256 + threadIdx.x) >> 6, nwaves = (gridDim.x * 256) >> 6;
   const bool with_val = a.val && a.out_val;
+  struct Piece {  // up to four entries of one row, in registers between their load and their store
+    i4v c;
+    f4v v;
+    long long o;  // where they go
+    int n;        // how many there are (0: none)
+  };
+  auto fetch = [&](long long e0, long long o0, int len, int e, Piece &p) __attribute__((always_inline)) {
+    p.n = min(4, len - e);
+    p.o = o0 + e;
+    if (p.n == 4) {
+      p.c = *reinterpret_cast<const i4v *>(a.col + e0 + e);
+      if (with_val) p.v = *reinterpret_cast<const f4v *>(a.val + e0 + e);
+    } else {
+#pragma unroll
+      for (int k = 0; k < 3; ++k) {
+        if (k < p.n) {
+          p.c[k] = a.col[e0 + e + k];
+          if (with_val) p.v[k] = a.val[e0 + e + k];
+        }
+      }
+    }
+  };
+  auto put = [&](const Piece &p) __attribute__((always_inline)) {
+    if (p.n == 4) {
+      *reinterpret_cast<i4v *>(a.out_col + p.o) = p.c;
+      if (with_val) *reinterpret_cast<f4v *>(a.out_val + p.o) = p.v;
+    } else {
+#pragma unroll
+      for (int k = 0; k < 3; ++k) {
+        if (k < p.n) {
+          a.out_col[p.o + k] = p.c[k];
+          if (with_val) a.out_val[p.o + k] = p.v[k];
+        }
+      }
+    }
+  };
   for (int base = wave * kWave; base < m; base += nwaves * kWave) {
     const int r = base + lane;
     long long e0_l = 0, o0_l = 0;
@@ -230,27 +272,22 @@ __global__ __launch_bounds__(256) void k_csr_copy(const GatherCsrArgs a) {
       if (o0_l + len_l > a.out_nnz_cap) len_l = 0;  // a row that does not fit is not copied
     }
     const int cnt = min(kWave, m - base);
-    for (int it = 0; it * 4 < cnt; ++it) {
+    const int iters = (cnt + 3) / 4;
+    Piece next;
+    fetch(__shfl(e0_l, grp, kWave), __shfl(o0_l, grp, kWave), __shfl(len_l, grp, kWave), sub * 4, next);
+    for (int it = 0; it < iters; ++it) {
       const int li = it * 4 + grp;
       const long long e0 = __shfl(e0_l, li, kWave), o0 = __shfl(o0_l, li, kWave);
       const int len = __shfl(len_l, li, kWave);  // rows past the batch's end have length 0
-      for (int e = sub; e < len; e += 64) {
-        int c[4];
-        float v[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int eu = e + 16 * u;
-          c[u] = eu < len ? a.col[e0 + eu] : 0;
-          v[u] = (with_val && eu < len) ? a.val[e0 + eu] : 0.f;
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int eu = e + 16 * u;
-          if (eu < len) {
-            a.out_col[o0 + eu] = c[u];
-            if (with_val) a.out_val[o0 + eu] = v[u];
-          }
-        }
+      const Piece now = next;
+      const int ln = min(li + 4, kWave - 1);
+      const int len_n = it + 1 < iters ? __shfl(len_l, ln, kWave) : 0;
+      fetch(__shfl(e0_l, ln, kWave), __shfl(o0_l, ln, kWave), len_n, sub * 4, next);
+      put(now);
+      for (int e = 64 + sub * 4; e < len; e += 64) {  // rows of more than 64 entries
+        Piece more;
+        fetch(e0, o0, len, e, more);
+        put(more);
       }
     }
   }

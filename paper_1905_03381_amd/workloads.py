@@ -6,6 +6,7 @@
     python -m paper_1905_03381_amd.workloads sk            # hard-threshold shrinking, dense rows
     python -m paper_1905_03381_amd.workloads stale         # two-stream Boss / Assistant pipeline
     python -m paper_1905_03381_amd.workloads rho           # dense fused step at fixed keep rates
+    python -m paper_1905_03381_amd.workloads score         # dense scoring pass at growing pool sizes
 
 Each prints one JSON line: the stages of the workload with their time per call (HIP events
 on the launch stream, median of the repeats), the bytes each stage has to move and the
@@ -313,8 +314,58 @@ def rho(a, torch, api, synth):
             "stages": stages}
 
 
+def score(a, torch, api, synth):
+    """The scoring pass (a1) and the fused score + keep + compact (a7) on the dense configuration
+    at growing pool sizes: these calls depend on no earlier step, so a caller may score many
+    pools at once, and a larger launch streams closer to the HBM peak."""
+    n, d, P, F, Xd, yd, perm = _dense_job(a, torch, api, synth)
+    phi = torch.from_numpy((np.random.default_rng(5).standard_normal(d) / 32).astype(np.float32)).cuda()
+    b = torch.zeros(1, device="cuda")
+    stages = []
+    for pool in (16384, 65536, 262144, 983040):
+        pool = min(pool, n)
+        prob = torch.zeros(pool, device="cuda")
+        keep = torch.zeros(pool, dtype=torch.uint8, device="cuda")
+        pos = torch.zeros(pool, dtype=torch.int32, device="cuda")
+        cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+        ws = api.Workspace(pool, d)
+        calls = max(1, min(n // pool, 16))
+
+        def run_score():
+            for t in range(calls):
+                api.assistant_score(F, perm[t * pool:(t + 1) * pool], pool, phi, b, None, prob)
+
+        def run_fused():
+            for t in range(calls):
+                api.score_shrink(F, perm[t * pool:(t + 1) * pool], pool, phi, b, 0.1, 42, t, None, prob,
+                                 keep, pos, cnt, ws)
+
+        us = _timed(torch, run_score, a.repeats) / calls
+        stages.append(_stage(f"assistant score, pool of {pool}", us, pool * (4 * d + 4 + 4), calls=calls))
+        us = _timed(torch, run_fused, a.repeats) / calls
+        m = int(cnt.item())
+        stages.append(_stage(f"score + keep + compact, pool of {pool}", us,
+                             pool * (4 * d + 4 + 4 + 1) + pool + 4 * m, calls=calls))
+        # the whole step with pools of this size (one aa_train_epoch call over calls * pool rows)
+        w, ph, bb = (torch.zeros(d, device="cuda"), torch.zeros(d, device="cuda"),
+                     torch.zeros(1, device="cuda"))
+        T = torch.zeros(1, device="cuda")
+        tu = torch.zeros(1, dtype=torch.int32, device="cuda")
+        hist = torch.zeros(calls, dtype=torch.int32, device="cuda")
+        cfg = api.step_config(0.1, 1e-4, 256.0, 0.1, 0.0, 42, 0, T)
+        us = _timed(torch, lambda: api.train_epoch(F, yd, perm, calls * pool, pool, w, ph, bb, cfg, tu,
+                                                   hist, ws),
+                    a.repeats, lambda: (w.zero_(), ph.zero_(), bb.zero_(), tu.zero_())) / calls
+        rate = float(hist.sum().item()) / (calls * pool)
+        stages.append(_stage(f"whole step (aa_train_epoch), pool of {pool}", us,
+                             pool * (4 * d + 9) + 4 * rate * pool, calls=calls,
+                             note=f"keep rate {rate:.2f}, {pool / us:.0f} M candidates/s"))
+    return {"workload": f"dense n={n} d={d}: scoring at pool sizes 16,384 to 983,040 (random rows)",
+            "stages": stages}
+
+
 WORKLOADS = {"rho": rho, "sparse": sparse, "images": images, "translation": translation, "sk": sk,
-             "stale": stale}
+             "stale": stale, "score": score}
 
 
 def main(argv=None):
