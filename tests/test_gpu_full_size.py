@@ -89,6 +89,24 @@ def test_first_pools_and_last_short_pool(ref, workload):
         assert abs(float(host(b)[0]) - b_ref) <= RTOL * (abs(b0) + LR_A) + LR_A / m * int(near.sum())
 
 
+def test_pools_of_262144_rows(ref, workload):
+    """The same whole step with pools sixteen times the configuration's (the launch bench.py
+    times beside its headline figure): two steps, each against the oracle step from the GPU's
+    previous state, then both in one call bit for bit.  A wave walks 128 rows here, the
+    compaction runs in the update kernel's tile blocks (no carried compaction at this size)."""
+    from stepwise import check_epoch
+    X, y, Xd, yd = workload
+    big = 262144
+    perm = synth.epoch_permutation(N, seed=7, epoch=1)
+    Fh = ref.Features.dense(X)
+    F = api.Features.dense(Xd)
+    ws = api.Workspace(big, D)
+    zeros = np.zeros(D, np.float32)
+    counts, _ = check_epoch(ref, Fh, F, y, perm, 2 * big, big, zeros, zeros, 0.0, gamma=GAMMA, seed=SEED,
+                            step0=5, lam=LAM, lr0=LR0, lr_a=LR_A, T=0.0, ws=ws)
+    assert all(0.3 * big < m < 0.8 * big for m in counts)
+
+
 def test_dense_slice_five_epochs_every_step(ref):
     """A 65,536-row slice of the dense configuration (d = 1024, pools of 16,384) trained for five
     epochs at the bench's step size through aa_train_epoch: every one of the 20 steps is
