@@ -210,6 +210,23 @@ int32_t aa_boss_assistant_step(const aa_features *F, const float *y, const int32
 int32_t aa_threshold_update(const float *loss, const int32_t *m_dev, int32_t m_max, float momentum,
                             float *T, int32_t *initialised, void *stream);
 
+/* The per-batch Assistant step of that generator (Sec. 5.2: the label of a kept
+ * instance is "Boss loss above the threshold", here the running median) in one
+ * call: the same results, bit for bit, as aa_threshold_update(loss, m_dev,
+ * m_max, momentum, T, initialised) followed by aa_assistant_update(F, rows,
+ * m_dev, m_max, loss, T, phi, bias, lr_a, l2_a), i.e. the labels are taken
+ * against the threshold AFTER this batch's median went into it.  Dense rows in a
+ * register layout and m_max <= 512 run as one pass and one update launch (every
+ * block of the pass works the new threshold out for itself); anything else
+ * runs the two calls it stands for.  T and initialised are device scalars,
+ * read during the pass and written by the update launch; workspace as for
+ * aa_assistant_update.  Errors: AA_ERR_SHAPE (m_max < 0 or > 16384, momentum
+ * outside [0, 1]), AA_ERR_NULL, AA_ERR_WORKSPACE, AA_ERR_HIP. */
+int32_t aa_threshold_assistant_update(const aa_features *F, const int32_t *rows, const int32_t *m_dev,
+                                      int32_t m_max, const float *loss, float momentum, float *T,
+                                      int32_t *initialised, float *phi, float *bias, float lr_a,
+                                      float l2_a, void *ws, size_t ws_bytes, void *stream);
+
 /* Length-bucketed batching of m kept sentence pairs (translation batch
  * generator): bucket(r) = min(n_buckets - 1, (max(len_s[r], len_t[r]) - 1) / width),
  * n_buckets <= 32.  order[] lists r grouped by bucket, arrival order kept inside

@@ -22,7 +22,8 @@ SYMBOLS = [
     "aa_profile_hooks",
     "aa_assistant_score", "aa_shrink", "aa_score_shrink", "aa_shrink_threshold", "aa_gather",
     "aa_gather_csr", "aa_svm_sgd_step", "aa_assistant_update", "aa_boss_assistant_step",
-    "aa_fused_step", "aa_sk_step", "aa_train_epoch", "aa_threshold_update", "aa_bucket_batches",
+    "aa_fused_step", "aa_sk_step", "aa_train_epoch", "aa_threshold_update",
+    "aa_threshold_assistant_update", "aa_bucket_batches",
     "aa_pipeline_workspace_bytes", "aa_train_epoch_stale", "aa_sk_epoch",
     "aa_static_scratch_bytes", "aa_fused_step_static",
 ]
@@ -81,6 +82,7 @@ def lib():
         "aa_train_epoch": (i32, [FP, vp, vp, i64, i32, vp, vp, vp, CP, vp, vp, vp, vp, vp, sz, vp]),
         "aa_sk_epoch": (i32, [FP, vp, vp, i64, i32, vp, vp, f32, f32, vp, vp, vp, vp, vp, sz, vp]),
         "aa_threshold_update": (i32, [vp, vp, i32, f32, vp, vp, vp]),
+        "aa_threshold_assistant_update": (i32, [FP, vp, vp, i32, vp, f32, vp, vp, vp, vp, f32, f32, vp, sz, vp]),
         "aa_pipeline_workspace_bytes": (sz, [i32, i32, i32]),
         "aa_train_epoch_stale": (i32, [FP, vp, vp, i64, i32, i32, vp, vp, vp, CP, vp, vp, vp, vp, sz, vp, vp]),
         "aa_bucket_batches": (i32, [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]),
@@ -292,6 +294,14 @@ def train_epoch_stale(F, y, perm, n_perm, P, staleness, w, phi, bias, cfg, t_upd
 def threshold_update(loss, m_dev, m_max, momentum, T, initialised):
     _check(lib().aa_threshold_update(_ptr(loss), _ptr(m_dev), m_max, momentum, _ptr(T),
                                      _ptr(initialised), _stream()), "aa_threshold_update")
+
+
+def threshold_assistant_update(F, rows, m_dev, m_max, loss, momentum, T, initialised, phi, bias, lr_a,
+                               l2_a, ws):
+    _check(lib().aa_threshold_assistant_update(F.ref(), _ptr(rows), _ptr(m_dev), m_max, _ptr(loss),
+                                               momentum, _ptr(T), _ptr(initialised), _ptr(phi),
+                                               _ptr(bias), lr_a, l2_a, ws.ptr, ws.bytes, _stream()),
+           "aa_threshold_assistant_update")
 
 
 def bucket_batches(len_s, len_t, m_dev, m_max, width, n_buckets, token_budget, order, bucket_start,

@@ -25,6 +25,7 @@ static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 namespace {
 
 constexpr int kCtlUpdateSnapshot = 0;  // control word: update counter before the running step
+constexpr int kCtlThresholdNext = 1;   // control word: the running threshold a pass worked out (a float)
 
 struct Ws {
   char *base;
@@ -163,6 +164,10 @@ struct PassSpec {
   const float *loss_in;
   const int32_t *t_upd;
   CompactArgs prev;  // compaction of the previous pool carried by this pass (fast dense pool pass only)
+  // kAssist alone on the fast dense path: take the threshold from the batch's own losses
+  // (running median with this momentum; *T and *med_init are rewritten by the update kernel)
+  int32_t *med_init;
+  float med_momentum;
 };
 
 bool use_fast(const PassSpec &s) {
@@ -212,6 +217,9 @@ hipError_t run_pass(const PassSpec &s, const Ws &ws, int32_t *nblk_out, hipStrea
     a.t_upd = s.t_upd;
     a.t_snap = ws.ctl + kCtlUpdateSnapshot;
     a.prev = s.prev;
+    a.med_init = s.med_init;
+    a.med_momentum = s.med_momentum;
+    a.T_next = reinterpret_cast<float *>(ws.ctl + kCtlThresholdNext);
 #ifdef AA_PHASE_TRACE
     a.trace = g_phase_trace;
 #endif
@@ -323,6 +331,11 @@ hipError_t run_update(const PassSpec &s, const UpdateSpec &u, const Ws &ws, int3
     f.phi_copy = u.phi_copy;
     f.bias_copy = u.bias_copy;
     f.t_snap = ws.ctl + kCtlUpdateSnapshot;
+    if (s.med_init) {
+      f.T_next = reinterpret_cast<const float *>(ws.ctl + kCtlThresholdNext);
+      f.T_out = const_cast<float *>(s.T);
+      f.T_init = s.med_init;
+    }
     f.flags = u.flags;
     f.P = u.P;
     f.idx = u.idx;
@@ -800,6 +813,43 @@ int32_t aa_assistant_update(const aa_features *F, const int32_t *rows, const int
   s.bias = bias;
   s.T = T;
   s.loss_in = loss;
+  Ws ws = carve(ws_ptr, grad_bytes_for(s), 0);
+  if (int32_t rc = check_ws(ws_ptr, ws_bytes, ws.total)) return rc;
+  int32_t nblk = 0;
+  hipStream_t st = as_stream(stream);
+  if (run_pass(s, ws, &nblk, st) != hipSuccess) return AA_ERR_HIP;
+  UpdateSpec u{};
+  u.lr_a = lr_a;
+  u.l2_a = l2_a;
+  return hip_status(run_update(s, u, ws, nblk, st));
+}
+
+int32_t aa_threshold_assistant_update(const aa_features *F, const int32_t *rows, const int32_t *m_dev,
+                                      int32_t m_max, const float *loss, float momentum, float *T,
+                                      int32_t *initialised, float *phi, float *bias, float lr_a,
+                                      float l2_a, void *ws_ptr, size_t ws_bytes, void *stream) {
+  if (m_max < 0 || m_max > kMedianMax) return AA_ERR_SHAPE;
+  if (!(momentum >= 0.f && momentum <= 1.f)) return AA_ERR_SHAPE;
+  if (m_max == 0) return AA_OK;
+  if (int32_t rc = check_features(F)) return rc;
+  if (!loss || !T || !initialised || !phi || !m_dev) return AA_ERR_NULL;
+  PassSpec s{};
+  s.F = F;
+  s.mode = kAssist;
+  s.rows = rows;
+  s.count_max = m_max;
+  s.m_dev = m_dev;
+  s.phi = phi;
+  s.bias = bias;
+  s.T = T;
+  s.loss_in = loss;
+  if (!use_fast(s) || m_max > kRankSelectMax) {  // no room in that pass: the two calls it stands for
+    if (int32_t rc = aa_threshold_update(loss, m_dev, m_max, momentum, T, initialised, stream)) return rc;
+    return aa_assistant_update(F, rows, m_dev, m_max, loss, T, phi, bias, lr_a, l2_a, ws_ptr, ws_bytes,
+                               stream);
+  }
+  s.med_init = initialised;
+  s.med_momentum = momentum;
   Ws ws = carve(ws_ptr, grad_bytes_for(s), 0);
   if (int32_t rc = check_ws(ws_ptr, ws_bytes, ws.total)) return rc;
   int32_t nblk = 0;

@@ -14,10 +14,6 @@ namespace aa {
 
 namespace {
 
-// Batches up to this size find the two middle values by rank counting (every thread ranks one
-// loss against all others read as LDS broadcasts: two barriers); larger ones are sorted.
-constexpr int kRankSelectMax = 512;
-
 __global__ __launch_bounds__(1024) void k_threshold_update(const ThresholdArgs a) {
   __shared__ __attribute__((aligned(16))) float s[kMedianMax];
   __shared__ float s_mid[2];
@@ -94,24 +90,8 @@ __global__ __launch_bounds__(1024) void k_threshold_update(const ThresholdArgs a
     hi_mid = s[m / 2];
   }
   if (threadIdx.x == 0) {
-    // every product and sum below is rounded to fp32 on its own: no fused multiply-add
-#pragma clang fp contract(off)
-    float med;
-    if (m & 1) {
-      med = hi_mid;
-    } else {
-      const float sum = lo_mid + hi_mid;
-      med = sum * 0.5f;
-    }
-    if (init_old == 0) {
-      *a.T = med;
-      *a.initialised = 1;
-    } else {
-      const float keep_part = a.momentum * T_old;
-      const float one_minus = 1.0f - a.momentum;
-      const float new_part = one_minus * med;
-      *a.T = keep_part + new_part;
-    }
+    *a.T = running_threshold(lo_mid, hi_mid, m, init_old, T_old, a.momentum);
+    if (init_old == 0) *a.initialised = 1;
   }
 }
 

@@ -10,6 +10,7 @@
 // products are folded with DPP row operations and lane reads (no LDS traffic);
 // the gradient sums of the kept rows accumulate per lane in registers and are
 // combined per block in LDS in a fixed order.
+#include "aa_batching.hpp"
 #include "aa_compact.hpp"
 #include "aa_dense.hpp"
 
@@ -142,6 +143,8 @@ __global__ __launch_bounds__(NW * 64)
   __shared__ f4 s_w[SVM ? ROW4 : 1];
   __shared__ f4 s_phi[NEED_PHI ? ROW4 : 1];
   __shared__ f4 s_red[GRAD ? NW * NVEC * ROW4 : 1];  // one slot per wave and vector
+  constexpr bool MEDIAN = ASSIST && !SVM && !POOL;   // may take its threshold from the batch itself
+  __shared__ __attribute__((aligned(16))) float s_med[MEDIAN ? kRankSelectMax + 2 : 1];
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int grp = lane / LPR, sub = lane % LPR;
@@ -172,7 +175,8 @@ __global__ __launch_bounds__(NW * 64)
     st_p[q] = (NEED_PHI && c < a.d4) ? reinterpret_cast<const f4 *>(a.phi)[c] : zero4;
   }
   const float b = (NEED_PHI && a.bias) ? *a.bias : 0.f;
-  const float T = (ASSIST || HARD) ? *a.T : 0.f;
+  float T = (ASSIST || HARD) ? *a.T : 0.f;
+  const int med_init_old = (MEDIAN && a.med_init) ? *a.med_init : 0;
 
   f4 x[RIF][VPL];
   // Every load of the next RIF rows, before any is used.  When the row fills the lane layout
@@ -247,6 +251,14 @@ __global__ __launch_bounds__(NW * 64)
     if (lane == 0) s_carry[wave] = carry_cnt;
   }
   __syncthreads();
+  if (MEDIAN && a.med_init && total > 0) {  // (the same in every thread of the grid)
+    float lo_mid, hi_mid;
+    if (block_middle_values(a.loss_in, total, s_med, &lo_mid, &hi_mid))
+      T = running_threshold(lo_mid, hi_mid, total, med_init_old, T, a.med_momentum);
+    else
+      T = __builtin_nanf("");  // a NaN loss has no rank: the threshold becomes NaN, visibly
+    if (blockIdx.x == 0 && threadIdx.x == 0) *a.T_next = T;
+  }
   if (POOL && GRAD && carry && wave == NW - 1) {
     int before = 0;
 #pragma unroll
@@ -725,6 +737,7 @@ __global__ __launch_bounds__(256) void k_finalize(const FinalizeArgs a) {
   const int m_given = *(a.m_dev ? a.m_dev : ints);
   int t_old = *(a.t_upd ? a.t_snap : ints);
   float b_new = *(bias_block ? a.bias : a.blk_gb);       // the bias before this update
+  const float t_next = *(a.T_next ? a.T_next : a.blk_gb);
   float old[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) old[i] = model[min(k0 + i, a.d - 1)];
@@ -807,6 +820,10 @@ __global__ __launch_bounds__(256) void k_finalize(const FinalizeArgs a) {
   }
   if (a.bias_copy && bias_thread) *a.bias_copy = b_new;
   if (blockIdx.x == 0 && tid == 0 && a.kept_hist) *a.kept_hist = m;
+  if (blockIdx.x == 0 && tid == 0 && a.T_next && m > 0) {
+    *a.T_out = t_next;
+    *a.T_init = 1;
+  }
   if (blockIdx.x == 0 && tid == 0 && a.t_upd) *a.t_upd = t_new;
 }
 

@@ -38,6 +38,14 @@ struct PassArgs {
   float *blk_gb;          // [nblk] bias-gradient partial (kAssist)
   const int32_t *t_upd;   // optional update counter; block 0 snapshots it into *t_snap
   int32_t *t_snap;
+  // kAssist alone, at most kRankSelectMax rows: with med_init the labels are taken against
+  // the running threshold AFTER this batch (first batch: the median of loss_in; later:
+  // momentum * *T + (1 - momentum) * median) instead of *T.  Every block works it out for
+  // itself from *T and *med_init, which stay untouched during the pass; block 0 leaves the value
+  // in *T_next, and the update kernel stores it to *T and sets the flag.
+  const int32_t *med_init;
+  float med_momentum;
+  float *T_next;
   // Compaction of the pool before this one, carried by a pool pass with gradient sums
   // (prev.flags == NULL: none): block b compacts positions [64 b, 64 b + 64) of that pool
   // while its own rows are in flight.  Needs ceil(prev.P / 64) <= blocks of this launch and
@@ -69,6 +77,11 @@ struct FinalizeArgs {
   int32_t *t_upd;          // optional device update counter driving lr/sqrt(t)
   const int32_t *t_snap;   // its value before this step (written by the pass kernel)
   int32_t *kept_hist;      // optional: receives m
+  // optional: the threshold a pass has worked out (see PassArgs::med_init) becomes the running
+  // threshold, and its flag is set, when the batch is not empty
+  const float *T_next;
+  float *T_out;
+  int32_t *T_init;
   // optional compaction blocks (pool mode), one per tile of flags
   const uint8_t *flags;
   int32_t P;

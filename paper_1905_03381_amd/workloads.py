@@ -131,20 +131,32 @@ def images(a, torch, api, synth):
             api.threshold_update(losses[i], sizes[i], B, 0.9, T, init)
             api.assistant_update(F, ids[i * B:], sizes[i], B, losses[i], T, phi, b, 0.05, 0.0, ws)
 
+    def updates_one_call():   # the same two steps per batch in one call: two launches, not three
+        for i in range(nb):
+            api.threshold_assistant_update(F, ids[i * B:], sizes[i], B, losses[i], 0.9, T, init, phi, b,
+                                           0.05, 0.0, ws)
+
     reset = lambda: (phi.copy_(phi0), b.zero_(), init.zero_())
     us_upd = _timed(torch, updates, a.repeats, reset)
-    # the same sequence of launches replayed as one hipGraph
-    reset()
-    side = torch.cuda.Stream()
-    side.wait_stream(torch.cuda.current_stream())
-    with torch.cuda.stream(side):
-        updates()
-    torch.cuda.current_stream().wait_stream(side)
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph):
-        updates()
-    us_upd_graph = _timed(torch, graph.replay, a.repeats, reset)
-    total = us_score + us_gather + us_upd_graph
+
+    def as_graph(fn):   # the same sequence of launches replayed as one hipGraph
+        reset()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            fn()
+        torch.cuda.current_stream().wait_stream(side)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            fn()
+        return _timed(torch, graph.replay, a.repeats, reset)
+
+    us_upd_graph = as_graph(updates)
+    phi_two = phi.clone()
+    us_one = _timed(torch, updates_one_call, a.repeats, reset)
+    us_one_graph = as_graph(updates_one_call)
+    assert torch.equal(phi, phi_two), "the one-call form must reproduce the two calls bit for bit"
+    total = us_score + us_gather + us_one_graph
     return {"workload": f"image batch generator P={P} d={d} image {row_bytes} B, batches of {B}",
             "kept": m, "images_per_s": m / total * 1e6, "candidates_per_s": P / total * 1e6,
             "stages": [_stage("score + keep + compact", us_score, P * (4 * d + 4 + 1 + 4) + 4 * m),
@@ -152,7 +164,12 @@ def images(a, torch, api, synth):
                        _stage("running median + Assistant update, per batch", us_upd / nb,
                               B * (4 * d + 4 + 4), calls=nb, note="eager launches"),
                        _stage("the same, all batches replayed as one hipGraph", us_upd_graph / nb,
-                              B * (4 * d + 4 + 4), calls=nb, note="launch-latency bound")]}
+                              B * (4 * d + 4 + 4), calls=nb, note="launch-latency bound"),
+                       _stage("the same as one call per batch (aa_threshold_assistant_update)",
+                              us_one / nb, B * (4 * d + 4 + 4), calls=nb, note="eager launches"),
+                       _stage("the one-call form, all batches replayed as one hipGraph",
+                              us_one_graph / nb, B * (4 * d + 4 + 4), calls=nb,
+                              note="two dependent launches per batch")]}
 
 
 def translation(a, torch, api, synth):

@@ -186,6 +186,8 @@ def test_image_batch_generator_full_shape(ref):
     T_r, init_r = 0.0, False
     T = scalar_dev(0.0)
     init = torch.zeros(1, dtype=torch.int32, device="cuda")
+    # (a second copy of the state goes through the one-call form of the same two steps)
+    phi2, b2, T2, init2 = dev(phi0), scalar_dev(0.0), scalar_dev(0.0), torch.zeros_like(init)
     n_batches = (m + B - 1) // B
     for bt in range(n_batches):
         size = min(B, m - bt * B)
@@ -200,10 +202,75 @@ def test_image_batch_generator_full_shape(ref):
         api.threshold_update(loss_d, size_d, B, 0.9, T, init)
         api.assistant_update(F, ids[bt * B:], size_d, B, loss_d, T, phi, b, lr_a, 0.0, ws)
         assert host(T)[0] == np.float32(T_r), f"threshold after batch {bt}"
+        api.threshold_assistant_update(F, ids[bt * B:], size_d, B, loss_d, 0.9, T2, init2, phi2, b2,
+                                       lr_a, 0.0, ws)
+        assert torch.equal(T2, T) and torch.equal(init2, init), f"one-call threshold, batch {bt}"
+        assert torch.equal(phi2, phi) and torch.equal(b2, b), f"one-call update, batch {bt}"
         scale = np.abs(phi_prev.astype(np.float64)) + lr_a / size * np.abs(
             feats[rows].astype(np.float64)).sum(axis=0)
         assert_close_scaled(host(phi), phi_r, scale, f"phi after batch {bt}")
         assert abs(float(host(b)[0]) - b_r) <= 1e-5 * (abs(b_prev) + lr_a), f"bias after batch {bt}"
+
+
+@pytest.mark.parametrize("d,ld", [(512, None), (128, None), (36, None), (200, 256), (1024, None), (130, None)])
+@pytest.mark.parametrize("m,m_max", [(1, 1), (2, 7), (255, 256), (256, 256), (511, 512), (512, 512), (0, 64),
+                                     (600, 700)])
+def test_threshold_assistant_update_equals_the_two_calls(d, ld, m, m_max):
+    """aa_threshold_assistant_update against aa_threshold_update + aa_assistant_update on the
+    same inputs, bit for bit, over three batches in a row (first batch sets the threshold, the
+    others move it): every register layout, the general kernel (d = 130) and a batch too large
+    for the in-pass median (both fall back to the two calls), ties among the losses, an empty
+    batch."""
+    r = rng(1000 * d + m)
+    n = 900
+    X = r.standard_normal((n, ld or d)).astype(np.float32)
+    F = api.Features.dense(dev(X), d=d)   # (ld > d: padded rows)
+    ws = api.Workspace(max(m_max, 64), d)
+    phi0 = (r.standard_normal(d) / 8).astype(np.float32)
+    state = []
+    for _ in range(2):
+        state.append([dev(phi0), scalar_dev(0.25), scalar_dev(0.0), torch.zeros(1, dtype=torch.int32, device="cuda")])
+    for batch in range(3):
+        rows = dev(r.integers(0, n, size=max(m_max, 1)).astype(np.int32))
+        loss = r.gamma(2.0, 0.5, size=max(m_max, 1)).astype(np.float32)
+        loss[::3] = loss[0]                                  # ties
+        loss_d, m_d = dev(loss), scalar_dev(m, torch.int32)
+        phi, b, T, init = state[0]
+        api.threshold_update(loss_d, m_d, m_max, 0.9, T, init)
+        api.assistant_update(F, rows, m_d, m_max, loss_d, T, phi, b, 0.3, 1e-3, ws)
+        phi, b, T, init = state[1]
+        api.threshold_assistant_update(F, rows, m_d, m_max, loss_d, 0.9, T, init, phi, b, 0.3, 1e-3, ws)
+        for name, x0, x1 in zip(("phi", "bias", "T", "initialised"), state[0], state[1]):
+            assert torch.equal(x0, x1), f"{name} differs after batch {batch}"
+    if m > 0:
+        assert int(host(state[1][3])[0]) == 1 and not np.array_equal(host(state[1][0]), phi0)
+    else:
+        assert int(host(state[1][3])[0]) == 0 and np.array_equal(host(state[1][0]), phi0)
+
+
+def test_threshold_assistant_update_nan_loss():
+    """A NaN among the losses: the threshold becomes NaN in the one-call form as in the two calls
+    (no label is 1 afterwards), and the Assistant's state equals theirs."""
+    r = rng(77)
+    n, d, m = 400, 512, 200
+    F = api.Features.dense(dev(r.standard_normal((n, d)).astype(np.float32)))
+    ws = api.Workspace(256, d)
+    rows = dev(r.integers(0, n, size=m).astype(np.int32))
+    loss = r.gamma(2.0, 0.5, size=m).astype(np.float32)
+    loss[17] = np.nan
+    phi0 = (r.standard_normal(d) / 8).astype(np.float32)
+    out = []
+    for one_call in (False, True):
+        phi, b, T, init = dev(phi0), scalar_dev(0.0), scalar_dev(0.7), torch.ones(1, dtype=torch.int32, device="cuda")
+        m_d = scalar_dev(m, torch.int32)
+        if one_call:
+            api.threshold_assistant_update(F, rows, m_d, m, dev(loss), 0.9, T, init, phi, b, 0.3, 0.0, ws)
+        else:
+            api.threshold_update(dev(loss), m_d, m, 0.9, T, init)
+            api.assistant_update(F, rows, m_d, m, dev(loss), T, phi, b, 0.3, 0.0, ws)
+        out.append((host(phi).copy(), host(b).copy(), host(T).copy()))
+    assert np.isnan(out[0][2][0]) and np.isnan(out[1][2][0])
+    assert np.array_equal(out[0][0], out[1][0]) and np.array_equal(out[0][1], out[1][1])
 
 
 def test_translation_batch_generator_full_shape(ref):
