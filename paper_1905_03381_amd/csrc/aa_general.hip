@@ -498,7 +498,6 @@ constexpr int kScoreTableMaxCols = 2 * kScoreTableCols;
 template <bool VAL>
 __global__ __launch_bounds__(kScoreTableThreads) void k_score_table(const GenArgs a) {
   constexpr int GL = 16, G = kWave / GL, kUnroll = 8, kChunk = GL * kUnroll;
-  constexpr int kIters = kWave / G;  // row groups per round
   __shared__ float s_phi[kScoreTableCols];
   const int D = min(kScoreTableCols, a.d);
   for (int k = threadIdx.x; k < D; k += kScoreTableThreads) s_phi[k] = a.phi[k];
@@ -532,17 +531,19 @@ __global__ __launch_bounds__(kScoreTableThreads) void k_score_table(const GenArg
     float x[kUnroll];
     float far[kUnroll];
   };
-  // entries [e, e + kChunk) of the row that starts at entry e0 and has len entries
-  auto request = [&](int e0, int len, int e, Slot &t) __attribute__((always_inline)) {
+  // One half of a slot: the kHalf turns from turn u0 on hold entries [e, e + kHalfChunk) of the
+  // row that starts at entry e0 and has len entries.
+  constexpr int kHalf = kUnroll / 2, kHalfChunk = GL * kHalf;
+  auto request_half = [&](int e0, int len, int e, int u0, Slot &t) __attribute__((always_inline)) {
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
+    for (int u = 0; u < kHalf; ++u) {
       const int eu = e + sub + u * GL;
       const int off = eu < len ? (e0 + eu) * 4 : kNone;
-      t.c[u] = __builtin_amdgcn_raw_buffer_load_b32(r_col, off, 0, 0);
+      t.c[u0 + u] = __builtin_amdgcn_raw_buffer_load_b32(r_col, off, 0, 0);
       if (VAL)
-        t.x[u] = __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(r_val, off, 0, 0));
+        t.x[u0 + u] = __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(r_val, off, 0, 0));
       else
-        t.x[u] = eu < len ? 1.f : 0.f;
+        t.x[u0 + u] = eu < len ? 1.f : 0.f;
     }
   };
   auto gather = [&](Slot &t) __attribute__((always_inline)) {  // columns past the table
@@ -551,13 +552,13 @@ __global__ __launch_bounds__(kScoreTableThreads) void k_score_table(const GenArg
       t.far[u] = __int_as_float(
           __builtin_amdgcn_raw_buffer_load_b32(r_phi, t.c[u] >= D ? t.c[u] * 4 : kNone, 0, 0));
   };
-  auto dot = [&](const Slot &t, float dp) __attribute__((always_inline)) {
-    float near[kUnroll];
+  auto dot_half = [&](const Slot &t, int u0, float dp) __attribute__((always_inline)) {
+    float near[kHalf];
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) near[u] = s_phi[min(t.c[u], D - 1)];
+    for (int u = 0; u < kHalf; ++u) near[u] = s_phi[min(t.c[u0 + u], D - 1)];
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u)
-      dp = __fmaf_rn(t.c[u] >= D ? t.far[u] : near[u], t.x[u], dp);
+    for (int u = 0; u < kHalf; ++u)
+      dp = __fmaf_rn(t.c[u0 + u] >= D ? t.far[u0 + u] : near[u], t.x[u0 + u], dp);
     return dp;
   };
   auto emit = [&](int j, float dp, float u) __attribute__((always_inline)) {
@@ -588,45 +589,83 @@ __global__ __launch_bounds__(kScoreTableThreads) void k_score_table(const GenArg
   int id_after = row_id(lo + 2 * kWave + lane);
   bool any_longer = false;
 
-  constexpr int kAhead = 3;  // row groups in flight; slot (it % kAhead) holds group it of a round
-  static_assert(kIters % kAhead == 1, "the rotation below ends on slot 0");
+  // A step gives every group of 16 lanes two half slots of 64 entries: both chunks of one row of
+  // 65 to 128 entries, or the only chunks of two rows of up to 64.  Per round the wave's 64 rows
+  // are put in that order -- the longer rows, then the shorter ones, each class in pool order --
+  // with one ds_permute per value, so half slot h belongs to sorted row h / 2 (chunk h % 2) while
+  // h < 2 M and to sorted row h - M after that (M = number of longer rows).
+  constexpr int kAhead = 3;  // steps in flight; slot (it % kAhead) holds step it of a round
   Slot t[kAhead];
   for (int base = lo; base < hi; base += kWave) {
     const float u_l = a.do_keep ? keep_uniform(a.key, (uint32_t)(base + lane)) : 2.f;
-    int len_cur = base + lane < hi ? (int)(cur.hi - cur.lo) : 0;
+    const bool valid = base + lane < hi;
+    int len_cur = valid ? (int)(cur.hi - cur.lo) : 0;
     if (cur.hi > kSpan) len_cur = kChunk + 1;  // (out of reach: a row for the walk after the loop)
-    any_longer = any_longer || len_cur > kChunk;
-    auto request_group = [&](int it, Slot &s) __attribute__((always_inline)) {
-      const int li = min(it * G + grp, kWave - 1);
-      const int e0 = __shfl((int)cur.lo, li, kWave);
-      const int len = __shfl(len_cur, li, kWave);
-      request(e0, (it < kIters && len <= kChunk) ? len : 0, 0, s);
+    any_longer = any_longer || (valid && len_cur > kChunk);
+    const bool two = valid && len_cur > kHalfChunk && len_cur <= kChunk;
+    const bool one = valid && len_cur <= kHalfChunk;
+    const unsigned long long m_two = __ballot(two), m_one = __ballot(one);
+    const int M = __popcll(m_two), S = __popcll(m_one), H = 2 * M + S;
+    auto rank_in = [&](unsigned long long mask) __attribute__((always_inline)) {
+      return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                            __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
     };
-    auto finish_group = [&](int it, float dp) __attribute__((always_inline)) {
-      const int li = it * G + grp;
-      const int len = __shfl(len_cur, li, kWave);
-      const float u = __shfl(u_l, li, kWave);
-      dp = gsum<GL>(dp);
-      if (sub == 0 && base + li < hi && len <= kChunk) emit(base + li, dp, u);
+    const int dest = two ? rank_in(m_two) : one ? M + rank_in(m_one) : M + S + rank_in(~(m_two | m_one));
+    const int e0_s = __builtin_amdgcn_ds_permute(dest * 4, (int)cur.lo);
+    const int len_s = __builtin_amdgcn_ds_permute(dest * 4, len_cur);
+    const int src_s = __builtin_amdgcn_ds_permute(dest * 4, lane);
+    const float u_s = __int_as_float(__builtin_amdgcn_ds_permute(dest * 4, __float_as_int(u_l)));
+    const int nsteps = (H + 2 * G - 1) / (2 * G);
+    // half slots (A, B) of this lane's group in step `it`: sorted row and first entry of each
+    auto halves = [&](int it, int *rowA, int *rowB, bool *same) __attribute__((always_inline)) {
+      const int hA = 2 * (it * G + grp), hB = hA + 1;
+      *same = hB < 2 * M;
+      *rowA = hA < 2 * M ? (hA >> 1) : hA - M;
+      *rowB = *same ? *rowA : hB - M;
+      if (hA >= H) *rowA = -1;
+      if (hB >= H) *rowB = -1;
+    };
+    auto request_step = [&](int it, Slot &s) __attribute__((always_inline)) {
+      int rowA, rowB;
+      bool same;
+      halves(it, &rowA, &rowB, &same);
+      const int e0A = __shfl(e0_s, max(rowA, 0), kWave), lenA = __shfl(len_s, max(rowA, 0), kWave);
+      const int e0B = __shfl(e0_s, max(rowB, 0), kWave), lenB = __shfl(len_s, max(rowB, 0), kWave);
+      request_half(e0A, rowA >= 0 ? min(lenA, kHalfChunk) : 0, 0, 0, s);
+      request_half(e0B, rowB >= 0 ? (same ? lenB : min(lenB, kHalfChunk)) : 0, same ? kHalfChunk : 0,
+                   kHalf, s);
+    };
+    auto finish_step = [&](int it, float dpA, float dpB) __attribute__((always_inline)) {
+      int rowA, rowB;
+      bool same;
+      halves(it, &rowA, &rowB, &same);
+      dpA = gsum<GL>(dpA);
+      dpB = gsum<GL>(dpB);
+      const int jA = base + __shfl(src_s, max(rowA, 0), kWave), jB = base + __shfl(src_s, max(rowB, 0), kWave);
+      const float uA = __shfl(u_s, max(rowA, 0), kWave), uB = __shfl(u_s, max(rowB, 0), kWave);
+      if (sub == 0 && rowA >= 0 && !same) emit(jA, dpA, uA);
+      if (sub == 0 && rowB >= 0) emit(jB, dpB, uB);
     };
     // the extents of the next round and the row ids of the one after go out ahead of this
     // round's entries: the only loads of a round that wait for nothing
     const Extent coming = extent(base + 2 * kWave + lane, id_after);
     id_after = row_id(base + 3 * kWave + lane);
 #pragma unroll
-    for (int p = 0; p < kAhead; ++p) request_group(p, t[p]);
+    for (int p = 0; p < kAhead; ++p) request_step(p, t[p]);
     gather(t[0]);
+    // (whole turns of the three slots: the steps past the last one hold nothing and load nothing)
 #pragma unroll 1
-    for (int it0 = 0; it0 + 1 < kIters; it0 += kAhead) {
+    for (int it0 = 0; it0 < nsteps; it0 += kAhead) {
 #pragma unroll
       for (int p = 0; p < kAhead; ++p) {
-        gather(t[(p + 1) % kAhead]);  // group it + 1: its entries were requested two steps ago
-        const float dp = dot(t[p], 0.f);
-        request_group(it0 + p + kAhead, t[p]);
-        finish_group(it0 + p, dp);
+        gather(t[(p + 1) % kAhead]);  // step it + 1: its entries were requested two steps ago
+        const int hB = 2 * ((it0 + p) * G + grp) + 1;
+        const float dpA = dot_half(t[p], 0, 0.f);
+        const float dpB = dot_half(t[p], kHalf, hB < 2 * M ? dpA : 0.f);  // (one row: its sum goes on)
+        request_step(it0 + p + kAhead, t[p]);
+        finish_step(it0 + p, dpA, dpB);
       }
     }
-    finish_group(kIters - 1, dot(t[0], 0.f));
     cur = next;
     next = coming;
   }
