@@ -29,6 +29,12 @@
  *    not checked on the device: an id outside the range reads (or, for column
  *    ids of a gradient pass, writes) outside the caller's buffers.
  *  - P == 0 and *m == 0 are valid and leave the model state untouched.
+ *  - Reproducibility: the same call on the same inputs gives the same bits.  The
+ *    register-resident dense kernels add in a fixed order.  The CSR / general
+ *    kernels add the fp32 terms of a column in doubles and round the total
+ *    once, so the order in which waves arrive does not show -- unless the terms
+ *    of one column span more than about 2^17 in magnitude, where a double sum
+ *    can round and the last fp32 bit may then differ from run to run.
  */
 #ifndef AUTOASSIST_H
 #define AUTOASSIST_H
