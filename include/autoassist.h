@@ -306,7 +306,7 @@ int32_t aa_sk_step(const aa_features *F, const float *y, const int32_t *idx, int
  * entries each; either may be NULL: the batch then lives in ws until the next
  * step replaces it).  With the fast dense layout the compaction of step t is
  * carried by the row pass of step t+1 (every output is complete when the
- * call's work has drained).  Needs the fast dense layout when t_upd is given. */
+ * call's work has drained).  Every layout takes t_upd. */
 int32_t aa_train_epoch(const aa_features *F, const float *y, const int32_t *perm,
                        int64_t n_perm, int32_t P, float *w, float *phi, float *bias,
                        const aa_step_config *cfg, int32_t *t_upd, int32_t *kept_hist,
@@ -318,7 +318,7 @@ int32_t aa_train_epoch(const aa_features *F, const float *y, const int32_t *perm
  * lr_t = lr0 / sqrt(t_upd) kept on the device as in aa_train_epoch (t_upd ==
  * NULL: lr0 throughout), kept counts in kept_hist[t], and the kept ids and
  * losses of step t in kept_ids_hist[t*P ..] / loss_hist[t*P ..] (each may be
- * NULL).  T: device scalar.  Needs the fast dense layout when t_upd is given. */
+ * NULL).  T: device scalar. */
 int32_t aa_sk_epoch(const aa_features *F, const float *y, const int32_t *perm, int64_t n_perm,
                     int32_t P, float *w, const float *T, float lambda, float lr0, int32_t *t_upd,
                     int32_t *kept_hist, int32_t *kept_ids_hist, float *loss_hist, void *ws,
@@ -342,7 +342,7 @@ int32_t aa_sk_epoch(const aa_features *F, const float *y, const int32_t *perm, i
  * kept_hist[steps] (may be NULL): kept count of each tick.  kept_ids_hist
  * [steps][P] (may be NULL): the kept ids of each batch, row s holding
  * kept_hist[s] entries.  ws must hold aa_pipeline_workspace_bytes(P, d,
- * staleness) bytes.  t_upd needs the fast dense layout (AA_ERR_SHAPE). */
+ * staleness) bytes. */
 size_t aa_pipeline_workspace_bytes(int32_t P_max, int32_t d_max, int32_t staleness);
 int32_t aa_train_epoch_stale(const aa_features *F, const float *y, const int32_t *perm,
                              int64_t n_perm, int32_t P, int32_t staleness, float *w, float *phi,

@@ -281,6 +281,8 @@ hipError_t run_pass(const PassSpec &s, const Ws &ws, int32_t *nblk_out, hipStrea
   a.bin_fill = reinterpret_cast<unsigned long long *>(acc + 16);
   a.bins = reinterpret_cast<TailRecord *>(ws.grad + general_bins_offset(s.F->d));
   a.plan = general_bin_plan(s.F->d, a.head, nvec, s.count_max);
+  a.t_upd = s.t_upd;
+  a.t_snap = ws.ctl + kCtlUpdateSnapshot;
   const int32_t nblk = general_pass_blocks(s.count_max, csr, s.mode);
   *nblk_out = nblk;
   const Hook hook;
@@ -360,6 +362,8 @@ hipError_t run_update(const PassSpec &s, const UpdateSpec &u, const Ws &ws, int3
   p.bin_fill = reinterpret_cast<const unsigned long long *>(acc + 16);
   p.bins = reinterpret_cast<const TailRecord *>(ws.grad + general_bins_offset(s.F->d));
   p.plan = general_bin_plan(s.F->d, p.head, p.nvec, s.count_max);
+  p.t_upd = u.t_upd;
+  p.t_snap = ws.ctl + kCtlUpdateSnapshot;
   p.nblk_pass = nblk;
   p.m_dev = pool ? nullptr : s.m_dev;
   p.m_max = s.count_max;
@@ -449,7 +453,6 @@ int32_t fused_step_impl(const aa_features *F, const float *y, const int32_t *idx
   s.prob = prob;
   s.t_upd = t_upd;
   const bool fast = use_fast(s);
-  if (t_upd && !fast) return AA_ERR_SHAPE;  // device-side step-size schedule: fast dense only
   const size_t gbytes = grad_bytes_for(s);
   Ws ws = carve(ws_ptr, gbytes, s.count_max, ep != nullptr);
   if (int32_t rc = check_ws(ws_ptr, ws_bytes, ws.total)) return rc;
@@ -1122,7 +1125,6 @@ int32_t aa_train_epoch_stale(const aa_features *F, const float *y, const int32_t
   boss.bias = bias;
   boss.T = cfg->T;
   boss.t_upd = t_upd;
-  if (t_upd && !use_fast(boss)) return AA_ERR_SHAPE;  // device-side step-size schedule: fast dense only
   const size_t need_common = aa_workspace_bytes(P, F->d);
   Ws ws = carve(ws_ptr, grad_bytes_for(boss), P, true);
   if (ws.total > need_common) return AA_ERR_WORKSPACE;

@@ -65,6 +65,7 @@ __device__ __forceinline__ void add_global(const GenArgs &a, int c, double ta, d
 __device__ __forceinline__ float float_part(double s, int k) {
   const float hi = (float)s;
   if (k == 0) return hi;
+  if (!(fabsf(hi) <= 3.402823466e38f)) return 0.f;  // infinite or NaN: nothing is left to carry
   const double r1 = s - (double)hi;
   const float mid = (float)r1;
   return k == 1 ? mid : (float)(r1 - (double)mid);
@@ -190,6 +191,7 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
   const int grp = lane / GL, sub = lane % GL;
 
+  if (GRAD && a.t_upd && blockIdx.x == 0 && threadIdx.x == 0) *a.t_snap = *a.t_upd;
   int total = a.count_max;
   if (!POOL && a.m_dev) total = min(max(*a.m_dev, 0), a.count_max);
   const int nwaves = gridDim.x * nw, gwave = blockIdx.x * nw + wave;
@@ -721,9 +723,13 @@ struct Fold {
   const ApplyArgs &a;
   int m;
   float inv_m, shrink, scale;
-  __device__ Fold(const ApplyArgs &args, int m_)
-      : a(args), m(m_), inv_m(m_ > 0 ? 1.f / (float)m_ : 0.f),
-        shrink(1.f - args.lr * args.lambda), scale(args.lr * inv_m) {}
+  __device__ Fold(const ApplyArgs &args, int m_) : a(args), m(m_), inv_m(m_ > 0 ? 1.f / (float)m_ : 0.f) {
+    // step size: constant, or lr / sqrt(number of updates made, this one included)
+    float lr = args.lr;
+    if (args.t_upd && m_ > 0) lr = args.lr / sqrtf((float)(*args.t_snap + 1));
+    shrink = 1.f - lr * args.lambda;
+    scale = lr * inv_m;
+  }
   // w_old, ph: the column's current values, loaded by the caller
   __device__ __forceinline__ void loaded(int k, float gw, float gp, float w_old, float ph) const {
     if (m <= 0) {
@@ -923,6 +929,7 @@ __global__ __launch_bounds__(kApplyThreads) void k_apply_general(const ApplyArgs
     const int m = pass_totals(a, cnt, gbs, s_m, s_g, &gb_pass);  // barrier
     const Fold fold(a, m);
     if (hb == 0 && t == 0 && a.kept_hist) *a.kept_hist = m;
+    if (hb == 0 && t == 0 && a.t_upd && m > 0) *a.t_upd = *a.t_snap + 1;
     if (q == 0 && k < a.head) {
       for (int i = 0; i < 16; ++i) {
         gw += s_part[0][i][cl];

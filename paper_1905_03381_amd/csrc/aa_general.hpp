@@ -91,6 +91,10 @@ struct GenArgs {
   TailRecord *bins;
   unsigned long long *bin_fill;
   BinPlan plan;
+  // optional device-side update counter (step size lr / sqrt(t)): block 0 of a gradient pass
+  // copies it to *t_snap, which the update kernel reads (the counter itself changes there)
+  const int32_t *t_upd;
+  int32_t *t_snap;
 };
 
 // Columns whose gradient sums leave a block as plain stores instead of atomics, for a pass
@@ -127,6 +131,8 @@ struct ApplyArgs {
   const unsigned long long *bin_fill;
   BinPlan plan;
   float lambda, lr, lr_a, l2_a;
+  int32_t *t_upd;          // optional update counter: the Boss step size is lr / sqrt(updates so far)
+  const int32_t *t_snap;   // its value before this step (written by the pass kernel)
   int32_t *kept_hist;
   const uint8_t *flags;
   int32_t P;

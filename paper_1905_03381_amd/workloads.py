@@ -60,33 +60,29 @@ def sparse(a, torch, api, synth):
     w, phi, b = (torch.zeros(d, device="cuda"), torch.zeros(d, device="cuda"),
                  torch.zeros(1, device="cuda"))
     T = torch.zeros(1, device="cuda")
-    cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
-    out = [torch.zeros(P, device="cuda"), torch.zeros(P, dtype=torch.uint8, device="cuda"),
-           torch.zeros(P, dtype=torch.int32, device="cuda"),
-           torch.zeros(P, dtype=torch.int32, device="cuda"), torch.zeros(P, device="cuda")]
+    prob = torch.zeros(P, device="cuda")
     steps = n // P
     nnz_pool = float(rowptr[-1]) / n * P
-    kept = []
+    tu = torch.zeros(1, dtype=torch.int32, device="cuda")
+    hist = torch.zeros(steps, dtype=torch.int32, device="cuda")
+    cfg = api.step_config(0.1, 1e-4, 1.0, 0.1, 0.0, 42, 0, T)
 
     def reset():
-        w.zero_(), phi.zero_(), b.zero_()
+        w.zero_(), phi.zero_(), b.zero_(), tu.zero_()
 
-    def epoch():
-        kept.clear()
-        for t in range(steps):
-            cfg = api.step_config(0.1, 1e-4, 1.0 / np.sqrt(t + 1.0), 0.1, 0.0, 42, t, T)
-            api.fused_step(F, yd, perm[t * P:(t + 1) * P], P, w, phi, b, cfg, None, *out, cnt, ws)
+    def epoch():   # one call: every step's batch in the workspace, step size 1 / sqrt(t) on the device
+        api.train_epoch(F, yd, perm, steps * P, P, w, phi, b, cfg, tu, hist, ws)
 
     def score():
         for t in range(steps):
-            api.assistant_score(F, perm[t * P:(t + 1) * P], P, phi, b, None, out[0])
+            api.assistant_score(F, perm[t * P:(t + 1) * P], P, phi, b, None, prob)
 
     us_step = _timed(torch, epoch, a.repeats, reset) / steps
     us_score = _timed(torch, score, a.repeats) / steps
     row_bytes = nnz_pool * 8 + P * (16 + 4)          # col + val per entry, row pointers, pool id
     return {"workload": f"sparse linear SVM n={n} d=2^20 nnz/row~{rowptr[-1] / n:.0f}, pool {P}, "
                         f"{steps} pools per epoch",
-            "candidates_per_s": P / us_step * 1e6,
+            "candidates_per_s": P / us_step * 1e6, "keep_rate": float(hist.sum().item()) / (steps * P),
             "stages": [_stage("fused step (score, keep, compact, SVM step, Assistant update)", us_step,
                               row_bytes, note="bound by the latency of the cold-column gathers, not by HBM"),
                        _stage("assistant score only", us_score, row_bytes)]}

@@ -3,7 +3,7 @@
 A chain of steps cannot be compared with an oracle chain at 1e-5 (rounding differences of one
 step are the inputs of the next), so the chain is re-synchronised every step: the GPU runs the
 epoch one step per call, and after each step the oracle computes the same step FROM THE GPU'S
-PREVIOUS STATE.  Every stage is then held to the single-step tolerances of gpu_util:
+PREVIOUS STATE.  Dense or CSR rows.  Every stage is then held to the single-step tolerances of gpu_util:
 
   * keep decisions: equal to the oracle's wherever the draw is farther than 1e-6 from its
     probability (the GPU's mask is rebuilt from its kept ids);
@@ -22,7 +22,8 @@ import torch
 
 from paper_1905_03381_amd import api
 
-from gpu_util import DRAW_BAND, RTOL, abs_dot_scale, assert_close_scaled, dev, host, row_dots, scalar_dev
+from gpu_util import (DRAW_BAND, RTOL, abs_dot_scale, assert_close_scaled, col_abs_sum, dev, host, row_dots,
+                      scalar_dev)
 
 
 def pools_of(n_perm, P):
@@ -90,20 +91,20 @@ def run_stepwise(ref, Fh, F, y, perm, n_perm, P, w0, phi0, b0, gamma, seed, step
         w_ref, loss_ref = ref.svm_sgd_step(Fh, y, ids_g, m, w_prev, lam, lr)
         S = abs_dot_scale(Fh, ids_g, w_prev)
         assert_close_scaled(loss_g, loss_ref, S, f"step {t}: loss")
-        Xk = np.abs(Fh.x[ids_g, :Fh.d].astype(np.float64))
         marg = y[ids_g].astype(np.float64) * row_dots(Fh, ids_g, w_prev)
         active = marg < 1
         near_kink = np.abs(1.0 - marg) <= RTOL * (S + 1.0)
-        w_scale = abs(1 - lr * lam) * np.abs(w_prev.astype(np.float64)) + float(lr) / m * Xk[active].sum(axis=0)
-        w_atol = float(lr) / m * Xk[near_kink].sum(axis=0) if near_kink.any() else 0.0
+        w_scale = (abs(1 - lr * lam) * np.abs(w_prev.astype(np.float64))
+                   + float(lr) / m * col_abs_sum(Fh, ids_g[active]))
+        w_atol = float(lr) / m * col_abs_sum(Fh, ids_g[near_kink]) if near_kink.any() else 0.0
         assert_close_scaled(host(w), w_ref, w_scale, f"step {t}: w", atol=w_atol)
         if hard:
             continue
         # ---- Assistant update labelled by those losses
         phi_ref, b_ref = ref.assistant_update(Fh, ids_g, m, loss_ref, T, phi_prev, b_prev, lr_a)
         near_T = np.abs(loss_ref.astype(np.float64) - T) <= RTOL * (S + 1.0)
-        phi_scale = np.abs(phi_prev.astype(np.float64)) + lr_a / m * Xk.sum(axis=0)
-        phi_atol = lr_a / m * Xk[near_T].sum(axis=0) if near_T.any() else 0.0
+        phi_scale = np.abs(phi_prev.astype(np.float64)) + lr_a / m * col_abs_sum(Fh, ids_g)
+        phi_atol = lr_a / m * col_abs_sum(Fh, ids_g[near_T]) if near_T.any() else 0.0
         assert_close_scaled(host(phi), phi_ref, phi_scale, f"step {t}: phi", atol=phi_atol)
         b_bound = RTOL * (abs(b_prev) + lr_a) + lr_a / m * int(near_T.sum())
         assert abs(float(host(b)[0]) - b_ref) <= b_bound, f"step {t}: bias"

@@ -361,52 +361,32 @@ def test_sparse_config_full_size_first_pools(ref):
 
 
 def test_train_epoch_on_csr_rows(ref, ws, sparse):
-    """aa_train_epoch over CSR rows (general kernels, constant step size): kept counts and the
-    batch of every step against the oracle loop, the model within tolerance."""
+    """aa_train_epoch over CSR rows (general kernels) with the step-size schedule on the device:
+    every step against the oracle step from the GPU's previous state at the single-step
+    tolerances, then the epoch in one call bit for bit (tests/stepwise.py) -- and again, twice:
+    the gradient sums do not depend on the order in which waves and blocks arrive."""
+    from stepwise import check_epoch, run_whole
     rowptr, col, val, y, d = sparse
     n, P = 9000, 2048
     perm = rng(21).permutation(rowptr.size - 1)[:n].astype(np.int32)
     Fh = ref.Features.csr(rowptr, col, val, d)
     F = csr_features(rowptr, col, val, d)
-    gamma, lam, lr, lr_a, T, step0 = 0.1, 1e-4, 0.5, 0.3, 0.0, 3
-    steps = (n + P - 1) // P
-    for seed in range(42, 62):
-        w_r, phi_r, b_r = np.zeros(d, np.float32), np.zeros(d, np.float32), 0.0
-        ms, batches, ok = [], [], True
-        for t in range(steps):
-            idx = perm[t * P:(t + 1) * P]
-            out = ref.step(Fh, y, idx, idx.size, w_r, phi_r, b_r, gamma, seed, step0 + t, lam, lr, T, lr_a)
-            ok = ok and clear_draws(ref, out["prob"], gamma, seed, step0 + t).all()
-            w_r, phi_r, b_r = out["w"], out["phi"], out["bias"]
-            ms.append(out["m"])
-            batches.append(out["kept_ids"])
-        if ok:
-            break
-    assert ok
-    w, phi, b = dev(np.zeros(d, np.float32)), dev(np.zeros(d, np.float32)), scalar_dev(0.0)
-    Tt = scalar_dev(T)     # stays alive: the configuration holds its address
-    cfg = api.step_config(gamma, lam, lr, lr_a, 0.0, seed, step0, Tt)
-    hist = torch.full((steps,), -1, dtype=torch.int32, device="cuda")
-    ids = torch.full((steps, P), -1, dtype=torch.int32, device="cuda")
-    api.train_epoch(F, dev(y), dev(perm), n, P, w, phi, b, cfg, None, hist, ws, ids, None)
-    assert host(hist).tolist() == ms
-    for t, want in enumerate(batches):
-        assert np.array_equal(host(ids)[t, :ms[t]], want), f"batch {t}"
-    assert np.allclose(host(w), w_r, rtol=5e-4, atol=5e-6)
-    assert np.allclose(host(phi), phi_r, rtol=5e-4, atol=5e-6)
-    assert abs(float(host(b)[0]) - b_r) < 1e-5
-    # the gradient sums do not depend on the order in which waves and blocks arrive: the same
-    # epoch again gives the same bits
-    first = (host(w).copy(), host(phi).copy(), host(b).copy())
-    for _ in range(3):
-        w, phi, b = dev(np.zeros(d, np.float32)), dev(np.zeros(d, np.float32)), scalar_dev(0.0)
-        api.train_epoch(F, dev(y), dev(perm), n, P, w, phi, b, cfg, None, hist, ws, ids, None)
-        assert np.array_equal(host(w), first[0]) and np.array_equal(host(phi), first[1])
-        assert np.array_equal(host(b), first[2])
-    # the device-side step-size schedule needs the register-resident dense kernels
-    with pytest.raises(api.AAError):
-        api.train_epoch(F, dev(y), dev(perm), n, P, w, phi, b, cfg,
-                        torch.zeros(1, dtype=torch.int32, device="cuda"), hist, ws)
+    zeros = np.zeros(d, np.float32)
+    args = dict(gamma=0.1, seed=42, step0=3, lam=1e-4, lr0=2.0, lr_a=0.3, T=0.0, ws=ws)
+    counts, state = check_epoch(ref, Fh, F, y, perm, n, P, zeros, zeros, 0.0, **args)
+    assert len(counts) == 5 and all(0 < m < P for m in counts) and state[3] == 5
+    for _ in range(2):
+        hist, _, _, again = run_whole(F, y, perm, n, P, zeros, zeros, 0.0, **args)
+        assert hist == counts and again[3] == state[3]
+        assert np.array_equal(again[0], state[0]) and np.array_equal(again[1], state[1])
+        assert np.array_equal(again[2], state[2])
+    # a constant step size (no counter) is still there
+    w, phi, b = dev(zeros), dev(zeros), scalar_dev(0.0)
+    Tt = scalar_dev(0.0)
+    cfg = api.step_config(0.1, 1e-4, 0.5, 0.3, 0.0, 42, 3, Tt)
+    hist = torch.full((5,), -1, dtype=torch.int32, device="cuda")
+    api.train_epoch(F, dev(y), dev(perm), n, P, w, phi, b, cfg, None, hist, ws)
+    assert host(hist).tolist()[0] == counts[0] and np.abs(host(w)).max() > 0
 
 
 def _uniform_csr(r, n, d, nnz_lo, nnz_hi):

@@ -93,7 +93,10 @@ def test_staleness_changes_the_batches(ref):
         assert any(not np.array_equal(a, b) for a, b in zip(outs[0][1]["kept_ids"], outs[2][1]["kept_ids"]))
 
 
-def test_sparse_rows_constant_step(ref):
+@pytest.mark.parametrize("schedule", [False, True])
+def test_sparse_rows(ref, schedule):
+    """CSR rows through the general kernels, with a constant step size and with the step-size
+    schedule kept on the device."""
     rowptr, col, val, y, _ = synth.sparse_svm(n=12_000, d=1 << 14, mean_nnz=60, threads=4)
     n, d, P, k = rowptr.size - 1, 1 << 14, 3000, 1
     perm = synth.epoch_permutation(n, seed=7, epoch=0)
@@ -102,11 +105,11 @@ def test_sparse_rows_constant_step(ref):
     gamma, lam, lr0, T, lr_a, step0 = 0.1, 1e-4, 0.5, 0.0, 0.5, 5
     for seed in range(42, 62):
         want = ref.train_stale(Fh, y, perm, P, z, z, 0.0, gamma, seed, step0, lam, lr0, T, lr_a, k,
-                               schedule=False)
+                               schedule=schedule)
         if all(clear_draws(ref, p, gamma, seed, step0 + s).all() for s, p in enumerate(want["prob"])):
             break
     got = _run_gpu(csr_features(rowptr, col, val, d), y, perm, n, P, d, k, gamma, seed, step0, lam, lr0,
-                   T, lr_a, z, z, 0.0, False)
+                   T, lr_a, z, z, 0.0, schedule)
     _compare(ref, got, want, P, gamma, seed, step0, rtol=5e-4, atol=5e-6)
 
 
