@@ -177,6 +177,43 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
   double *const s_ha = s_hs, *const s_hb = s_hs + (NVEC == 2 ? H : 0);
   const bool binned = GRAD && a.plan.nb > 0;
   const int salt = (int)((blockIdx.x * 0x9E3779B1u) >> 19) & (H - 1);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  const int grp = lane / GL, sub = lane % GL;
+
+  int total = a.count_max;
+  if (!POOL && a.m_dev) total = min(max(*a.m_dev, 0), a.count_max);
+  const int nwaves = gridDim.x * nw, gwave = blockIdx.x * nw + wave;
+  const int per = total / nwaves, rem = total % nwaves;
+  const int lo = gwave * per + min(gwave, rem);
+  const int hi = lo + per + (gwave < rem ? 1 : 0);
+
+  // One row per lane, 64 rows per round: id, extent, label, draw, incoming loss.
+  struct RowInfo {
+    long long e0;
+    int len;
+    float y, u, lin;
+  };
+  auto load_rows = [&](int round) {
+    RowInfo r{0, 0, 0.f, 2.f, 0.f};
+    const int base = lo + round * kWave;
+    const int j_l = base + lane;
+    if (j_l < hi) {
+      const int row_l = a.rows ? a.rows[j_l] : j_l;
+      if (CSR) {
+        r.e0 = a.rowptr[row_l];
+        r.len = (int)(a.rowptr[row_l + 1] - r.e0);
+      } else {
+        r.e0 = (long long)row_l * a.ld;
+        r.len = a.d;
+      }
+      if (SVM) r.y = a.y[row_l];
+      if (POOL && a.do_keep) r.u = keep_uniform(a.key, (uint32_t)j_l);
+      if (ASSIST && !SVM) r.lin = a.loss_in[j_l];
+    }
+    return r;
+  };
+  // (the first round's row loads are in flight while the block sets up its LDS)
+  RowInfo first = load_rows(0);
   if (GRAD) {
     for (int k = threadIdx.x; k < NVEC * D; k += blockDim.x) s_sum[k] = 0.0;
     for (int k = threadIdx.x; k < min(D, a.d); k += blockDim.x) {
@@ -188,16 +225,7 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
     if (threadIdx.x == 0) s_nrec = 0;
     __syncthreads();
   }
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
-  const int grp = lane / GL, sub = lane % GL;
-
   if (GRAD && a.t_upd && blockIdx.x == 0 && threadIdx.x == 0) *a.t_snap = *a.t_upd;
-  int total = a.count_max;
-  if (!POOL && a.m_dev) total = min(max(*a.m_dev, 0), a.count_max);
-  const int nwaves = gridDim.x * nw, gwave = blockIdx.x * nw + wave;
-  const int per = total / nwaves, rem = total % nwaves;
-  const int lo = gwave * per + min(gwave, rem);
-  const int hi = lo + per + (gwave < rem ? 1 : 0);
 
   const float b = (NEED_PHI && a.bias) ? *a.bias : 0.f;
   const float T = (ASSIST || HARD) ? *a.T : 0.f;
@@ -210,26 +238,35 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
   for (int round = 0; round < rounds; ++round) {
     const int base = lo + round * kWave;
     const int cnt = max(0, min(kWave, hi - base));
-    const int j_l = base + lane;
-    int row_l = 0;
-    long long e0_l = 0;
-    int len_l = 0;
-    float y_l = 0.f, u_l = 2.f, lin_l = 0.f;
-    if (lane < cnt) {
-      row_l = a.rows ? a.rows[j_l] : j_l;
-      if (CSR) {
-        e0_l = a.rowptr[row_l];
-        len_l = (int)(a.rowptr[row_l + 1] - e0_l);
-      } else {
-        e0_l = (long long)row_l * a.ld;
-        len_l = a.d;
-      }
-      if (SVM) y_l = a.y[row_l];
-      if (POOL && a.do_keep) u_l = keep_uniform(a.key, (uint32_t)j_l);
-      if (ASSIST && !SVM) lin_l = a.loss_in[j_l];
-    }
+    const RowInfo ri = round == 0 ? first : load_rows(round);
+    const long long e0_l = ri.e0;
+    const int len_l = ri.len;
+    const float y_l = ri.y, u_l = ri.u, lin_l = ri.lin;
     // the same trip count in every wave of the block (rows past a wave's own count are idle)
     const int iters = (max(0, min(kWave, rows_max - round * kWave)) + G - 1) / G;
+    constexpr int kUnroll = 8;
+    constexpr bool KEEP = GRAD && CSR;  // (dense rows here are long: nothing worth keeping)
+    // entries e, e + GL, ... of the row that starts at entry e0 and has len entries
+    auto load_entries_at = [&](long long e0, int len, int e, int *c, float *xv) {
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        const int eu = e + u * GL;
+        const bool in = eu < len;
+        c[u] = CSR ? (in ? a.col[e0 + eu] : 0) : (in ? eu : 0);
+        xv[u] = in ? (CSR ? (a.val ? a.val[e0 + eu] : 1.f) : a.x[e0 + eu]) : 0.f;
+      }
+    };
+    // The first kUnroll entries per lane of the NEXT group of rows are requested while this
+    // group's terms are scattered, so that a group's walk starts with its entries at hand.
+    int cn[KEEP ? kUnroll : 1];
+    float xn[KEEP ? kUnroll : 1];
+    auto prefetch_group = [&](int it) {
+      const int li = min(it * G + grp, kWave - 1);
+      const long long e0 = __shfl(e0_l, li, kWave);
+      const int len = __shfl(len_l, li, kWave);
+      load_entries_at(e0, it * G + grp < cnt ? len : 0, sub, cn, xn);
+    };
+    if (KEEP && iters > 0) prefetch_group(0);
     for (int it = 0; it < iters; ++it) {
       const int li = it * G + grp;
       const bool live = li < cnt;
@@ -243,18 +280,9 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
       float dp = 0.f, dw = 0.f;
       // kUnroll entries per lane at a time: their column and value loads leave together, then
       // the model gathers that depend on the columns (the chain that bounds this loop)
-      constexpr int kUnroll = 8;
       int c0[kUnroll];  // the first kUnroll entries of the lane stay in registers for the second walk
       float x0[kUnroll];
-      auto load_entries = [&](int e, int *c, float *xv) {
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-          const int eu = e + u * GL;
-          const bool in = eu < len;
-          c[u] = CSR ? (in ? a.col[e0 + eu] : 0) : (in ? eu : 0);
-          xv[u] = in ? (CSR ? (a.val ? a.val[e0 + eu] : 1.f) : a.x[e0 + eu]) : 0.f;
-        }
-      };
+      auto load_entries = [&](int e, int *c, float *xv) { load_entries_at(e0, len, e, c, xv); };
       auto dot_entries = [&](const int *c, const float *xv) {
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
@@ -277,9 +305,12 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
           }
         }
       };
-      constexpr bool KEEP = GRAD && CSR;  // (dense rows here are long: nothing worth keeping)
       if (KEEP) {
-        load_entries(sub, c0, x0);
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+          c0[u] = cn[u];
+          x0[u] = xn[u];
+        }
         dot_entries(c0, x0);
       }
       for (int e = sub + (KEEP ? GL * kUnroll : 0); e < len; e += GL * kUnroll) {
@@ -323,6 +354,7 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
           if (sub == 0) gb += resid;
         }
         if (sub == 0 && keep) kept += 1;
+        if (KEEP && it + 1 < iters) prefetch_group(it + 1);
         // second walk: the wave's groups step together, so that lanes with an entry outside the
         // table can reserve their places in the record buffer with one LDS atomic per step
         const bool contrib = cw != 0.f || resid != 0.f;
@@ -438,12 +470,6 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
       a.blk_cnt[blockIdx.x] = kb;
       a.blk_gb[blockIdx.x] = gbb;
     }
-    // the first columns: this block's sums, zeros included, as plain stores
-    float *const mine = a.part + (size_t)blockIdx.x * NVEC * a.head;
-    for (int k = threadIdx.x; k < a.head; k += blockDim.x) {
-      if (SVM) mine[k] = (float)s_w[k];
-      if (ASSIST) mine[(SVM ? a.head : 0) + k] = (float)s_p[k];
-    }
     if (binned) {
       flush_records<R, H, SVM, ASSIST, true>(a, D, s_rc, s_ra, s_rb, &s_nrec, s_tag, s_ha, s_hb,
                                              s_hist, s_base);
@@ -453,6 +479,13 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
         if (c >= 0)
           add_global<SVM, ASSIST>(a, c, s_ha[k], (SVM && ASSIST) ? s_hb[k] : 0.0);
       }
+    }
+    // the first columns: this block's sums, zeros included, as plain stores -- the last thing a
+    // wave does, so that nothing waits for them (a barrier after them would)
+    float *const mine = a.part + (size_t)blockIdx.x * NVEC * a.head;
+    for (int k = threadIdx.x; k < a.head; k += blockDim.x) {
+      if (SVM) mine[k] = (float)s_w[k];
+      if (ASSIST) mine[(SVM ? a.head : 0) + k] = (float)s_p[k];
     }
   }
 }
@@ -466,8 +499,6 @@ __global__ __launch_bounds__(256) void k_zero_f32(float *p, size_t count) {
   if (tid < count - 4 * n4) p[4 * n4 + tid] = 0.f;
 }
 
-// What a pass that updates both vectors needs beforehand, in one launch: the accumulators and
-// the header cleared, and the two model vectors side by side for the columns past the LDS table.
 // Scoring pass over CSR rows with the first kScoreTableCols entries of phi in LDS: one block of
 // 16 waves per compute unit loads them once and then walks its rows; only columns past the
 // table are gathered through the caches.  Pays when phi is too large for the vector L1 (a few
@@ -697,6 +728,8 @@ __global__ __launch_bounds__(kScoreTableThreads) void k_score_table(const GenArg
   }
 }
 
+// What a pass that updates both vectors needs beforehand, in one launch: the accumulators and
+// the header cleared, and the two model vectors side by side for the columns past the LDS table.
 __global__ __launch_bounds__(256) void k_prepare_general(float *p, size_t count, const float *w,
                                                          const float *phi, float2 *wp, int head,
                                                          int d) {
