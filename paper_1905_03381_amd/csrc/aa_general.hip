@@ -212,8 +212,6 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
     }
     return r;
   };
-  // (the first round's row loads are in flight while the block sets up its LDS)
-  RowInfo first = load_rows(0);
   if (GRAD) {
     for (int k = threadIdx.x; k < NVEC * D; k += blockDim.x) s_sum[k] = 0.0;
     for (int k = threadIdx.x; k < min(D, a.d); k += blockDim.x) {
@@ -238,7 +236,7 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
   for (int round = 0; round < rounds; ++round) {
     const int base = lo + round * kWave;
     const int cnt = max(0, min(kWave, hi - base));
-    const RowInfo ri = round == 0 ? first : load_rows(round);
+    const RowInfo ri = load_rows(round);  // (ahead of the LDS set-up these loads only delay it: measured)
     const long long e0_l = ri.e0;
     const int len_l = ri.len;
     const float y_l = ri.y, u_l = ri.u, lin_l = ri.lin;
@@ -416,9 +414,86 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
           }
                 };
         if (KEEP) {
+          // The entries held in registers go through the same stations as `scatter` above, but
+          // kBatch of a lane together: their tag reads are in flight at once, then the claims,
+          // then the second probes, and the wave reserves its places in the record buffer once
+          // -- a handful of LDS round trips per batch, not per entry.  (All kUnroll together
+          // cost more registers than there are.)
+          constexpr int kBatch = 4;
 #pragma unroll
-          for (int u = 0; u < kUnroll; ++u) {  // from registers
-            if (u * GL < steps_len) scatter(contrib && sub + u * GL < len, c0[u], x0[u]);
+          for (int u0 = 0; u0 < kUnroll; u0 += kBatch) {
+            if (u0 * GL >= steps_len) break;  // (no row of the wave reaches this far)
+            bool tl[kBatch];    // entry still on its way to a hashed slot or a record
+            int slot[kBatch];   // hashed slot it is looking at
+            int seen[kBatch];   // the tag found there
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) {
+              const int u = u0 + k;
+              const bool active = contrib && sub + u * GL < len;
+              const int c = c0[u];
+              if (active && c < D) {
+                if (SVM && cw != 0.f) unsafeAtomicAdd(s_w + c, (double)(cw * x0[u]));
+                if (ASSIST && resid != 0.f) unsafeAtomicAdd(s_p + c, (double)(resid * x0[u]));
+              }
+              tl[k] = active && c >= D;
+              slot[k] = (c ^ (c >> 11) ^ salt) & (H - 1);
+              seen[k] = tl[k] ? s_tag[slot[k]] : 0;
+            }
+            auto claim = [&](int k) {  // (a tag changes once, from -1 to its column)
+              if (tl[k] && seen[k] == -1) {
+                const int old = atomicCAS(s_tag + slot[k], -1, c0[u0 + k]);
+                seen[k] = old == -1 ? c0[u0 + k] : old;
+              }
+            };
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) claim(k);
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) {  // second try, elsewhere in the table
+              if (tl[k] && seen[k] != c0[u0 + k]) {
+                slot[k] = (slot[k] ^ (H / 2) ^ (c0[u0 + k] >> 5)) & (H - 1);
+                seen[k] = s_tag[slot[k]];
+              }
+            }
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) claim(k);
+            int n_tail = 0;
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) {
+              const int u = u0 + k;
+              if (tl[k] && seen[k] == c0[u]) {
+                const float ta = SVM ? cw * x0[u] : resid * x0[u], tb = resid * x0[u];
+                if (SVM && cw != 0.f) unsafeAtomicAdd(s_ha + slot[k], (double)ta);
+                if (ASSIST && resid != 0.f) unsafeAtomicAdd((SVM ? s_hb : s_ha) + slot[k], (double)tb);
+                tl[k] = false;
+              }
+              n_tail += __popcll(__ballot(tl[k]));
+            }
+            if (n_tail > 0) {  // (the same in every lane)
+              int first = 0;
+              if (binned) {
+                if (lane == 0) first = atomicAdd(&s_nrec, n_tail);
+                first = __shfl(first, 0, kWave);
+              }
+#pragma unroll
+              for (int k = 0; k < kBatch; ++k) {
+                const int u = u0 + k;
+                const unsigned long long mask = __ballot(tl[k]);
+                if (tl[k]) {
+                  const float ta = SVM ? cw * x0[u] : resid * x0[u], tb = resid * x0[u];
+                  const int pos = first + (int)__builtin_amdgcn_mbcnt_hi(
+                                              (uint32_t)(mask >> 32),
+                                              __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+                  if (binned && (unsigned)pos < (unsigned)R) {
+                    s_rc[pos] = c0[u];
+                    s_ra[pos] = ta;
+                    if (NVEC == 2) s_rb[pos] = tb;
+                  } else {
+                    add_global<SVM, ASSIST>(a, c0[u], ta, tb);
+                  }
+                }
+                first += __popcll(mask);
+              }
+            }
           }
         }
         for (int eb = KEEP ? GL * kUnroll : 0; eb < steps_len; eb += GL) {
