@@ -271,7 +271,7 @@ hipError_t run_pass(const PassSpec &s, const Ws &ws, int32_t *nblk_out, hipStrea
   a.blk_gb = ws.blk_gb;
   const int nvec = ((s.mode & kSvm) ? 1 : 0) + ((s.mode & kAssist) ? 1 : 0);
   a.acc_w = reinterpret_cast<double *>(acc + kGeneralHeader);
-  a.acc_used = reinterpret_cast<int32_t *>(acc) + 2;
+  a.acc_used = reinterpret_cast<int32_t *>(acc) + 16 + 2 * kMaxBins;
   a.acc_p = a.acc_w + s.F->d;
   a.part = reinterpret_cast<float *>(ws.grad + general_part_offset(s.F->d));
   a.head = general_head_columns(s.F->d, nvec);
@@ -354,7 +354,7 @@ hipError_t run_update(const PassSpec &s, const UpdateSpec &u, const Ws &ws, int3
   p.blk_cnt = ws.blk_cnt;
   p.blk_gb = ws.blk_gb;
   p.acc_w = reinterpret_cast<const double *>(acc + kGeneralHeader);
-  p.acc_used = reinterpret_cast<const int32_t *>(acc) + 2;
+  p.acc_used = reinterpret_cast<const int32_t *>(acc) + 16 + 2 * kMaxBins;
   p.acc_p = p.acc_w + s.F->d;
   p.part = reinterpret_cast<const float *>(ws.grad + general_part_offset(s.F->d));
   p.nvec = ((s.mode & kSvm) ? 1 : 0) + ((s.mode & kAssist) ? 1 : 0);

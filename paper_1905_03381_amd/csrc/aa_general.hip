@@ -39,13 +39,13 @@ __device__ __forceinline__ float gsum(float v) {
 // The sums are doubles: on MI355X `ds_add_f32` retires about one lane every three cycles,
 // `ds_add_f64` three lanes a cycle (measured, scattered addresses), and the sums come out
 // closer to exact.
-constexpr int kDirectTwoVec = 4096, kHashedTwoVec = 1024, kRecordsTwoVec = 3072;
+constexpr int kDirectTwoVec = 3072, kHashedTwoVec = 1024, kRecordsTwoVec = 5120;
 constexpr int kDirectOneVec = 8192, kHashedOneVec = 2048, kRecordsOneVec = 4096;
 constexpr int kGradThreads = 1024, kPoolThreads = 256;
 constexpr int kCheckRows = 8;  // rows per wave between two looks at the record buffer (4: 2 to 4 % slower, 16: the buffer overflows)
 
 __device__ __forceinline__ int bin_of(int c, int head, const BinPlan &p) {
-  return ((c - head) >> kBinGroupLog2) & (p.nb - 1);
+  return ((c - head) >> p.group_log2) & (p.nb - 1);
 }
 
 // Adds one entry's terms to the dense accumulators in HBM (the path of last resort).  They
@@ -53,7 +53,9 @@ __device__ __forceinline__ int bin_of(int c, int head, const BinPlan &p) {
 // so their sum must not round before it meets the rest of the column's total.
 template <bool SVM, bool ASSIST>
 __device__ __forceinline__ void add_global(const GenArgs &a, int c, double ta, double tb) {
-  *a.acc_used = 1;  // tells the update kernel to read the accumulators at all
+  // tells the owner of the column's bin to read its columns' accumulators at all (an entry
+  // that goes this way must not make every owner read every accumulator)
+  if (a.plan.nb > 0) a.acc_used[bin_of(c, a.head, a.plan)] = 1;
   if (SVM && ta != 0.0) unsafeAtomicAdd(a.acc_w + c, ta);
   if (ASSIST) {
     const double t = SVM ? tb : ta;
@@ -61,60 +63,54 @@ __device__ __forceinline__ void add_global(const GenArgs &a, int c, double ta, d
   }
 }
 
-// The k-th of the three floats whose sum is the double `s` exactly (24 + 24 + 5 bits).
-__device__ __forceinline__ float float_part(double s, int k) {
-  const float hi = (float)s;
-  if (k == 0) return hi;
-  if (!(fabsf(hi) <= 3.402823466e38f)) return 0.f;  // infinite or NaN: nothing is left to carry
-  const double r1 = s - (double)hi;
-  const float mid = (float)r1;
-  return k == 1 ? mid : (float)(r1 - (double)mid);
-}
-
 // Empties the block's record buffer -- and with HASHED its hashed slots -- into the bins.
 // Whole block; the caller has put a barrier between the last append and this call.
 // Which columns win a hashed slot depends on the order in which the waves arrive, so a slot's
-// sum must leave the block without rounding: it goes out as up to three records whose float
-// terms add up to the double exactly (the second and third are zero, and skipped, unless the
-// sum needs more than 24 bits).  The bin owner adds every record of a column in doubles, so a
-// column's total does not depend on how its entries were split between slots and records.
+// sum must leave the block without rounding: it goes out as a record of its own kind that
+// carries the double itself (one per updated vector).  The bin owner adds every record of a
+// column in doubles, so a column's total does not depend on how its entries were split
+// between slots and records.
 template <int R, int H, bool SVM, bool ASSIST, bool HASHED>
 __device__ __forceinline__ void flush_records(const GenArgs &a, int head, const int *s_rc,
                                               const float *s_ra, const float *s_rb, int *s_nrec,
                                               const int *s_tag, const double *s_ha,
                                               const double *s_hb, int *s_hist, int *s_base) {
-  constexpr int kPerR = R / kGradThreads, kPerH = HASHED ? 3 * H / kGradThreads : 0;
+  constexpr int kVec = (SVM && ASSIST) ? 2 : 1;
+  constexpr int kPerR = R / kGradThreads, kPerH = HASHED ? kVec * H / kGradThreads : 0;
   constexpr int kPer = kPerR + kPerH;
+  // the kind of the q-th record of a thread: 0 two float terms, 1 + v the double of vector v
+  auto kind_of = [](int q) { return q < kPerR ? 0 : 1 + ((q - kPerR) * kGradThreads) / H; };
   static_assert(R % kGradThreads == 0 && H % kGradThreads == 0, "whole turns of the block");
   const int n = min(*s_nrec, R);
   const int nb = a.plan.nb;
   for (int t = threadIdx.x; t < nb; t += blockDim.x) s_hist[t] = 0;
   __syncthreads();
   int col[kPer], rank[kPer];
-  float va[kPer], vb[kPer];
+  int va[kPer], vb[kPer];  // the record's second and third words
 #pragma unroll
   for (int q = 0; q < kPer; ++q) {
     const int i = threadIdx.x + q * kGradThreads;
     int c = -1;
-    float ta = 0.f, tb = 0.f;
+    int wa = 0, wb = 0;
     if (q < kPerR) {
       if (i < n) {
         c = s_rc[i];
-        ta = s_ra[i];
-        if (SVM && ASSIST) tb = s_rb[i];
+        wa = __float_as_int(s_ra[i]);
+        if (SVM && ASSIST) wb = __float_as_int(s_rb[i]);
       }
     } else {
-      const int slot = (i - R) & (H - 1), part = (i - R) / H;
+      const int slot = (i - R) & (H - 1);
       c = s_tag[slot];
       if (c >= 0) {
-        ta = float_part(s_ha[slot], part);
-        if (SVM && ASSIST) tb = float_part(s_hb[slot], part);
-        if (ta == 0.f && tb == 0.f) c = -1;
+        const double v = kind_of(q) == 1 ? s_ha[slot] : s_hb[slot];
+        wa = __double2loint(v);
+        wb = __double2hiint(v);
+        if (v == 0.0) c = -1;
       }
     }
     col[q] = c;
-    va[q] = ta;
-    vb[q] = tb;
+    va[q] = wa;
+    vb[q] = wb;
     rank[q] = c >= 0 ? atomicAdd(s_hist + bin_of(c, head, a.plan), 1) : 0;
   }
   __syncthreads();
@@ -132,15 +128,19 @@ __device__ __forceinline__ void flush_records(const GenArgs &a, int head, const 
     if (c < 0) continue;
     const int bin = bin_of(c, head, a.plan);
     const int pos = s_base[bin] + rank[q];
+    const int kind = kind_of(q);
     if (pos < a.plan.cap) {
       TailRecord r;
       r.col = c;
       r.a = va[q];
       r.b = vb[q];
-      r.pad = 0;
+      r.kind = kind;
       a.bins[(size_t)bin * a.plan.cap + pos] = r;
+    } else if (kind == 0) {
+      add_global<SVM, ASSIST>(a, c, __int_as_float(va[q]), __int_as_float(vb[q]));
     } else {
-      add_global<SVM, ASSIST>(a, c, va[q], vb[q]);
+      const double v = __hiloint2double(vb[q], va[q]);
+      add_global<SVM, ASSIST>(a, c, kind == 1 ? v : 0.0, kind == 1 ? 0.0 : v);
     }
   }
   __syncthreads();
@@ -826,6 +826,8 @@ constexpr int kHeadCols = 16;
 constexpr int kApplyThreads = 256;
 static_assert(kGeneralGradBlocks <= kApplyThreads, "one per-block count of the pass per thread");
 
+typedef float f4v __attribute__((ext_vector_type(4), aligned(4)));  // (any float address)
+
 // The update of one column from its gradient sums (m == 0: the model stays, its copy is still due).
 struct Fold {
   const ApplyArgs &a;
@@ -854,6 +856,26 @@ struct Fold {
   __device__ __forceinline__ void column(int k, float gw, float gp) const {
     loaded(k, gw, gp, a.w ? a.w[k] : 0.f, a.phi ? a.phi[k] : 0.f);
   }
+  // four columns from k on (the same arithmetic per column), as 128-bit stores
+  __device__ __forceinline__ void loaded4(int k, f4v gw, f4v gp, f4v w_old, f4v ph) const {
+    if (m <= 0) {
+      if (a.phi && a.phi_copy) *reinterpret_cast<f4v *>(a.phi_copy + k) = ph;
+      return;
+    }
+    if (a.w) {
+      f4v wn;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) wn[i] = __fmaf_rn(scale, gw[i], shrink * w_old[i]);
+      *reinterpret_cast<f4v *>(a.w + k) = wn;
+    }
+    if (a.phi) {
+      f4v pn;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) pn[i] = ph[i] - a.lr_a * __fmaf_rn(a.l2_a, ph[i], gp[i] * inv_m);
+      *reinterpret_cast<f4v *>(a.phi + k) = pn;
+      if (a.phi_copy) *reinterpret_cast<f4v *>(a.phi_copy + k) = pn;
+    }
+  }
 };
 
 // Kept count of the pass (and the sum of its bias gradients): one per-block value per thread.
@@ -876,57 +898,53 @@ __device__ __forceinline__ int pass_totals(const ApplyArgs &a, int cnt, float gb
 }
 
 __device__ __forceinline__ int bin_local(int col, const ApplyArgs &a) {
-  const int rel = col - a.head;
-  return (((rel >> kBinGroupLog2) >> a.plan.nb_log2) << kBinGroupLog2) | (rel & (kBinGroup - 1));
+  const int rel = col - a.head, gl = a.plan.group_log2;
+  return (((rel >> gl) >> a.plan.nb_log2) << gl) | (rel & ((1 << gl) - 1));
 }
 
 __device__ __forceinline__ int bin_column(int k, int bin, const ApplyArgs &a) {
-  return a.head +
-         (((((k >> kBinGroupLog2) << a.plan.nb_log2) | bin) << kBinGroupLog2) | (k & (kBinGroup - 1)));
+  const int gl = a.plan.group_log2;
+  return a.head + (((((k >> gl) << a.plan.nb_log2) | bin) << gl) | (k & ((1 << gl) - 1)));
 }
 
 // The block that owns a bin.  Everything it needs from memory (the first records and columns
 // per thread, in registers) is requested before anything is used: one round trip, not five.
 __device__ __forceinline__ void apply_bin(const ApplyArgs &a, int bin, double *s_bin, int *s_m,
                                           float *s_g) {
-  constexpr int kRec = 16, kCol = 16;
+  // per thread: kRec records per batch; kCol runs of four columns (a bin's columns come in
+  // groups of at least four neighbours) -- 4 * kCol * kApplyThreads covers any bin of a pass
+  // that updates two vectors, and half of the largest bin of one that updates one
+  constexpr int kRec = 16, kCol = 4;
   const int tid = threadIdx.x, cols = a.plan.cols, cap = a.plan.cap;
   const int cnt = tid < a.nblk_pass ? a.blk_cnt[tid] : 0;
   const int fill = (int)min(a.bin_fill[bin], (unsigned long long)cap);
-  const int acc_used = *a.acc_used;
+  const int acc_used = a.acc_used[bin];
   const TailRecord *rec = a.bins + (size_t)bin * cap;
-  // records: column and the two terms (the fourth word of a record is padding); two register
-  // sets, so that the loads of the next batch are in flight while this one is added up
-  int c0[kRec], c1[kRec];
-  float a0[kRec], b0[kRec], a1[kRec], b1[kRec];
+  // records, four words each; two register sets, so that the loads of the next batch are in
+  // flight while this one is added up
+  int4 r0[kRec], r1[kRec];
   constexpr int kBatch = kRec * kApplyThreads;
-  auto load_batch = [&](int *__restrict__ tc, float *__restrict__ ta, float *__restrict__ tb,
-                        int base, int limit) __attribute__((always_inline)) {
+  // (Every load below is unconditional: a load under a condition makes the compiler wait for
+  // all loads in flight where the paths join, and the requests would go out one at a time.
+  // An index past the end is clamped to the last record, whose value is then not used.)
+  auto load_batch = [&](int4 *__restrict__ r, int base, int last) __attribute__((always_inline)) {
 #pragma unroll
-    for (int u = 0; u < kRec; ++u) {
-      const int i = base + tid + u * kApplyThreads;
-      if (i < limit) {
-        const int *words = reinterpret_cast<const int *>(rec + i);
-        tc[u] = words[0];
-        ta[u] = __int_as_float(words[1]);
-        tb[u] = __int_as_float(words[2]);
-      } else {
-        tc[u] = a.head;
-        ta[u] = tb[u] = 0.f;
-      }
-    }
+    for (int u = 0; u < kRec; ++u)
+      r[u] = *reinterpret_cast<const int4 *>(rec + min(base + tid + u * kApplyThreads, last));
   };
-  load_batch(c0, a0, b0, 0, cap);  // past the fill count: stale, in bounds, not used
-  int col[kCol];
-  float wo[kCol], po[kCol];
+  load_batch(r0, 0, cap - 1);  // past the fill count: stale, in bounds, not used
+  int col[kCol];   // first column of the run, -1: none, or not all four exist (the model's end)
+  f4v wo[kCol], po[kCol];
+  const float *const w_src = a.w ? a.w : a.phi, *const p_src = a.phi ? a.phi : a.w;
 #pragma unroll
   for (int u = 0; u < kCol; ++u) {
-    const int k = tid + u * kApplyThreads;
+    const int k = 4 * (tid + u * kApplyThreads);
     int c = bin_column(k, bin, a);
-    if (k >= cols || c >= a.d) c = -1;
+    if (k >= cols || c + 4 > a.d) c = -1;
     col[u] = c;
-    wo[u] = (c >= 0 && a.w) ? a.w[c] : 0.f;
-    po[u] = (c >= 0 && a.phi) ? a.phi[c] : 0.f;
+    const int c_safe = c >= 0 ? c : a.d - 4;  // (bins exist: so do more than four columns)
+    wo[u] = *reinterpret_cast<const f4v *>(w_src + c_safe);
+    po[u] = *reinterpret_cast<const f4v *>(p_src + c_safe);
   }
   // A bin of few columns keeps several copies of its sums, one per lane residue, so that the
   // lanes of a wave that meet on a hot column add to different addresses (an odd stride puts
@@ -940,22 +958,26 @@ __device__ __forceinline__ void apply_bin(const ApplyArgs &a, int bin, double *s
   const int m = pass_totals(a, cnt, 0.f, s_m, s_g, &gb_unused);  // barrier: the sums are zero
   const Fold fold(a, m);
   const int n = min(fill, cap);
-  auto add = [&](int c, float ta, float tb) {
-    const int k = bin_local(c, a);
-    if (ta != 0.f) unsafeAtomicAdd(s_mine + k, (double)ta);
-    if (a.nvec == 2 && tb != 0.f) unsafeAtomicAdd(s_mine + cols + k, (double)tb);
+  auto add = [&](const int4 &r) {  // (x: column, y and z: the terms, w: the record's kind)
+    const int k = bin_local(r.x, a);
+    if (r.w == 0) {
+      const float ta = __int_as_float(r.y), tb = __int_as_float(r.z);
+      if (ta != 0.f) unsafeAtomicAdd(s_mine + k, (double)ta);
+      if (a.nvec == 2 && tb != 0.f) unsafeAtomicAdd(s_mine + cols + k, (double)tb);
+    } else {  // a hashed slot's sum: the double of one vector
+      unsafeAtomicAdd(s_mine + (r.w == 2 ? cols : 0) + k, __hiloint2double(r.z, r.y));
+    }
   };
-  auto add_batch = [&](const int *tc, const float *ta, const float *tb, int base)
-      __attribute__((always_inline)) {
+  auto add_batch = [&](const int4 *r, int base) __attribute__((always_inline)) {
 #pragma unroll
     for (int u = 0; u < kRec; ++u)
-      if (base + tid + u * kApplyThreads < n) add(tc[u], ta[u], tb[u]);
+      if (base + tid + u * kApplyThreads < n) add(r[u]);
   };
   for (int base = 0; base < n; base += 2 * kBatch) {
-    if (base + kBatch < n) load_batch(c1, a1, b1, base + kBatch, n);
-    add_batch(c0, a0, b0, base);
-    if (base + 2 * kBatch < n) load_batch(c0, a0, b0, base + 2 * kBatch, n);
-    if (base + kBatch < n) add_batch(c1, a1, b1, base + kBatch);
+    load_batch(r1, base + kBatch, n - 1);
+    add_batch(r0, base);
+    load_batch(r0, base + 2 * kBatch, n - 1);
+    add_batch(r1, base + kBatch);
   }
   __syncthreads();
   auto sum_of = [&](int k) {  // over the copies, in order
@@ -967,17 +989,59 @@ __device__ __forceinline__ void apply_bin(const ApplyArgs &a, int bin, double *s
   // a column's total is rounded to fp32 once, after everything has been added in doubles
   auto acc_w_of = [&](int c) { return (acc_used && a.w) ? a.acc_w[c] : 0.0; };
   auto acc_p_of = [&](int c) { return (acc_used && a.phi) ? a.acc_p[c] : 0.0; };
+  // The runs held in registers, in three sweeps -- sums out of LDS, then (rarely) the
+  // accumulators, then nothing but stores: a load between two stores would make every store
+  // wait for the one before it to be acknowledged.
+  double ga[kCol][4], gp[kCol][4];
 #pragma unroll
   for (int u = 0; u < kCol; ++u) {
-    if (col[u] < 0) continue;
-    const int k = tid + u * kApplyThreads;
-    const double va = sum_of(k), vb = a.nvec == 2 ? sum_of(cols + k) : va;
-    fold.loaded(col[u], (float)(acc_w_of(col[u]) + (a.w ? va : 0.0)), (float)(acc_p_of(col[u]) + vb),
-                wo[u], po[u]);
+    if (4 * u * kApplyThreads >= cols) break;  // (no thread has a run this far out)
+    const int k = min(4 * (tid + u * kApplyThreads), cols - 4);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const double va = sum_of(k + i), vb = a.nvec == 2 ? sum_of(cols + k + i) : va;
+      ga[u][i] = a.w ? va : 0.0;
+      gp[u][i] = vb;
+    }
   }
-  for (int k = tid + kCol * kApplyThreads; k < cols; k += kApplyThreads) {
+  if (acc_used) {
+    const double *const w_acc = a.w ? a.acc_w : a.acc_p, *const p_acc = a.phi ? a.acc_p : a.acc_w;
+    double xa[kCol][4], xp[kCol][4];
+#pragma unroll
+    for (int u = 0; u < kCol; ++u) {
+      const int c_safe = col[u] >= 0 ? col[u] : a.d - 4;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        xa[u][i] = w_acc[c_safe + i];
+        xp[u][i] = p_acc[c_safe + i];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kCol; ++u) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        ga[u][i] += a.w ? xa[u][i] : 0.0;
+        gp[u][i] += a.phi ? xp[u][i] : 0.0;
+      }
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < kCol; ++u) {
+    if (4 * u * kApplyThreads >= cols) break;
+    if (col[u] < 0) continue;
+    f4v fa, fp;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      fa[i] = (float)ga[u][i];
+      fp[i] = (float)gp[u][i];
+    }
+    fold.loaded4(col[u], fa, fp, wo[u], po[u]);
+  }
+  // what is left: runs past the registers' reach, and the model's last columns where fewer
+  // than four exist
+  for (int k = tid; k < cols; k += kApplyThreads) {
     const int c = bin_column(k, bin, a);
-    if (c >= a.d) continue;
+    if (c >= a.d || (k < 4 * kCol * kApplyThreads && (c & ~3) + 4 <= a.d)) continue;
     const double va = sum_of(k), vb = a.nvec == 2 ? sum_of(cols + k) : va;
     fold.column(c, (float)(acc_w_of(c) + (a.w ? va : 0.0)), (float)(acc_p_of(c) + vb));
   }
@@ -1017,20 +1081,23 @@ __global__ __launch_bounds__(kApplyThreads) void k_apply_general(const ApplyArgs
     const int cl = t & (kHeadCols - 1), q = t >> 4;
     const int k = hb * kHeadCols + cl;
     float sw = 0.f, sp = 0.f;
-    if (k < a.head) {  // (all zeros when nothing was kept)
+    // (loads without conditions, so that they are all in flight together; with one updated
+    // vector both pointers name the same sums and one of the two results is dropped)
+    const int k_safe = min(k, a.head - 1);
+    {  // (all zeros when nothing was kept)
       const size_t stride = (size_t)a.nvec * a.head;
-      const float *pw = a.part + k, *pp = a.part + (a.w ? a.head : 0) + k;
+      const float *pw = a.part + k_safe, *pp = a.part + (a.w ? a.head : 0) + k_safe;
 #pragma unroll 8
       for (int b = q; b < a.nblk_pass; b += 16) {
-        if (a.w) sw += pw[b * stride];
-        if (a.phi) sp += pp[b * stride];
+        sw += pw[b * stride];
+        sp += pp[b * stride];
       }
     }
-    float gw = 0.f, gp = 0.f, wo = 0.f, po = 0.f;
-    if (q == 0 && k < a.head) {  // (the accumulators take entries of the other columns only)
-      wo = a.w ? a.w[k] : 0.f;
-      po = a.phi ? a.phi[k] : 0.f;
-    }
+    if (!a.w || k >= a.head) sw = 0.f;
+    if (!a.phi || k >= a.head) sp = 0.f;
+    // (the accumulators take entries of the other columns only)
+    float gw = 0.f, gp = 0.f;
+    const float wo = (a.w ? a.w : a.phi)[k_safe], po = (a.phi ? a.phi : a.w)[k_safe];
     s_part[0][q][cl] = sw;
     s_part[1][q][cl] = sp;
     float gb_pass;

@@ -6,22 +6,31 @@
 
 namespace aa {
 
-// One stored entry of a kept row whose column has no slot in the block's LDS table:
-// its column and its terms of the (up to two) gradient sums.
+// What leaves a block of a gradient pass for a column without a slot in its LDS table.
+// kind 0: one stored entry of a kept row -- a and b hold, as float bits, its terms of the (up
+// to two) gradient sums (two updated vectors: a -> w, b -> phi; one: a -> that vector).
+// kind 1, 2: the sum a hashed slot collected for the first / second updated vector -- a and b
+// hold the low and high word of the double.
 struct __attribute__((aligned(16))) TailRecord {
   int32_t col;
-  float a, b;  // two updated vectors: a -> w, b -> phi; one: a -> that vector
-  int32_t pad;
+  int32_t a, b;
+  int32_t kind;
 };
 
-// Columns from `head` on are dealt to nb bins (a power of two, 0: no binning) in groups of 16
-// (one 64-byte line of a model vector): group g = (col - head) / 16 goes to bin g % nb,
-// where it is group g / nb; a bin spans `cols` columns in all and holds up to `cap` records.
+// Columns from `head` on are dealt to nb bins (a power of two, 0: no binning) in groups of
+// 2^group_log2: group g = (col - head) >> group_log2 goes to bin g % nb, where it is group
+// g / nb; a bin spans `cols` columns in all and holds up to `cap` records.  A group is 16
+// columns (one 64-byte line of a model vector) when there are many columns, so that the
+// owners read and write the model in whole lines; with fewer columns that traffic is small
+// beside the records', and groups of 4 spread a run of frequent neighbouring columns (the
+// head of a vocabulary, say) over four times as many bins -- the bin with the most records
+// sets the update kernel's time.
 struct BinPlan {
-  int32_t nb, nb_log2, cols, cap;
+  int32_t nb, nb_log2, cols, cap, group_log2;
 };
 constexpr int kMaxBins = 256;
-constexpr int kBinGroupLog2 = 4, kBinGroup = 1 << kBinGroupLog2;
+constexpr int kBinGroupLog2 = 4, kBinFineGroupLog2 = 2;
+constexpr int64_t kBinFineColsMax = 1 << 18;  // groups of 4 up to this many binned columns
 constexpr int kBinColsMax = 8192;  // LDS floats of a bin's owner in the update kernel
 // Records the bins hold in all: 48 per candidate (the sparse configuration needs about 26),
 // at least 65,536, at most 2^27 (2 GiB); what does not fit goes to the accumulators.
@@ -30,18 +39,21 @@ inline size_t general_record_capacity(int32_t count_max) {
   return want < 65536 ? 65536 : (want > ((size_t)1 << 27) ? ((size_t)1 << 27) : want);
 }
 inline BinPlan general_bin_plan(int32_t d, int32_t head, int nvec, int32_t count_max) {
-  BinPlan p{0, 0, 0, 0};
-  const int64_t groups = ((int64_t)d - head + kBinGroup - 1) / kBinGroup;
+  BinPlan p{0, 0, 0, 0, kBinGroupLog2};
+  const int gl = (int64_t)d - head <= kBinFineColsMax ? kBinFineGroupLog2 : kBinGroupLog2;
+  const int64_t group = (int64_t)1 << gl;
+  const int64_t groups = ((int64_t)d - head + group - 1) / group;
   if (groups <= 0 || nvec < 1) return p;
   int nb = 1, lg = 0;
   while (nb * 2 <= kMaxBins && nb * 2 <= groups) {
     nb *= 2;
     ++lg;
   }
-  const int64_t cols = kBinGroup * ((groups + nb - 1) / nb);
+  const int64_t cols = group * ((groups + nb - 1) / nb);
   if (cols * nvec > kBinColsMax) return p;  // too many columns for the owners' LDS: atomics instead
   p.nb = nb;
   p.nb_log2 = lg;
+  p.group_log2 = gl;
   p.cols = (int32_t)cols;
   p.cap = (int32_t)(general_record_capacity(count_max) / nb);
   return p;
@@ -75,10 +87,11 @@ struct GenArgs {
   // brings both values of a column that is not in LDS (written before the pass; NULL unless
   // the pass updates both vectors)
   const float2 *wp;
-  // atomic accumulators (zeroed before the pass); *acc_used (zeroed too) is set by whoever adds
+  // atomic accumulators (zeroed before the pass); with bins, acc_used[bin] (zeroed too) is set
+  // by whoever adds to a column of that bin
   double *acc_w;     // [d]
   double *acc_p;     // [d]
-  int32_t *acc_used;
+  int32_t *acc_used; // [kMaxBins]
   // per-block kept count and bias-gradient sum of a gradient pass (plain stores)
   int32_t *blk_cnt;  // [blocks of the pass]
   float *blk_gb;     // [blocks of the pass]
@@ -101,9 +114,9 @@ struct GenArgs {
 // that updates nvec vectors over d columns; blocks of a gradient pass at most.
 int32_t general_head_columns(int32_t d, int nvec);
 constexpr int kGeneralGradBlocks = 256;
-// floats ahead of the accumulators: 16 scalars, then the 64-bit fill counts of the bins
-// (an even count: the accumulators behind it are doubles)
-constexpr int kGeneralHeader = 16 + 2 * kMaxBins;
+// floats ahead of the accumulators: 16 scalars, the 64-bit fill counts of the bins, then one
+// flag per bin (an even count in all: the accumulators behind it are doubles)
+constexpr int kGeneralHeader = 16 + 3 * kMaxBins;
 // floats the header and the two accumulators of d doubles take
 inline size_t general_clear_floats(int32_t d) { return kGeneralHeader + 4 * (size_t)d; }
 inline size_t general_part_floats(int32_t d) {
@@ -115,7 +128,7 @@ struct ApplyArgs {
   int32_t d;
   const double *acc_w;
   const double *acc_p;
-  const int32_t *acc_used;  // 0: the pass added nothing to the accumulators
+  const int32_t *acc_used;  // [bin] 0: the pass added nothing to the accumulators of the bin's columns
   const int32_t *blk_cnt;  // per-block kept counts and bias-gradient sums of the pass
   const float *blk_gb;
   const int32_t *m_dev;
