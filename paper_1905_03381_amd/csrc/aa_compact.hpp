@@ -63,19 +63,34 @@ __device__ inline void tile_compact(const CompactArgs &c, int tile, int *smem) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int j0 = tile * kCompactTile;
   const int seg = j0 + wave * (kCompactTile / 4);
-  // the tile's own loads go out first, then the count of the flags before the tile
+  // The tile's own loads go out first, then the count of the flags before the tile.  No load
+  // sits under a per-element condition (the compiler would wait for each before requesting
+  // the next): a position past the pool reads the pool's last element instead, and whether
+  // an array takes part at all is decided once, around its eight loads.
   uint8_t fl[8];
   int ids[8];
   float ls[8];
+  const int last = c.P - 1;  // (a tile exists: P > 0)
 #pragma unroll
-  for (int r = 0; r < 8; ++r) {
-    const int j = seg + r * kWave + lane;
-    const bool in = j < c.P;
-    fl[r] = in ? c.flags[j] : (uint8_t)0;
-    ids[r] = (in && c.kept_ids) ? (c.idx ? c.idx[j] : j) : 0;
-    ls[r] = (in && c.loss) ? c.loss_pool[j] : 0.f;
+  for (int r = 0; r < 8; ++r) fl[r] = c.flags[min(seg + r * kWave + lane, last)];
+  if (c.kept_ids && c.idx) {
+#pragma unroll
+    for (int r = 0; r < 8; ++r) ids[r] = c.idx[min(seg + r * kWave + lane, last)];
+  } else {
+#pragma unroll
+    for (int r = 0; r < 8; ++r) ids[r] = seg + r * kWave + lane;
+  }
+  if (c.loss) {
+#pragma unroll
+    for (int r = 0; r < 8; ++r) ls[r] = c.loss_pool[min(seg + r * kWave + lane, last)];
+  } else {
+#pragma unroll
+    for (int r = 0; r < 8; ++r) ls[r] = 0.f;
   }
   const int prefix = c.tile_off ? c.tile_off[tile] : count_flags_before(c.flags, j0, smem);
+#pragma unroll
+  for (int r = 0; r < 8; ++r)
+    if (seg + r * kWave + lane > last) fl[r] = 0;
   unsigned long long masks[8];
   int wave_total = 0;
 #pragma unroll

@@ -183,16 +183,22 @@ __global__ __launch_bounds__(NW * 64)
   // (d4 == ROW4) the loads are unconditional: a slot past the end of the group re-reads the
   // group's last row (a cache hit) and is never consumed, so the loads carry no branches.
   const bool full = a.d4 == ROW4;
+  // (The two cases are two loops, not one loop with a case inside: the compiler would share
+  // code between them, and with it the waits that the conditional loads need.)
   auto issue_rows = [&](int it0) {
+    if (full) {
 #pragma unroll
-    for (int r = 0; r < RIF; ++r) {
-      const int li = (it0 + r) * G + grp;
-      if (full) {
+      for (int r = 0; r < RIF; ++r) {
+        const int li = (it0 + r) * G + grp;
         const int row = __shfl(row_l, min(li, cnt - 1), kWave);
         const f4 *xr = reinterpret_cast<const f4 *>(a.x + (int64_t)row * a.ld);
 #pragma unroll
         for (int v = 0; v < VPL; ++v) x[r][v] = AA_ROW_LOAD(xr + v * LPR + sub);
-      } else {
+      }
+    } else {
+#pragma unroll
+      for (int r = 0; r < RIF; ++r) {
+        const int li = (it0 + r) * G + grp;
         const int row = __shfl(row_l, li & 63, kWave);
         const f4 *xr = reinterpret_cast<const f4 *>(a.x + (int64_t)row * a.ld);
 #pragma unroll
