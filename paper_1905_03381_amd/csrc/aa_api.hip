@@ -168,6 +168,9 @@ struct PassSpec {
   // (running median with this momentum; *T and *med_init are rewritten by the update kernel)
   int32_t *med_init;
   float med_momentum;
+  // general path: the update kernel of the previous step of this call has left the workspace
+  // ready (cleared counts and accumulators, current model pairs): no preparing launch
+  bool ws_ready;
 };
 
 bool use_fast(const PassSpec &s) {
@@ -233,7 +236,7 @@ hipError_t run_pass(const PassSpec &s, const Ws &ws, int32_t *nblk_out, hipStrea
   }
   const bool csr = s.F->layout == AA_CSR;
   float *acc = reinterpret_cast<float *>(ws.grad);
-  if (s.mode & (kSvm | kAssist)) {
+  if ((s.mode & (kSvm | kAssist)) && !s.ws_ready) {
     const size_t clear = general_clear_floats(s.F->d);
     const bool both = (s.mode & kSvm) && (s.mode & kAssist);
     const int32_t head = general_head_columns(s.F->d, 2);
@@ -304,6 +307,7 @@ struct UpdateSpec {
   const float *loss_pool;
   float *loss;
   int32_t *kept_count;
+  bool keep_ready;  // general path: leave the workspace ready for the next pass of this call
 };
 
 // Fold the gradient sums of the pass into the model.
@@ -348,22 +352,26 @@ hipError_t run_update(const PassSpec &s, const UpdateSpec &u, const Ws &ws, int3
     f.kept_count = u.kept_count;
     return launch_dense_finalize(f, st);
   }
-  const float *acc = reinterpret_cast<const float *>(ws.grad);
+  float *acc = reinterpret_cast<float *>(ws.grad);
   ApplyArgs p{};
   p.d = s.F->d;
   p.blk_cnt = ws.blk_cnt;
   p.blk_gb = ws.blk_gb;
-  p.acc_w = reinterpret_cast<const double *>(acc + kGeneralHeader);
-  p.acc_used = reinterpret_cast<const int32_t *>(acc) + 16 + 2 * kMaxBins;
+  p.acc_w = reinterpret_cast<double *>(acc + kGeneralHeader);
+  p.acc_used = reinterpret_cast<int32_t *>(acc) + 16 + 2 * kMaxBins;
   p.acc_p = p.acc_w + s.F->d;
   p.part = reinterpret_cast<const float *>(ws.grad + general_part_offset(s.F->d));
   p.nvec = ((s.mode & kSvm) ? 1 : 0) + ((s.mode & kAssist) ? 1 : 0);
   p.head = general_head_columns(s.F->d, p.nvec);
-  p.bin_fill = reinterpret_cast<const unsigned long long *>(acc + 16);
+  p.bin_fill = reinterpret_cast<unsigned long long *>(acc + 16);
   p.bins = reinterpret_cast<const TailRecord *>(ws.grad + general_bins_offset(s.F->d));
   p.plan = general_bin_plan(s.F->d, p.head, p.nvec, s.count_max);
   p.t_upd = u.t_upd;
   p.t_snap = ws.ctl + kCtlUpdateSnapshot;
+  p.keep_ready = (u.keep_ready && p.plan.nb > 0) ? 1 : 0;
+  p.wp_out = (p.keep_ready && p.nvec == 2 && s.F->d > p.head)
+                 ? reinterpret_cast<float2 *>(ws.grad + general_pairs_offset(s.F->d))
+                 : nullptr;
   p.nblk_pass = nblk;
   p.m_dev = pool ? nullptr : s.m_dev;
   p.m_max = s.count_max;
@@ -426,6 +434,8 @@ struct EpochCtl {
   bool may_defer;
   CompactArgs *deferred;     // out: filled when this step's compaction was left to the next pass
   bool did_defer;
+  bool ws_ready;             // in: the previous step of this call left the general workspace ready
+  bool left_ready;           // out: this step did
 };
 
 int32_t fused_step_impl(const aa_features *F, const float *y, const int32_t *idx, int32_t P,
@@ -470,6 +480,8 @@ int32_t fused_step_impl(const aa_features *F, const float *y, const int32_t *idx
     }
     if (ep->carry && fast) s.prev = *ep->carry;
     ep->did_defer = false;
+    s.ws_ready = !fast && ep->ws_ready;
+    ep->left_ready = false;
   }
   s.loss_out = loss_pool;
   int32_t nblk = 0;
@@ -482,6 +494,7 @@ int32_t fused_step_impl(const aa_features *F, const float *y, const int32_t *idx
   u.l2_a = cfg->l2_a;
   u.t_upd = t_upd;
   u.kept_hist = kept_hist;
+  u.keep_ready = ep && !fast && general_keeps_ready(F->d, hard ? 1 : 2);
   if (kept_pos || kept_ids || loss || kept_count) {
     CompactArgs c{};
     c.flags = s.flags;
@@ -506,7 +519,9 @@ int32_t fused_step_impl(const aa_features *F, const float *y, const int32_t *idx
       u.kept_count = c.kept_count;
     }
   }
-  return hip_status(run_update(s, u, ws, nblk, st));
+  const int32_t rc = hip_status(run_update(s, u, ws, nblk, st));
+  if (ep && rc == AA_OK) ep->left_ready = u.keep_ready;
+  return rc;
 }
 
 // Extra workspace of the two-stream pipeline behind the common layout: `ring` batch slots
@@ -1044,6 +1059,7 @@ static int32_t epoch_impl(const aa_features *F, const float *y, const int32_t *p
   const int mode = hard ? (kPool | kSvm | kHard) : (kPool | kSvm | kAssist);
   CompactArgs pending{};
   bool have_pending = false;
+  bool ws_ready = false;  // (the first step of a call always prepares the workspace itself)
   for (int64_t t = 0; t < steps; ++t) {
     const int64_t lo = t * P;
     const int32_t Pt = (int32_t)((n_perm - lo) < P ? (n_perm - lo) : P);
@@ -1053,6 +1069,7 @@ static int32_t epoch_impl(const aa_features *F, const float *y, const int32_t *p
     ep.ids_dst = kept_ids_hist ? kept_ids_hist + t * (int64_t)P : nullptr;
     ep.loss_dst = loss_hist ? loss_hist + t * (int64_t)P : nullptr;
     ep.carry = have_pending ? &pending : nullptr;
+    ep.ws_ready = ws_ready;
     CompactArgs mine{};
     ep.deferred = &mine;
     // This pool's compaction rides on the next step's pass when that pass has a block for
@@ -1069,6 +1086,7 @@ static int32_t epoch_impl(const aa_features *F, const float *y, const int32_t *p
     if (rc != AA_OK) return rc;
     have_pending = ep.did_defer;
     pending = mine;
+    ws_ready = ep.left_ready;
   }
   return AA_OK;
 }

@@ -846,12 +846,14 @@ struct Fold {
       if (a.phi && a.phi_copy) a.phi_copy[k] = ph;
       return;
     }
-    if (a.w) a.w[k] = __fmaf_rn(scale, gw, shrink * w_old);
+    const float wn = __fmaf_rn(scale, gw, shrink * w_old);
+    const float pn = ph - a.lr_a * __fmaf_rn(a.l2_a, ph, gp * inv_m);
+    if (a.w) a.w[k] = wn;
     if (a.phi) {
-      const float pn = ph - a.lr_a * __fmaf_rn(a.l2_a, ph, gp * inv_m);
       a.phi[k] = pn;
       if (a.phi_copy) a.phi_copy[k] = pn;
     }
+    if (a.wp_out) a.wp_out[k] = make_float2(wn, pn);  // (both vectors are updated then)
   }
   __device__ __forceinline__ void column(int k, float gw, float gp) const {
     loaded(k, gw, gp, a.w ? a.w[k] : 0.f, a.phi ? a.phi[k] : 0.f);
@@ -862,18 +864,22 @@ struct Fold {
       if (a.phi && a.phi_copy) *reinterpret_cast<f4v *>(a.phi_copy + k) = ph;
       return;
     }
-    if (a.w) {
-      f4v wn;
+    f4v wn, pn;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) wn[i] = __fmaf_rn(scale, gw[i], shrink * w_old[i]);
-      *reinterpret_cast<f4v *>(a.w + k) = wn;
+    for (int i = 0; i < 4; ++i) {
+      wn[i] = __fmaf_rn(scale, gw[i], shrink * w_old[i]);
+      pn[i] = ph[i] - a.lr_a * __fmaf_rn(a.l2_a, ph[i], gp[i] * inv_m);
     }
+    if (a.w) *reinterpret_cast<f4v *>(a.w + k) = wn;
     if (a.phi) {
-      f4v pn;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) pn[i] = ph[i] - a.lr_a * __fmaf_rn(a.l2_a, ph[i], gp[i] * inv_m);
       *reinterpret_cast<f4v *>(a.phi + k) = pn;
       if (a.phi_copy) *reinterpret_cast<f4v *>(a.phi_copy + k) = pn;
+    }
+    if (a.wp_out) {  // (both vectors are updated then)
+      const f4v lo = {wn[0], pn[0], wn[1], pn[1]}, hi = {wn[2], pn[2], wn[3], pn[3]};
+      f4v *const dst = reinterpret_cast<f4v *>(a.wp_out + k);
+      dst[0] = lo;
+      dst[1] = hi;
     }
   }
 };
@@ -1005,7 +1011,7 @@ __device__ __forceinline__ void apply_bin(const ApplyArgs &a, int bin, double *s
     }
   }
   if (acc_used) {
-    const double *const w_acc = a.w ? a.acc_w : a.acc_p, *const p_acc = a.phi ? a.acc_p : a.acc_w;
+    double *const w_acc = a.w ? a.acc_w : a.acc_p, *const p_acc = a.phi ? a.acc_p : a.acc_w;
     double xa[kCol][4], xp[kCol][4];
 #pragma unroll
     for (int u = 0; u < kCol; ++u) {
@@ -1022,6 +1028,17 @@ __device__ __forceinline__ void apply_bin(const ApplyArgs &a, int bin, double *s
       for (int i = 0; i < 4; ++i) {
         ga[u][i] += a.w ? xa[u][i] : 0.0;
         gp[u][i] += a.phi ? xp[u][i] : 0.0;
+      }
+    }
+    if (a.keep_ready) {  // what was read is cleared for the next pass (this bin's columns only)
+#pragma unroll
+      for (int u = 0; u < kCol; ++u) {
+        if (col[u] < 0) continue;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          w_acc[col[u] + i] = 0.0;
+          p_acc[col[u] + i] = 0.0;
+        }
       }
     }
   }
@@ -1044,6 +1061,14 @@ __device__ __forceinline__ void apply_bin(const ApplyArgs &a, int bin, double *s
     if (c >= a.d || (k < 4 * kCol * kApplyThreads && (c & ~3) + 4 <= a.d)) continue;
     const double va = sum_of(k), vb = a.nvec == 2 ? sum_of(cols + k) : va;
     fold.column(c, (float)(acc_w_of(c) + (a.w ? va : 0.0)), (float)(acc_p_of(c) + vb));
+    if (acc_used && a.keep_ready) {
+      if (a.w) a.acc_w[c] = 0.0;
+      if (a.phi) a.acc_p[c] = 0.0;
+    }
+  }
+  if (a.keep_ready && tid == 0) {  // (read at the top; the next pass counts from zero)
+    a.bin_fill[bin] = 0ull;
+    a.acc_used[bin] = 0;
   }
 }
 
@@ -1205,6 +1230,10 @@ hipError_t launch_zero_f32(float *p, size_t count, hipStream_t st) {
   if (blocks < 1) blocks = 1;
   hipLaunchKernelGGL(k_zero_f32, dim3((unsigned)blocks), dim3(256), 0, st, p, count);
   return hipGetLastError();
+}
+
+bool general_keeps_ready(int32_t d, int nvec) {
+  return general_bin_plan(d, general_head_columns(d, nvec), nvec, 1).nb > 0;
 }
 
 int32_t general_head_columns(int32_t d, int nvec) {

@@ -113,6 +113,8 @@ struct GenArgs {
 // Columns whose gradient sums leave a block as plain stores instead of atomics, for a pass
 // that updates nvec vectors over d columns; blocks of a gradient pass at most.
 int32_t general_head_columns(int32_t d, int nvec);
+// Whether the update kernel can leave the workspace ready for the next pass (see ApplyArgs).
+bool general_keeps_ready(int32_t d, int nvec);
 constexpr int kGeneralGradBlocks = 256;
 // floats ahead of the accumulators: 16 scalars, the 64-bit fill counts of the bins, then one
 // flag per bin (an even count in all: the accumulators behind it are doubles)
@@ -126,9 +128,15 @@ inline size_t general_part_floats(int32_t d) {
 
 struct ApplyArgs {
   int32_t d;
-  const double *acc_w;
-  const double *acc_p;
-  const int32_t *acc_used;  // [bin] 0: the pass added nothing to the accumulators of the bin's columns
+  double *acc_w;
+  double *acc_p;
+  int32_t *acc_used;  // [bin] 0: the pass added nothing to the accumulators of the bin's columns
+  // Leave the workspace as the next pass of the same call needs it, so that no preparing
+  // launch has to run in between (bins only): every bin owner clears its fill count, its flag
+  // and whatever it read from the accumulators, and with two updated vectors writes the new
+  // (w[c], phi[c]) pairs of its columns.
+  int32_t keep_ready;
+  float2 *wp_out;     // pairs, indexed by column (NULL: none)
   const int32_t *blk_cnt;  // per-block kept counts and bias-gradient sums of the pass
   const float *blk_gb;
   const int32_t *m_dev;
@@ -141,7 +149,7 @@ struct ApplyArgs {
   const float *part;  // per-block sums of the first `head` columns (see GenArgs)
   int32_t head, nvec, nblk_pass;
   const TailRecord *bins;  // records of the other columns (see GenArgs)
-  const unsigned long long *bin_fill;
+  unsigned long long *bin_fill;
   BinPlan plan;
   float lambda, lr, lr_a, l2_a;
   int32_t *t_upd;          // optional update counter: the Boss step size is lr / sqrt(updates so far)

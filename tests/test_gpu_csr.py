@@ -451,6 +451,35 @@ def test_csr_updates_uniform_columns(ref, n, nnz_lo, nnz_hi):
     assert abs(float(host(b)[0]) - b_ref) <= RTOL * (abs(b0) + lr_a)
 
 
+def test_train_epoch_with_overflowing_bins(ref):
+    """aa_train_epoch over rows of about 600 entries with columns uniform over d = 2^18: in every
+    step the record buffer and the bins overflow into the accumulators.  One step per call
+    (each call prepares the workspace itself) is held to the oracle step at the single-step
+    tolerances; then the epoch in one call, where from the second step on no launch prepares
+    the workspace -- the update kernel of the step before has cleared what it read and has
+    written the model pairs -- must give the same bits: a count or an accumulator left over, or
+    a stale pair, would show.  Twice."""
+    from stepwise import check_epoch, run_whole
+    r = rng(33)
+    n, d, P = 3000, 1 << 18, 1000
+    rowptr, col, val = _uniform_csr(r, n, d, 500, 700)
+    y = np.where(r.random(n) < 0.5, -1.0, 1.0).astype(np.float32)
+    perm = r.permutation(n).astype(np.int32)
+    Fh = ref.Features.csr(rowptr, col, val, d)
+    F = csr_features(rowptr, col, val, d)
+    ws = api.Workspace(P, d)
+    w0 = (0.5 * r.standard_normal(d)).astype(np.float32)
+    phi0 = (0.5 * r.standard_normal(d)).astype(np.float32)
+    args = dict(gamma=0.3, seed=7, step0=0, lam=1e-3, lr0=20.0, lr_a=10.0, T=0.5, ws=ws)
+    counts, state = check_epoch(ref, Fh, F, y, perm, n, P, w0, phi0, 0.1, **args)
+    assert len(counts) == 3 and all(P // 4 < m <= P for m in counts)
+    for _ in range(2):
+        hist, _, _, again = run_whole(F, y, perm, n, P, w0, phi0, 0.1, **args)
+        assert hist == counts
+        assert np.array_equal(again[0], state[0]) and np.array_equal(again[1], state[1])
+        assert np.array_equal(again[2], state[2])
+
+
 def test_csr_fused_step_more_columns_than_the_bins_cover(ref):
     """d = 1,300,000 with both vectors updated: too many columns for the column bins, so every
     entry outside the per-block table goes to the dense accumulators."""
