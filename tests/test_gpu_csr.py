@@ -526,6 +526,73 @@ def test_csr_fused_step_more_columns_than_the_bins_cover(ref):
                         "phi")
 
 
+def _check_csr_updates(ref, r, d, n, kind, lo, hi, with_val):
+    """Boss step, Assistant update and both in one pass on random CSR rows of `lo` to `hi`
+    entries against the oracle (columns uniform, Zipf-like or hot at the end of the range)."""
+    lens = r.integers(lo, hi + 1, size=n)
+    if r.random() < 0.2 and n > 1:
+        lens[r.integers(1, n, size=max(1, n // 10))] = 0  # empty rows
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(lens, out=rowptr[1:])
+    nnz = int(rowptr[-1])
+    if kind == "uniform":
+        col = r.integers(0, d, size=nnz)
+    elif kind == "zipf":
+        col = np.minimum(r.pareto(1.1, size=nnz).astype(np.int64), d - 1)
+    else:  # a few very hot columns at the end of the range
+        col = np.where(r.random(nnz) < 0.5, d - 1 - r.integers(0, min(3, d), size=nnz),
+                       r.integers(0, d, size=nnz))
+    col = col.astype(np.int32)
+    val = r.standard_normal(nnz).astype(np.float32) if with_val else None
+    y = np.where(r.random(n) < 0.5, -1.0, 1.0).astype(np.float32)
+    w0 = (0.3 * r.standard_normal(d)).astype(np.float32)
+    phi0 = (0.3 * r.standard_normal(d)).astype(np.float32)
+    m = int(r.integers(1, n + 1))
+    rows = r.permutation(n)[:m].astype(np.int32)
+    tag = f"d={d} n={n} m={m} nnz={nnz} {kind}"
+    Fh = ref.Features.csr(rowptr, col, val, d)
+    F = csr_features(rowptr, col, val, d)
+    ws = api.Workspace(m, d)
+    vv = np.ones(nnz) if val is None else val.astype(np.float64)
+    S = sp.csr_matrix((vv, col, rowptr), shape=(n, d))
+    Sa = sp.csr_matrix((np.abs(vv), col, rowptr), shape=(n, d))
+    lam, lr, T, lr_a, b0 = 1e-3, 0.7, 0.4, 0.5, 0.1
+    w_ref, loss_ref = ref.svm_sgd_step(Fh, y, rows, m, w0, lam, lr)
+    dots = (S[rows] @ w0.astype(np.float64)) * y[rows]
+    Sdot = Sa[rows] @ np.abs(w0.astype(np.float64))
+    kink = np.abs(dots - 1) <= RTOL * Sdot
+    w = dev(w0)
+    loss = torch.zeros(m, device="cuda")
+    api.svm_sgd_step(F, dev(y), dev(rows), scalar_dev(m, torch.int32), m, w, lam, lr, 0.0, loss, ws)
+    assert_close_scaled(host(loss), loss_ref, Sdot, "loss " + tag, atol=1e-6)
+    absx_w = np.asarray(Sa[rows[dots < 1]].sum(axis=0)).ravel()
+    akink = np.asarray(Sa[rows[kink]].sum(axis=0)).ravel()
+    assert_close_scaled(host(w), w_ref, np.abs(w0.astype(np.float64)) + lr / m * absx_w, "w " + tag,
+                        atol=lr / m * akink)
+    phi_ref, b_ref = ref.assistant_update(Fh, rows, m, loss_ref, T, phi0, b0, lr_a)
+    phi, b = dev(phi0), scalar_dev(b0)
+    api.assistant_update(F, dev(rows), scalar_dev(m, torch.int32), m, dev(loss_ref),
+                         scalar_dev(T), phi, b, lr_a, 0.0, ws)
+    absx = np.asarray(Sa[rows].sum(axis=0)).ravel()
+    assert_close_scaled(host(phi), phi_ref, np.abs(phi0.astype(np.float64)) + lr_a / m * absx,
+                        "phi " + tag)
+    assert abs(float(host(b)[0]) - b_ref) <= RTOL * (abs(b0) + lr_a), tag
+    # both updates in one pass over the rows (labels from the kernel's own losses: a row
+    # whose loss sits within rounding of T may take either label)
+    w, phi, b = dev(w0), dev(phi0), scalar_dev(b0)
+    Tt = scalar_dev(T)
+    cfg = api.step_config(0.0, lam, lr, lr_a, 0.0, 1, 0, Tt)
+    api.boss_assistant_step(F, dev(y), dev(rows), scalar_dev(m, torch.int32), m, w, phi, b, cfg,
+                            loss, ws)
+    assert_close_scaled(host(w), w_ref, np.abs(w0.astype(np.float64)) + lr / m * absx_w,
+                        "w (one pass) " + tag, atol=lr / m * akink)
+    on_T = np.abs(loss_ref.astype(np.float64) - T) <= RTOL * Sdot
+    a_T = np.asarray(Sa[rows[on_T]].sum(axis=0)).ravel()
+    assert_close_scaled(host(phi), phi_ref, np.abs(phi0.astype(np.float64)) + lr_a / m * absx,
+                        "phi (one pass) " + tag, atol=lr_a / m * a_T)
+    assert abs(float(host(b)[0]) - b_ref) <= RTOL * (abs(b0) + lr_a) + lr_a / m * on_T.sum(), tag
+
+
 @pytest.mark.parametrize("block", range(4))
 def test_csr_updates_random_shapes(ref, block):
     """Randomised shapes for the CSR Boss step and Assistant update: d from 37 to 1,200,000
@@ -535,70 +602,22 @@ def test_csr_updates_random_shapes(ref, block):
     master = rng(7000 + block)
     for case in range(6):
         r = rng(int(master.integers(1 << 30)))
-        d = int(r.choice([37, 600, 4096, 5000, 8192, 8193, 20000, 70000, 300000, 1 << 20, 1_200_000]))
+        d = int(r.choice([37, 600, 3072, 4096, 5000, 8192, 8193, 20000, 70000, 300000, 1 << 20, 1_200_000]))
         n = int(r.choice([1, 7, 300, 5000, 40000]))
         kind = r.choice(["uniform", "zipf", "hot_tail"])
         lo, hi = (1, 12) if r.random() < 0.5 else (30, 200)
         n = min(n, 3_000_000 // hi)
-        lens = r.integers(lo, hi + 1, size=n)
-        if r.random() < 0.2 and n > 1:
-            lens[r.integers(1, n, size=max(1, n // 10))] = 0  # empty rows
-        rowptr = np.zeros(n + 1, dtype=np.int64)
-        np.cumsum(lens, out=rowptr[1:])
-        nnz = int(rowptr[-1])
-        if kind == "uniform":
-            col = r.integers(0, d, size=nnz)
-        elif kind == "zipf":
-            col = np.minimum(r.pareto(1.1, size=nnz).astype(np.int64), d - 1)
-        else:  # a few very hot columns at the end of the range
-            col = np.where(r.random(nnz) < 0.5, d - 1 - r.integers(0, min(3, d), size=nnz),
-                           r.integers(0, d, size=nnz))
-        col = col.astype(np.int32)
-        val = None if r.random() < 0.3 else r.standard_normal(nnz).astype(np.float32)
-        y = np.where(r.random(n) < 0.5, -1.0, 1.0).astype(np.float32)
-        w0 = (0.3 * r.standard_normal(d)).astype(np.float32)
-        phi0 = (0.3 * r.standard_normal(d)).astype(np.float32)
-        m = int(r.integers(1, n + 1))
-        rows = r.permutation(n)[:m].astype(np.int32)
-        tag = f"d={d} n={n} m={m} nnz={nnz} {kind}"
-        Fh = ref.Features.csr(rowptr, col, val, d)
-        F = csr_features(rowptr, col, val, d)
-        ws = api.Workspace(m, d)
-        vv = np.ones(nnz) if val is None else val.astype(np.float64)
-        S = sp.csr_matrix((vv, col, rowptr), shape=(n, d))
-        Sa = sp.csr_matrix((np.abs(vv), col, rowptr), shape=(n, d))
-        lam, lr, T, lr_a, b0 = 1e-3, 0.7, 0.4, 0.5, 0.1
-        w_ref, loss_ref = ref.svm_sgd_step(Fh, y, rows, m, w0, lam, lr)
-        dots = (S[rows] @ w0.astype(np.float64)) * y[rows]
-        Sdot = Sa[rows] @ np.abs(w0.astype(np.float64))
-        kink = np.abs(dots - 1) <= RTOL * Sdot
-        w = dev(w0)
-        loss = torch.zeros(m, device="cuda")
-        api.svm_sgd_step(F, dev(y), dev(rows), scalar_dev(m, torch.int32), m, w, lam, lr, 0.0, loss, ws)
-        assert_close_scaled(host(loss), loss_ref, Sdot, "loss " + tag, atol=1e-6)
-        absx_w = np.asarray(Sa[rows[dots < 1]].sum(axis=0)).ravel()
-        akink = np.asarray(Sa[rows[kink]].sum(axis=0)).ravel()
-        assert_close_scaled(host(w), w_ref, np.abs(w0.astype(np.float64)) + lr / m * absx_w, "w " + tag,
-                            atol=lr / m * akink)
-        phi_ref, b_ref = ref.assistant_update(Fh, rows, m, loss_ref, T, phi0, b0, lr_a)
-        phi, b = dev(phi0), scalar_dev(b0)
-        api.assistant_update(F, dev(rows), scalar_dev(m, torch.int32), m, dev(loss_ref),
-                             scalar_dev(T), phi, b, lr_a, 0.0, ws)
-        absx = np.asarray(Sa[rows].sum(axis=0)).ravel()
-        assert_close_scaled(host(phi), phi_ref, np.abs(phi0.astype(np.float64)) + lr_a / m * absx,
-                            "phi " + tag)
-        assert abs(float(host(b)[0]) - b_ref) <= RTOL * (abs(b0) + lr_a), tag
-        # both updates in one pass over the rows (labels from the kernel's own losses: a row
-        # whose loss sits within rounding of T may take either label)
-        w, phi, b = dev(w0), dev(phi0), scalar_dev(b0)
-        Tt = scalar_dev(T)
-        cfg = api.step_config(0.0, lam, lr, lr_a, 0.0, 1, 0, Tt)
-        api.boss_assistant_step(F, dev(y), dev(rows), scalar_dev(m, torch.int32), m, w, phi, b, cfg,
-                                loss, ws)
-        assert_close_scaled(host(w), w_ref, np.abs(w0.astype(np.float64)) + lr / m * absx_w,
-                            "w (one pass) " + tag, atol=lr / m * akink)
-        on_T = np.abs(loss_ref.astype(np.float64) - T) <= RTOL * Sdot
-        a_T = np.asarray(Sa[rows[on_T]].sum(axis=0)).ravel()
-        assert_close_scaled(host(phi), phi_ref, np.abs(phi0.astype(np.float64)) + lr_a / m * absx,
-                            "phi (one pass) " + tag, atol=lr_a / m * a_T)
-        assert abs(float(host(b)[0]) - b_ref) <= RTOL * (abs(b0) + lr_a) + lr_a / m * on_T.sum(), tag
+        _check_csr_updates(ref, r, d, n, kind, lo, hi, r.random() >= 0.3)
+
+
+@pytest.mark.parametrize("d", [3073, 3075, 3079, 3072 + 1021, 8193, 8195, 8192 + 1022,
+                               3072 + (1 << 18), 3072 + (1 << 18) + 5, 8192 + (1 << 18), 8192 + (1 << 18) + 6])
+def test_csr_updates_at_the_edges_of_the_column_bins(ref, d):
+    """Feature counts just past the per-block table (3072 columns when both vectors are
+    updated, 8192 with one): one, three, seven columns for the bins, a count that is no
+    multiple of four (the owners fold four neighbours at a time and finish the model's last
+    columns singly), fewer groups than bins, and both sides of the count at which the bins
+    change from groups of 4 to groups of 16 columns.  Hot columns at the end of the range."""
+    r = rng(900 + d % 1000)
+    _check_csr_updates(ref, r, d, 2000, "hot_tail", 20, 60, True)
+    _check_csr_updates(ref, r, d, 300, "uniform", 1, 12, False)
