@@ -526,9 +526,16 @@ def test_csr_fused_step_more_columns_than_the_bins_cover(ref):
                         "phi")
 
 
-def _check_csr_updates(ref, r, d, n, kind, lo, hi, with_val):
+def _check_csr_updates(ref, r, d, n, kind, lo, hi, with_val, misalign=False):
     """Boss step, Assistant update and both in one pass on random CSR rows of `lo` to `hi`
-    entries against the oracle (columns uniform, Zipf-like or hot at the end of the range)."""
+    entries against the oracle (columns uniform, Zipf-like or hot at the end of the range).
+    misalign: the model vectors start 4 bytes past a 16-byte boundary."""
+    def model(a):  # device copy of a model vector
+        if not misalign:
+            return dev(a)
+        t = dev(np.concatenate([np.zeros(1, np.float32), a]))[1:]
+        assert t.data_ptr() % 16 == 4
+        return t
     lens = r.integers(lo, hi + 1, size=n)
     if r.random() < 0.2 and n > 1:
         lens[r.integers(1, n, size=max(1, n // 10))] = 0  # empty rows
@@ -561,7 +568,7 @@ def _check_csr_updates(ref, r, d, n, kind, lo, hi, with_val):
     dots = (S[rows] @ w0.astype(np.float64)) * y[rows]
     Sdot = Sa[rows] @ np.abs(w0.astype(np.float64))
     kink = np.abs(dots - 1) <= RTOL * Sdot
-    w = dev(w0)
+    w = model(w0)
     loss = torch.zeros(m, device="cuda")
     api.svm_sgd_step(F, dev(y), dev(rows), scalar_dev(m, torch.int32), m, w, lam, lr, 0.0, loss, ws)
     assert_close_scaled(host(loss), loss_ref, Sdot, "loss " + tag, atol=1e-6)
@@ -570,7 +577,7 @@ def _check_csr_updates(ref, r, d, n, kind, lo, hi, with_val):
     assert_close_scaled(host(w), w_ref, np.abs(w0.astype(np.float64)) + lr / m * absx_w, "w " + tag,
                         atol=lr / m * akink)
     phi_ref, b_ref = ref.assistant_update(Fh, rows, m, loss_ref, T, phi0, b0, lr_a)
-    phi, b = dev(phi0), scalar_dev(b0)
+    phi, b = model(phi0), scalar_dev(b0)
     api.assistant_update(F, dev(rows), scalar_dev(m, torch.int32), m, dev(loss_ref),
                          scalar_dev(T), phi, b, lr_a, 0.0, ws)
     absx = np.asarray(Sa[rows].sum(axis=0)).ravel()
@@ -579,7 +586,7 @@ def _check_csr_updates(ref, r, d, n, kind, lo, hi, with_val):
     assert abs(float(host(b)[0]) - b_ref) <= RTOL * (abs(b0) + lr_a), tag
     # both updates in one pass over the rows (labels from the kernel's own losses: a row
     # whose loss sits within rounding of T may take either label)
-    w, phi, b = dev(w0), dev(phi0), scalar_dev(b0)
+    w, phi, b = model(w0), model(phi0), scalar_dev(b0)
     Tt = scalar_dev(T)
     cfg = api.step_config(0.0, lam, lr, lr_a, 0.0, 1, 0, Tt)
     api.boss_assistant_step(F, dev(y), dev(rows), scalar_dev(m, torch.int32), m, w, phi, b, cfg,
@@ -608,6 +615,13 @@ def test_csr_updates_random_shapes(ref, block):
         lo, hi = (1, 12) if r.random() < 0.5 else (30, 200)
         n = min(n, 3_000_000 // hi)
         _check_csr_updates(ref, r, d, n, kind, lo, hi, r.random() >= 0.3)
+
+
+def test_csr_updates_with_model_vectors_off_16_byte_alignment(ref):
+    """The bin owners move four model columns per 128-bit access wherever the vectors start."""
+    r = rng(77)
+    _check_csr_updates(ref, r, 20001, 3000, "zipf", 20, 60, True, misalign=True)
+    _check_csr_updates(ref, r, 300000, 3000, "hot_tail", 20, 60, False, misalign=True)
 
 
 @pytest.mark.parametrize("d", [3073, 3075, 3079, 3072 + 1021, 8193, 8195, 8192 + 1022,
