@@ -92,8 +92,9 @@ const char *aa_status_string(int32_t status);
 
 /* Bytes of scratch needed by any call with pool size <= P_max and feature
  * dimension <= d_max: a few MB for the dense layouts; for CSR rows (and dense
- * rows with d > 2048) about 16 d + 768 P_max bytes (gradient accumulators and
- * the bins that sort sparse gradient terms by column, at most 2 GiB of those). */
+ * rows with d > 2048) about 24 d + 790 P_max bytes plus 16 MB (gradient
+ * accumulators, model pairs, per-block partial sums and the bins that sort sparse
+ * gradient terms by column, at most 2 GiB of those). */
 size_t aa_workspace_bytes(int32_t P_max, int32_t d_max);
 
 /* Zero the control words of a fresh workspace (one small fill kernel). */
