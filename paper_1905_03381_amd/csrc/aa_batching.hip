@@ -107,9 +107,22 @@ __global__ __launch_bounds__(256) void k_bucket_counts(const BucketArgs a) {
   const int m = min(max(*a.m_dev, 0), a.m_max);
   if (threadIdx.x < kMaxBuckets) hist[threadIdx.x] = 0;
   __syncthreads();
-  const int r0 = blockIdx.x * kBucketTile;
-  for (int r = r0 + threadIdx.x; r < min(m, r0 + kBucketTile); r += 256)
-    atomicAdd(&hist[bucket_of(a.len_s[r], a.len_t[r], a.width, a.n_buckets)], 1);
+  // all sixteen loads of a thread first, none under a condition of its own (a row past the
+  // end reads the last kept row instead and is not counted): one memory round trip, not eight
+  const int r0 = blockIdx.x * kBucketTile, last = m - 1;
+  if (m > 0) {
+    int ls[kBucketTile / 256], lt[kBucketTile / 256];
+#pragma unroll
+    for (int q = 0; q < kBucketTile / 256; ++q) {
+      const int r = min(r0 + q * 256 + (int)threadIdx.x, last);
+      ls[q] = a.len_s[r];
+      lt[q] = a.len_t[r];
+    }
+#pragma unroll
+    for (int q = 0; q < kBucketTile / 256; ++q)
+      if (r0 + q * 256 + (int)threadIdx.x < m)
+        atomicAdd(&hist[bucket_of(ls[q], lt[q], a.width, a.n_buckets)], 1);
+  }
   __syncthreads();
   if ((int)threadIdx.x < a.n_buckets) a.tile_base[blockIdx.x * a.n_buckets + threadIdx.x] = hist[threadIdx.x];
 }
@@ -171,50 +184,65 @@ __global__ __launch_bounds__(1024) void k_bucket_scan(const BucketArgs a, int nt
 
 __global__ __launch_bounds__(256) void k_bucket_scatter(const BucketArgs a, int ntiles_max) {
   __shared__ int wave_tot[4][kMaxBuckets];
-  __shared__ int wave_run[4][kMaxBuckets];
   const int m = min(max(*a.m_dev, 0), a.m_max);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nb = a.n_buckets;
   const int seg = blockIdx.x * kBucketTile + wave * (kBucketTile / 4);
+  if (m <= 0) return;  // (the whole block: nothing is kept)
   int bk[8];
+  {  // (loads first and without conditions of their own, as in k_bucket_counts)
+    int ls[8], lt[8];
+    const int last = m - 1;
 #pragma unroll
-  for (int r = 0; r < 8; ++r) {
-    const int row = seg + r * kWave + lane;
-    bk[r] = row < m ? bucket_of(a.len_s[row], a.len_t[row], a.width, nb) : -1;
-  }
-  // totals of this wave per bucket
-  for (int b = 0; b < nb; ++b) {
-    int tot = 0;
+    for (int r = 0; r < 8; ++r) {
+      const int row = min(seg + r * kWave + lane, last);
+      ls[r] = a.len_s[row];
+      lt[r] = a.len_t[row];
+    }
 #pragma unroll
-    for (int r = 0; r < 8; ++r) tot += __popcll(__ballot(bk[r] == b));
-    if (lane == 0) wave_tot[wave][b] = tot;
+    for (int r = 0; r < 8; ++r)
+      bk[r] = seg + r * kWave + lane < m ? bucket_of(ls[r], lt[r], a.width, nb) : -1;
   }
-  __syncthreads();
-  if (lane < nb) {
-    int base = a.tile_base[blockIdx.x * nb + lane];
-    for (int w = 0; w < wave; ++w) base += wave_tot[w][lane];
-    wave_run[wave][lane] = base;
-  }
-  __builtin_amdgcn_wave_barrier();
+  // Lane b keeps what belongs to bucket b (there are at most 32): the wave's count, then its
+  // running position, the bucket's start, first batch and batch size.  A round of 64 rows is
+  // taken bucket by bucket over the buckets that occur in it (the leader lane's, then the
+  // next one still open), not over all of them.
+  auto for_each_bucket = [&](int bucket, auto &&body) __attribute__((always_inline)) {
+    unsigned long long todo = __ballot(bucket >= 0);
+    while (todo != 0ull) {
+      const int b = __shfl(bucket, __ffsll((long long)todo) - 1, kWave);
+      const unsigned long long mask = __ballot(bucket == b);
+      body(b, mask);
+      todo &= ~mask;
+    }
+  };
+  int mine = 0;
+#pragma unroll
+  for (int r = 0; r < 8; ++r)
+    for_each_bucket(bk[r], [&](int b, unsigned long long mask) {
+      if (lane == b) mine += __popcll(mask);
+    });
+  if (lane < nb) wave_tot[wave][lane] = mine;
   const int *tail = a.tile_base + (size_t)ntiles_max * nb;
+  const int lb = min(lane, nb - 1);
+  int run = a.tile_base[blockIdx.x * nb + lb];  // where this tile's share of bucket `lane` begins
+  const int first = tail[lb], first_batch = tail[nb + lb];
+  const int cap = max(1, a.token_budget / (2 * a.width * (lb + 1)));
+  __syncthreads();
+  for (int w = 0; w < wave; ++w) run += wave_tot[w][lb];
 #pragma unroll
-  for (int r = 0; r < 8; ++r) {
-    for (int b = 0; b < nb; ++b) {
-      const unsigned long long mask = __ballot(bk[r] == b);
-      if (mask == 0) continue;
-      const int base = wave_run[wave][b];
+  for (int r = 0; r < 8; ++r)
+    for_each_bucket(bk[r], [&](int b, unsigned long long mask) {
+      const int base = __shfl(run, b, kWave), b_first = __shfl(first, b, kWave);
+      const int b_batch = __shfl(first_batch, b, kWave), b_cap = __shfl(cap, b, kWave);
       if (bk[r] == b) {
         const int pos = base + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
                                                          __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-        const int cap = max(1, a.token_budget / (2 * a.width * (b + 1)));
         a.order[pos] = seg + r * kWave + lane;
-        a.batch_of[pos] = tail[nb + b] + (pos - tail[b]) / cap;
+        a.batch_of[pos] = b_batch + (pos - b_first) / b_cap;
       }
-      __builtin_amdgcn_wave_barrier();
-      if (lane == 0) wave_run[wave][b] = base + __popcll(mask);
-      __builtin_amdgcn_wave_barrier();
-    }
-  }
+      if (lane == b) run += __popcll(mask);
+    });
 }
 
 }  // namespace
