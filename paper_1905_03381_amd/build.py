@@ -8,7 +8,9 @@ Two measurement artefacts are built beside the library (python -m paper_1905_033
 phase_trace.py), and bare_read_probe, a stand-alone program that times kernels which only read
 the rows of a pool (the reference the row passes are measured against).
 """
+import json
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -22,7 +24,7 @@ PROBE = os.path.join(HERE, "bare_read_probe")
 SOURCES = ["aa_api.hip", "aa_batching.hip", "aa_dense.hip", "aa_general.hip", "aa_select.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wall", "-Wno-unused-function"]
+         "-Wall", "-Wno-unused-function", "-Rpass-analysis=kernel-resource-usage"]
 
 
 def _hipcc():
@@ -32,11 +34,54 @@ def _hipcc():
     return "hipcc"
 
 
+def _without_remarks(text):
+    """Compiler output without the resource-usage remarks (each a remark line, and for the
+    first of a kernel two lines of source context)."""
+    keep, skip = [], 0
+    for line in text.splitlines():
+        if "-Rpass-analysis=kernel-resource-usage" in line:
+            skip = 2 if "Function Name:" in line else 0
+            continue
+        if skip > 0 and re.match(r"\s*(\d+ \||\|)", line):
+            skip -= 1
+            continue
+        skip = 0
+        keep.append(line)
+    return keep
+
+
+def kernel_resources(tag=""):
+    """Resource table of the last build of the library: {kernel symbol: {...}} over all sources."""
+    out = {}
+    for src in SOURCES:
+        path = os.path.join(OBJ, tag + src.replace(".hip", ".o")) + ".resources.json"
+        with open(path) as f:
+            out.update(json.load(f))
+    return out
+
+
 def _stale(target, deps):
     if not os.path.exists(target):
         return True
     t = os.path.getmtime(target)
     return any(os.path.getmtime(d) > t for d in deps)
+
+
+def _resource_remarks(text):
+    """{kernel symbol: {"vgprs", "scratch", "lds", "occupancy"}} from the compiler's
+    kernel-resource-usage remarks (printed per kernel while it compiles)."""
+    out, cur = {}, None
+    keys = {"VGPRs": "vgprs", "ScratchSize [bytes/lane]": "scratch", "LDS Size [bytes/block]": "lds",
+            "Occupancy [waves/SIMD]": "occupancy"}
+    for line in text.splitlines():
+        m = re.search(r"remark:\s+Function Name: (\S+)", line)
+        if m:
+            cur = out.setdefault(m.group(1), {})
+            continue
+        m = re.search(r"remark:\s+([A-Za-z /\[\]]+): (\d+) \[-Rpass-analysis", line)
+        if m and cur is not None and m.group(1).strip() in keys:
+            cur[keys[m.group(1).strip()]] = int(m.group(2))
+    return out
 
 
 def build(force=True, verbose=False, extra_flags=(), lib=LIB, tag=""):
@@ -53,10 +98,14 @@ def build(force=True, verbose=False, extra_flags=(), lib=LIB, tag=""):
             if verbose:
                 print(" ".join(cmd), flush=True)
             r = subprocess.run(cmd, capture_output=True, text=True)
-            msgs = [l for l in (r.stdout + r.stderr).splitlines()
-                    if "packed-fp32-ops" not in l and l.strip()]
+            text = r.stdout + r.stderr
             if r.returncode != 0:
+                msgs = [l for l in text.splitlines() if "packed-fp32-ops" not in l and l.strip()]
                 raise RuntimeError(f"hipcc failed on {src}:\n" + "\n".join(msgs))
+            # registers, scratch and LDS of every kernel, as the compiler reports them
+            with open(o + ".resources.json", "w") as f:
+                json.dump(_resource_remarks(text), f, indent=1, sort_keys=True)
+            msgs = [l for l in _without_remarks(text) if "packed-fp32-ops" not in l and l.strip()]
             if verbose and msgs:
                 print("\n".join(msgs), flush=True)
         return o

@@ -239,7 +239,7 @@ hipError_t run_pass(const PassSpec &s, const Ws &ws, int32_t *nblk_out, hipStrea
   if ((s.mode & (kSvm | kAssist)) && !s.ws_ready) {
     const size_t clear = general_clear_floats(s.F->d);
     const bool both = (s.mode & kSvm) && (s.mode & kAssist);
-    const int32_t head = general_head_columns(s.F->d, 2);
+    const int32_t head = general_head_columns(s.F->d, 2, csr);
     float2 *pairs = reinterpret_cast<float2 *>(ws.grad + general_pairs_offset(s.F->d));
     hipError_t e = (both && s.F->d > head)
                        ? launch_prepare_general(acc, clear, s.w, s.phi, pairs, head, s.F->d, st)
@@ -277,7 +277,7 @@ hipError_t run_pass(const PassSpec &s, const Ws &ws, int32_t *nblk_out, hipStrea
   a.acc_used = reinterpret_cast<int32_t *>(acc) + 16 + 2 * kMaxBins;
   a.acc_p = a.acc_w + s.F->d;
   a.part = reinterpret_cast<float *>(ws.grad + general_part_offset(s.F->d));
-  a.head = general_head_columns(s.F->d, nvec);
+  a.head = general_head_columns(s.F->d, nvec, csr);
   a.wp = (nvec == 2 && s.F->d > a.head)
              ? reinterpret_cast<const float2 *>(ws.grad + general_pairs_offset(s.F->d))
              : nullptr;
@@ -362,7 +362,7 @@ hipError_t run_update(const PassSpec &s, const UpdateSpec &u, const Ws &ws, int3
   p.acc_p = p.acc_w + s.F->d;
   p.part = reinterpret_cast<const float *>(ws.grad + general_part_offset(s.F->d));
   p.nvec = ((s.mode & kSvm) ? 1 : 0) + ((s.mode & kAssist) ? 1 : 0);
-  p.head = general_head_columns(s.F->d, p.nvec);
+  p.head = general_head_columns(s.F->d, p.nvec, s.F->layout == AA_CSR);
   p.bin_fill = reinterpret_cast<unsigned long long *>(acc + 16);
   p.bins = reinterpret_cast<const TailRecord *>(ws.grad + general_bins_offset(s.F->d));
   p.plan = general_bin_plan(s.F->d, p.head, p.nvec, s.count_max);
@@ -494,7 +494,7 @@ int32_t fused_step_impl(const aa_features *F, const float *y, const int32_t *idx
   u.l2_a = cfg->l2_a;
   u.t_upd = t_upd;
   u.kept_hist = kept_hist;
-  u.keep_ready = ep && !fast && general_keeps_ready(F->d, hard ? 1 : 2);
+  u.keep_ready = ep && !fast && general_keeps_ready(F->d, hard ? 1 : 2, F->layout == AA_CSR);
   if (kept_pos || kept_ids || loss || kept_count) {
     CompactArgs c{};
     c.flags = s.flags;

@@ -905,8 +905,11 @@ template <int VPL, int NW, int RIF>
 hipError_t launch_step(const PassArgs &a, bool hard, int nblk, hipStream_t st, hipEvent_t e0,
                        hipEvent_t e1) {
   const dim3 grid(nblk), block(NW * 64);
+  // (the hard-threshold variant of the widest layout does not fit its registers with four
+  // rows in flight: the compiler then parks every arriving row in scratch, one load at a time)
+  constexpr int RIF_HARD = VPL == 8 ? RIF / 2 : RIF;
   if (hard)
-    launch_stamped((k_step_pass<VPL, true, NW, RIF>), grid, block, st, e0, e1, a);
+    launch_stamped((k_step_pass<VPL, true, NW, RIF_HARD>), grid, block, st, e0, e1, a);
   else
     launch_stamped((k_step_pass<VPL, false, NW, RIF>), grid, block, st, e0, e1, a);
   return hipGetLastError();

@@ -40,6 +40,9 @@ __device__ __forceinline__ float gsum(float v) {
 // `ds_add_f64` three lanes a cycle (measured, scattered addresses), and the sums come out
 // closer to exact.
 constexpr int kDirectTwoVec = 3072, kHashedTwoVec = 1024, kRecordsTwoVec = 5120;
+// (dense rows keep the older split: with the sizes above their kernels need more registers
+// than a block of 1024 threads has, and a dense row fills the table before anything else)
+constexpr int kDirectTwoVecDense = 4096, kRecordsTwoVecDense = 3072;
 constexpr int kDirectOneVec = 8192, kHashedOneVec = 2048, kRecordsOneVec = 4096;
 constexpr int kGradThreads = 1024, kPoolThreads = 256;
 constexpr int kCheckRows = 8;  // rows per wave between two looks at the record buffer (4: 2 to 4 % slower, 16: the buffer overflows)
@@ -85,13 +88,13 @@ __device__ __forceinline__ void flush_records(const GenArgs &a, int head, const 
   const int nb = a.plan.nb;
   for (int t = threadIdx.x; t < nb; t += blockDim.x) s_hist[t] = 0;
   __syncthreads();
-  int col[kPer], rank[kPer];
-  int va[kPer], vb[kPer];  // the record's second and third words
-#pragma unroll
-  for (int q = 0; q < kPer; ++q) {
+  // The q-th record of this thread: its column (-1: none) and its second and third words.
+  // (Read from LDS again after the places are known rather than kept in registers across the
+  // two barriers: only the ranks stay.)
+  auto record = [&](int q, int &wa, int &wb) __attribute__((always_inline)) {
     const int i = threadIdx.x + q * kGradThreads;
     int c = -1;
-    int wa = 0, wb = 0;
+    wa = wb = 0;
     if (q < kPerR) {
       if (i < n) {
         c = s_rc[i];
@@ -108,9 +111,13 @@ __device__ __forceinline__ void flush_records(const GenArgs &a, int head, const 
         if (v == 0.0) c = -1;
       }
     }
-    col[q] = c;
-    va[q] = wa;
-    vb[q] = wb;
+    return c;
+  };
+  int rank[kPer];
+#pragma unroll
+  for (int q = 0; q < kPer; ++q) {
+    int wa, wb;
+    const int c = record(q, wa, wb);
     rank[q] = c >= 0 ? atomicAdd(s_hist + bin_of(c, head, a.plan), 1) : 0;
   }
   __syncthreads();
@@ -124,7 +131,8 @@ __device__ __forceinline__ void flush_records(const GenArgs &a, int head, const 
   __syncthreads();
 #pragma unroll
   for (int q = 0; q < kPer; ++q) {
-    const int c = col[q];
+    int wa, wb;
+    const int c = record(q, wa, wb);
     if (c < 0) continue;
     const int bin = bin_of(c, head, a.plan);
     const int pos = s_base[bin] + rank[q];
@@ -132,14 +140,14 @@ __device__ __forceinline__ void flush_records(const GenArgs &a, int head, const 
     if (pos < a.plan.cap) {
       TailRecord r;
       r.col = c;
-      r.a = va[q];
-      r.b = vb[q];
+      r.a = wa;
+      r.b = wb;
       r.kind = kind;
       a.bins[(size_t)bin * a.plan.cap + pos] = r;
     } else if (kind == 0) {
-      add_global<SVM, ASSIST>(a, c, __int_as_float(va[q]), __int_as_float(vb[q]));
+      add_global<SVM, ASSIST>(a, c, __int_as_float(wa), __int_as_float(wb));
     } else {
-      const double v = __hiloint2double(vb[q], va[q]);
+      const double v = __hiloint2double(wb, wa);
       add_global<SVM, ASSIST>(a, c, kind == 1 ? v : 0.0, kind == 1 ? 0.0 : v);
     }
   }
@@ -158,9 +166,9 @@ __global__ __launch_bounds__(1024) void k_rows_general(const GenArgs a) {
   constexpr bool NEED_PHI = (POOL && !HARD) || ASSIST;
   constexpr int G = kWave / GL;
   constexpr int NVEC = (SVM ? 1 : 0) + (ASSIST ? 1 : 0);
-  constexpr int D = NVEC == 2 ? kDirectTwoVec : kDirectOneVec;  // slots 0..D-1: column = slot
+  constexpr int D = NVEC == 2 ? (CSR ? kDirectTwoVec : kDirectTwoVecDense) : kDirectOneVec;  // slots 0..D-1: column = slot
   constexpr int H = NVEC == 2 ? kHashedTwoVec : kHashedOneVec;  // hashed slots
-  constexpr int R = NVEC == 2 ? kRecordsTwoVec : kRecordsOneVec;  // record buffer
+  constexpr int R = NVEC == 2 ? (CSR ? kRecordsTwoVec : kRecordsTwoVecDense) : kRecordsOneVec;  // record buffer
   __shared__ double s_sum[GRAD ? NVEC * D : 1];
   __shared__ float s_model[GRAD ? NVEC * D : 1];  // the first D entries of w and / or phi
   __shared__ int s_tag[GRAD ? H : 1];
@@ -1232,12 +1240,12 @@ hipError_t launch_zero_f32(float *p, size_t count, hipStream_t st) {
   return hipGetLastError();
 }
 
-bool general_keeps_ready(int32_t d, int nvec) {
-  return general_bin_plan(d, general_head_columns(d, nvec), nvec, 1).nb > 0;
+bool general_keeps_ready(int32_t d, int nvec, bool csr) {
+  return general_bin_plan(d, general_head_columns(d, nvec, csr), nvec, 1).nb > 0;
 }
 
-int32_t general_head_columns(int32_t d, int nvec) {
-  const int direct = nvec == 2 ? kDirectTwoVec : kDirectOneVec;
+int32_t general_head_columns(int32_t d, int nvec, bool csr) {
+  const int direct = nvec == 2 ? (csr ? kDirectTwoVec : kDirectTwoVecDense) : kDirectOneVec;
   return d < direct ? d : direct;
 }
 

@@ -112,9 +112,9 @@ struct GenArgs {
 
 // Columns whose gradient sums leave a block as plain stores instead of atomics, for a pass
 // that updates nvec vectors over d columns; blocks of a gradient pass at most.
-int32_t general_head_columns(int32_t d, int nvec);
+int32_t general_head_columns(int32_t d, int nvec, bool csr);
 // Whether the update kernel can leave the workspace ready for the next pass (see ApplyArgs).
-bool general_keeps_ready(int32_t d, int nvec);
+bool general_keeps_ready(int32_t d, int nvec, bool csr);
 constexpr int kGeneralGradBlocks = 256;
 // floats ahead of the accumulators: 16 scalars, the 64-bit fill counts of the bins, then one
 // flag per bin (an even count in all: the accumulators behind it are doubles)

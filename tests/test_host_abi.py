@@ -70,3 +70,19 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(api, "LIB_PATH", "/nonexistent/libautoassist.so")
     with pytest.raises(api.AAError):
         api.lib()
+
+
+def test_no_kernel_spills_registers():
+    """The compiler's own report (written next to the objects by the build): no kernel of
+    the library uses scratch memory.  A kernel that does parks values in memory one load at
+    a time and its waves start late; on this target that has cost a factor of two."""
+    from paper_1905_03381_amd import build
+    try:
+        table = build.kernel_resources()
+    except FileNotFoundError:
+        build.build(force=True)
+        table = build.kernel_resources()
+    assert len(table) > 50, "the resource remarks were not parsed"
+    assert all("scratch" in v and "vgprs" in v for v in table.values())
+    spilled = {k: v for k, v in table.items() if v["scratch"] > 0}
+    assert not spilled, f"kernels with scratch: {spilled}"
