@@ -3,7 +3,8 @@
 hipcc cross-compiles without a GPU.  Objects go to paper_1905_03381_amd/_build/.
 
 Two measurement artefacts are built beside the library (python -m paper_1905_03381_amd.build
---measure, also built by default): libautoassist_trace.so, the same sources with
+--measure, also built by default; --resources prints the compiler's per-kernel register, scratch
+and LDS figures of the last build): libautoassist_trace.so, the same sources with
 -DAA_PHASE_TRACE (the whole-step dense pass records per-wave phase time stamps; read them with
 phase_trace.py), and bare_read_probe, a stand-alone program that times kernels which only read
 the rows of a pool (the reference the row passes are measured against).
@@ -133,7 +134,26 @@ def build_measure(force=True, verbose=False):
     return TRACE_LIB, PROBE
 
 
+def resource_table():
+    """Markdown table of what the compiler reports per kernel of the last build."""
+    table = kernel_resources()
+    names = subprocess.run(["c++filt"] + list(table), capture_output=True, text=True).stdout.splitlines()
+    if len(names) != len(table):
+        names = list(table)
+    rows = sorted(zip(names, table.values()), key=lambda t: (-t[1]["vgprs"], t[0]))
+    out = ["| kernel | VGPRs | scratch bytes/lane | LDS bytes/block | waves/SIMD |", "|---|---|---|---|---|"]
+    for name, v in rows:
+        short = name.replace("aa::(anonymous namespace)::", "").replace("(anonymous namespace)::", "")
+        short = re.sub(r"^void ", "", short)
+        short = re.sub(r"\(.*\)$", "", short)
+        out.append(f"| `{short}` | {v['vgprs']} | {v['scratch']} | {v['lds']} | {v['occupancy']} |")
+    return "\n".join(out)
+
+
 if __name__ == "__main__":
+    if "--resources" in sys.argv:  # table of the last build (build first)
+        print(resource_table())
+        sys.exit(0)
     force = "--if-stale" not in sys.argv
     print(build(force=force, verbose=True))
     if "--no-measure" not in sys.argv:
