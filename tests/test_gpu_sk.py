@@ -168,3 +168,24 @@ def test_sk_epoch_matches_chained_oracle_steps(ref, ws):
                                 lam=lam, lr0=lr0, lr_a=0.0, T=T, ws=ws, hard=True)
     assert len(counts) == n // P and 0 < min(counts) and max(counts) < P
     assert state[3] == n // P
+
+
+def test_sk_epoch_on_csr_rows(ref):
+    """aa_sk_epoch over CSR rows (general kernels, one updated vector): every step against the
+    oracle's step from the GPU's previous state, then the epoch in one call -- where from the
+    second step on the update kernel of the step before has left the workspace ready and no
+    launch clears it -- bit-identical to the step-wise run, twice."""
+    from stepwise import check_epoch, run_whole
+    rowptr, col, val, y, _ = synth.sparse_svm(n=12_000, d=1 << 16, mean_nnz=60, threads=4)
+    d, n, P = 1 << 16, 9000, 2048
+    perm = rng(31).permutation(rowptr.size - 1)[:n].astype(np.int32)
+    Fh = ref.Features.csr(rowptr, col, val, d)
+    F = csr_features(rowptr, col, val, d)
+    ws = api.Workspace(P, d)
+    w0 = (0.5 * rng(32).standard_normal(d)).astype(np.float32)
+    args = dict(gamma=0.0, seed=0, step0=0, lam=1e-3, lr0=2.0, lr_a=0.0, T=0.6, ws=ws, hard=True)
+    counts, state = check_epoch(ref, Fh, F, y, perm, n, P, w0, None, 0.0, **args)
+    assert len(counts) == 5 and all(0 < m < P for m in counts) and state[3] == 5
+    for _ in range(2):
+        hist, _, _, again = run_whole(F, y, perm, n, P, w0, None, 0.0, **args)
+        assert hist == counts and np.array_equal(again[0], state[0])
