@@ -572,6 +572,25 @@ def test_train_epoch_matches_oracle_driver(ref, ws):
     assert 0 < min(counts2[:-1]) and max(counts2) < 256
 
 
+@pytest.mark.parametrize("d", [130, 4137])
+def test_train_epoch_on_general_dense_rows(ref, d):
+    """aa_train_epoch over dense rows that the register kernels do not take (d = 130; d = 4137:
+    more columns than the per-block table, so the last ones go through the column bins, and no
+    multiple of four): every step against the oracle step from the GPU's previous state, then
+    the epoch in one call bit for bit -- there the update kernel of a step leaves the workspace
+    ready for the next pass (d = 4137)."""
+    from stepwise import check_epoch
+    n, P = 1500, 256
+    X, y = make_dense(n, d, 11, unit=True)
+    perm = rng(12).permutation(n).astype(np.int32)
+    Fh, F = ref.Features.dense(X), dense_features(X)
+    ws = api.Workspace(P, d)
+    zeros = np.zeros(d, np.float32)
+    counts, state = check_epoch(ref, Fh, F, y, perm, n, P, zeros, zeros, 0.0, gamma=0.2, seed=5,
+                                step0=0, lam=1e-4, lr0=0.5, lr_a=0.2, T=0.0, ws=ws)
+    assert len(counts) == 6 and all(0 < m <= P for m in counts)
+
+
 def test_argument_errors(ws):
     X, y = make_dense(10, 8, 1)
     F = dense_features(X)
